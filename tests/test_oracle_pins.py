@@ -1,0 +1,411 @@
+"""Pins for the fp64 oracle: closed forms, invariants, library reductions, brute force.
+
+None of these tests re-types the oracle's own loop.  Each compares it with
+something fixed by the mathematics of the layer definition (the selective SSM
+recurrence h_t = exp(delta_t A) h_{t-1} + delta_t B_t x_t, y_t = C_t h_t + D x_t,
+gated by silu(z), delta = softplus(dt + dt_bias); depthwise causal conv1d) or by
+the paper (Sec. 4.1: a child node copies its parent's state; batch size at draft
+position i is N_1 x ... x N_i; the next token depends only on the current state).
+"""
+import os
+
+import numpy as np
+import pytest
+from scipy.special import expit
+
+import oracle
+from paper_2506_01206_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rnd(seed):
+    return np.random.default_rng(seed)
+
+
+def rand_case(seed, B=2, L=7, D=3, N=4, with_h0=True):
+    r = rnd(seed)
+    c = dict(
+        x=r.standard_normal((B, L, D)), dt=0.3 * r.standard_normal((B, L, D)),
+        z=r.standard_normal((B, L, D)), Bm=r.standard_normal((B, L, N)),
+        Cm=r.standard_normal((B, L, N)), A=-r.uniform(0.2, 4.0, (D, N)),
+        Dskip=r.standard_normal(D), dt_bias=r.standard_normal(D) - 1.0,
+        h0=r.standard_normal((B, D, N)) if with_h0 else None)
+    return c
+
+
+def run_scan(c, **kw):
+    args = dict(x=c["x"], dt=c["dt"], A=c["A"], Bm=c["Bm"], Cm=c["Cm"], Dskip=c["Dskip"],
+                z=c["z"], dt_bias=c["dt_bias"], h0=c["h0"])
+    args.update(kw)
+    return oracle.scan_fwd(**args)
+
+
+# ---------------------------------------------------------------- P10: softplus, silu
+def test_softplus_matches_logaddexp():
+    # N=1, A=0, h0=0, B=C=1, D=0, x=1, no gate, L=1  =>  out = delta = softplus(dt + dt_bias)
+    v = np.concatenate([np.linspace(-40, 40, 321), [-745.0, -700.0, -100.0, 100.0, 700.0, 0.0]])
+    n = v.size
+    one = np.ones((n, 1, 1))
+    bias = np.array([0.37])
+    out, hf = oracle.scan_fwd(x=one, dt=(v - 0.37).reshape(n, 1, 1), A=np.zeros((1, 1)),
+                              Bm=one, Cm=one, dt_bias=bias, dt_softplus=True)
+    ref = np.logaddexp(0.0, (v - 0.37) + 0.37)
+    np.testing.assert_allclose(out.ravel(), ref, rtol=1e-14, atol=0)
+    np.testing.assert_allclose(hf.ravel(), ref, rtol=1e-14, atol=0)
+    # flag off: delta is dt + dt_bias itself
+    out2, _ = oracle.scan_fwd(x=one, dt=(v - 0.37).reshape(n, 1, 1), A=np.zeros((1, 1)),
+                              Bm=one, Cm=one, dt_bias=bias, dt_softplus=False)
+    np.testing.assert_allclose(out2.ravel(), (v - 0.37) + 0.37, rtol=1e-15, atol=0)
+
+
+def test_silu_gate_matches_expit():
+    # C = 0, D = 1, x = 1  =>  out = silu(z) = z * expit(z)
+    zv = np.concatenate([np.linspace(-30, 30, 241), [-700.0, 700.0]])
+    n = zv.size
+    one = np.ones((n, 1, 1))
+    out, _ = oracle.scan_fwd(x=one, dt=one, A=-np.ones((1, 2)), Bm=np.ones((n, 1, 2)),
+                             Cm=np.zeros((n, 1, 2)), Dskip=np.ones(1), z=zv.reshape(n, 1, 1))
+    np.testing.assert_allclose(out.ravel(), zv * expit(zv), rtol=1e-14, atol=1e-300)
+
+
+def test_inverse_softplus_round_trip_of_generator():
+    # the generator's dt_bias is the inverse softplus of a log-uniform dt0 in [1e-3, 0.1]
+    p = synth.layer_params(rnd(5), 512, 16, 4)
+    dt0 = np.logaddexp(0.0, p["dt_bias"].astype(np.float64))
+    assert dt0.min() > 1e-3 * 0.999 and dt0.max() < 0.1 * 1.001
+    lg = np.log(dt0)
+    assert abs(lg.mean() - 0.5 * (np.log(1e-3) + np.log(0.1))) < 0.2   # log-uniform, not uniform
+
+
+# ---------------------------------------------------------------- P1: geometric series
+@pytest.mark.parametrize("softplus", [False, True])
+def test_constant_inputs_geometric_series(softplus):
+    L, D, N = 50, 3, 5
+    r = rnd(11)
+    xc = r.standard_normal(D)
+    bc = r.standard_normal(N)
+    cc = r.standard_normal(N)
+    A = -r.uniform(0.1, 3.0, (D, N))
+    Dk = r.standard_normal(D)
+    zc = r.standard_normal(D)
+    h0 = r.standard_normal((1, D, N))
+    if softplus:
+        dtc = r.standard_normal(D)
+        bias = r.standard_normal(D)
+        delta = np.logaddexp(0.0, dtc + bias)
+    else:
+        dtc = r.uniform(0.01, 0.5, D)
+        bias = np.zeros(D)
+        delta = dtc
+    tile = lambda v, n: np.broadcast_to(v, (1, L, n)).copy()
+    out, hf = oracle.scan_fwd(x=tile(xc, D), dt=tile(dtc, D), A=A, Bm=tile(bc, N), Cm=tile(cc, N),
+                              Dskip=Dk, z=tile(zc, D), dt_bias=bias, h0=h0, dt_softplus=softplus)
+    abar = np.exp(delta[:, None] * A)                                  # (D,N)
+    t1 = np.arange(1, L + 1)[:, None, None]                            # t+1
+    pw = abar[None] ** t1                                              # (L,D,N)
+    h = pw * h0 + (delta[:, None] * bc[None, :] * xc[:, None])[None] * (1 - pw) / (1 - abar)[None]
+    y = (h * cc[None, None, :]).sum(-1) + Dk * xc
+    ref = y * (zc * expit(zc))
+    np.testing.assert_allclose(out[0], ref, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(hf[0], h[-1], rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P2: A = 0 -> cumulative sum
+def test_A_zero_reduces_to_cumsum():
+    c = rand_case(21, B=2, L=33, D=4, N=3)
+    c["A"] = np.zeros_like(c["A"])
+    out, hf = run_scan(c, z=None, Dskip=None)
+    delta = np.logaddexp(0.0, c["dt"] + c["dt_bias"])
+    inc = (delta * c["x"])[:, :, :, None] * c["Bm"][:, :, None, :]      # (B,L,D,N)
+    h = c["h0"][:, None] + np.cumsum(inc, axis=1)
+    y = np.einsum("bldn,bln->bld", h, c["Cm"])
+    np.testing.assert_allclose(out, y, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(hf, h[:, -1], rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P3: unrolled form, tiny
+def unrolled(c, softplus=True):
+    """h_t[n] = exp(A_n S_t) h0 + sum_{s<=t} exp(A_n (S_t - S_s)) delta_s B_s[n] x_s with
+    S_t = sum_{r<=t} delta_r; written as explicit sums, not as a recurrence."""
+    x, Bm, Cm, A = c["x"], c["Bm"], c["Cm"], c["A"]
+    Bn, L, D = x.shape
+    N = A.shape[1]
+    v = c["dt"] + (c["dt_bias"] if c["dt_bias"] is not None else 0.0)
+    delta = np.logaddexp(0.0, v) if softplus else v
+    h0 = c["h0"] if c["h0"] is not None else np.zeros((Bn, D, N))
+    out = np.zeros((Bn, L, D))
+    hlast = np.zeros((Bn, D, N))
+    for b in range(Bn):
+        for d in range(D):
+            S = np.cumsum(delta[b, :, d])
+            for t in range(L):
+                y = 0.0
+                for n in range(N):
+                    h = np.exp(A[d, n] * S[t]) * h0[b, d, n]
+                    for s in range(t + 1):
+                        h += np.exp(A[d, n] * (S[t] - S[s])) * delta[b, s, d] * Bm[b, s, n] * x[b, s, d]
+                    y += Cm[b, t, n] * h
+                    if t == L - 1:
+                        hlast[b, d, n] = h
+                if c["Dskip"] is not None:
+                    y += c["Dskip"][d] * x[b, t, d]
+                if c["z"] is not None:
+                    y *= c["z"][b, t, d] * expit(c["z"][b, t, d])
+                out[b, t, d] = y
+    return out, hlast
+
+
+@pytest.mark.parametrize("seed,softplus", [(1, True), (2, False), (3, True)])
+def test_unrolled_brute_force(seed, softplus):
+    c = rand_case(seed, B=2, L=8, D=3, N=4, with_h0=(seed != 3))
+    if not softplus:
+        c["dt"] = np.abs(c["dt"]) + 0.05
+        c["dt_bias"] = np.abs(c["dt_bias"]) * 0.1
+    out, hf = run_scan(c, dt_softplus=softplus)
+    ro, rh = unrolled(c, softplus)
+    np.testing.assert_allclose(out, ro, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(hf, rh, rtol=1e-11, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P4: scan == repeated step
+def test_scan_equals_repeated_steps():
+    c = rand_case(31, B=3, L=19, D=5, N=4)
+    out, hf = run_scan(c)
+    h = c["h0"].copy()
+    for t in range(19):
+        h, o = oracle.state_step(h, c["x"][:, t], c["dt"][:, t], c["A"], c["Bm"][:, t], c["Cm"][:, t],
+                                 Dskip=c["Dskip"], z=c["z"][:, t], dt_bias=c["dt_bias"])
+        np.testing.assert_allclose(o, out[:, t], rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(h, hf, rtol=1e-13, atol=1e-14)
+
+
+def test_step_parent_index_reads_parent_state():
+    # a step with parent p must equal a step on the explicitly gathered states
+    r = rnd(33)
+    n_in, n_out, D, N = 4, 9, 3, 5
+    h_in = r.standard_normal((n_in, D, N))
+    parent = r.integers(0, n_in, n_out).astype(np.int32)
+    tok = dict(x=r.standard_normal((n_out, D)), dt=r.standard_normal((n_out, D)),
+               Bm=r.standard_normal((n_out, N)), Cm=r.standard_normal((n_out, N)))
+    A = -r.uniform(0.1, 2, (D, N))
+    h1, o1 = oracle.state_step(h_in, A=A, parent=parent, **tok)
+    h2, o2 = oracle.state_step(h_in[parent], A=A, parent=None, **tok)
+    assert np.array_equal(h1, h2) and np.array_equal(o1, o2)
+    # and against the one-step closed form h' = exp(delta A) h_p + delta B x ; y = C.h'
+    delta = np.logaddexp(0, tok["dt"])
+    href = np.exp(delta[:, :, None] * A[None]) * h_in[parent] + \
+        (delta * tok["x"])[:, :, None] * tok["Bm"][:, None, :]
+    np.testing.assert_allclose(h1, href, rtol=1e-14)
+    np.testing.assert_allclose(o1, np.einsum("jdn,jn->jd", href, tok["Cm"]), rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- P5: chunk carry
+@pytest.mark.parametrize("L1", [1, 5, 12])
+def test_scan_chunk_carry(L1):
+    c = rand_case(41, B=2, L=13, D=4, N=3)
+    out, hf = run_scan(c)
+    sl = lambda k, a, b: c[k][:, a:b]
+    cut = lambda a, b, h0: oracle.scan_fwd(sl("x", a, b), sl("dt", a, b), c["A"], sl("Bm", a, b),
+                                           sl("Cm", a, b), c["Dskip"], sl("z", a, b), c["dt_bias"], h0)
+    o1, h1 = cut(0, L1, c["h0"])
+    o2, h2 = cut(L1, 13, h1)
+    np.testing.assert_allclose(np.concatenate([o1, o2], 1), out, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(h2, hf, rtol=1e-13, atol=1e-14)
+
+
+@pytest.mark.parametrize("K", [2, 3, 4])
+@pytest.mark.parametrize("L1", [1, 2, 7])
+def test_conv_chunk_carry(K, L1):
+    r = rnd(43)
+    B, L, D = 2, 11, 5
+    x = r.standard_normal((B, L, D))
+    w = r.standard_normal((D, K))
+    bias = r.standard_normal(D)
+    st0 = r.standard_normal((B, D, K - 1))
+    y, st = oracle.conv1d_fwd(x, w, bias, st0)
+    y1, s1 = oracle.conv1d_fwd(x[:, :L1], w, bias, st0)
+    y2, s2 = oracle.conv1d_fwd(x[:, L1:], w, bias, s1)
+    assert np.array_equal(np.concatenate([y1, y2], 1), y)
+    assert np.array_equal(s2, st)
+
+
+# ---------------------------------------------------------------- P6: delta -> 0
+def test_delta_to_zero_leaves_state_unchanged():
+    c = rand_case(51, B=2, L=9, D=4, N=3)
+    c["dt"] = np.full_like(c["dt"], -1e4)
+    c["dt_bias"] = np.zeros_like(c["dt_bias"])
+    out, hf = run_scan(c, z=None)
+    assert np.array_equal(hf, c["h0"])                       # exactly unchanged
+    y = np.einsum("bdn,bln->bld", c["h0"], c["Cm"]) + c["Dskip"] * c["x"]
+    np.testing.assert_allclose(out, y, rtol=1e-13, atol=1e-14)
+
+
+# ---------------------------------------------------------------- P7: linearity in x
+def test_linear_in_x_from_zero_state():
+    c = rand_case(61, B=1, L=15, D=4, N=4, with_h0=False)
+    x2 = rnd(62).standard_normal(c["x"].shape)
+    a, b = 0.7, -1.9
+    o1, h1 = run_scan(c)
+    o2, h2 = run_scan(c, x=x2)
+    o3, h3 = run_scan(c, x=a * c["x"] + b * x2)
+    np.testing.assert_allclose(o3, a * o1 + b * o2, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(h3, a * h1 + b * h2, rtol=1e-11, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P8: special cases
+def test_special_cases():
+    c = rand_case(71, B=2, L=6, D=3, N=4)
+    o, _ = run_scan(c, Cm=np.zeros_like(c["Cm"]))
+    np.testing.assert_allclose(o, c["Dskip"] * c["x"] * c["z"] * expit(c["z"]), rtol=1e-13, atol=1e-15)
+    o_gate, h_gate = run_scan(c)
+    o_nogate, h_nogate = run_scan(c, z=None)
+    np.testing.assert_allclose(o_gate, o_nogate * c["z"] * expit(c["z"]), rtol=1e-13, atol=1e-15)
+    assert np.array_equal(h_gate, h_nogate)                  # the gate does not touch the state
+    o_noskip, _ = run_scan(c, z=None, Dskip=None)
+    np.testing.assert_allclose(o_nogate - o_noskip, c["Dskip"] * c["x"], rtol=1e-9, atol=1e-12)
+    o_z0, _ = run_scan(c, z=np.zeros_like(c["z"]))
+    assert np.all(o_z0 == 0)
+    o_nb, _ = run_scan(c, dt_bias=None)
+    o_zb, _ = run_scan(c, dt_bias=np.zeros_like(c["dt_bias"]))
+    assert np.array_equal(o_nb, o_zb)
+    assert not np.allclose(o_nb, o_gate)                     # dt_bias is really used
+    o_h0none, _ = run_scan(c, h0=None)
+    o_h0zero, _ = run_scan(c, h0=np.zeros_like(c["h0"]))
+    assert np.array_equal(o_h0none, o_h0zero)
+    # batches are independent and B/C are per batch row
+    ob, hb = oracle.scan_fwd(c["x"][1:], c["dt"][1:], c["A"], c["Bm"][1:], c["Cm"][1:], c["Dskip"],
+                             c["z"][1:], c["dt_bias"], c["h0"][1:])
+    assert np.array_equal(ob, o_gate[1:]) and np.array_equal(hb, h_gate[1:])
+    # empty sequence: state passes through
+    e = lambda k: c[k][:, :0]
+    oe, he = oracle.scan_fwd(e("x"), e("dt"), c["A"], e("Bm"), e("Cm"), c["Dskip"], e("z"),
+                             c["dt_bias"], c["h0"])
+    assert oe.shape == (2, 0, 3) and np.array_equal(he, c["h0"])
+
+
+# ---------------------------------------------------------------- P9: conv
+@pytest.mark.parametrize("K", [1, 2, 3, 4])
+def test_conv_matches_numpy_convolve_and_toeplitz(K):
+    r = rnd(81)
+    B, L, D = 2, 17, 4
+    x = r.standard_normal((B, L, D))
+    w = r.standard_normal((D, K))
+    bias = r.standard_normal(D)
+    y, st = oracle.conv1d_fwd(x, w, bias, None, apply_silu=False)
+    for b in range(B):
+        for d in range(D):
+            # causal correlation with taps w[d,0..K-1] on x[t-K+1..t] == convolution with reversed taps
+            ref = np.convolve(x[b, :, d], w[d, ::-1])[:L] + bias[d]
+            np.testing.assert_allclose(y[b, :, d], ref, rtol=1e-12, atol=1e-13)
+            T = np.zeros((L, L))
+            for t in range(L):
+                for k in range(K):
+                    s = t - (K - 1) + k
+                    if s >= 0:
+                        T[t, s] = w[d, k]
+            np.testing.assert_allclose(y[b, :, d], T @ x[b, :, d] + bias[d], rtol=1e-12, atol=1e-13)
+    ys, _ = oracle.conv1d_fwd(x, w, bias, None, apply_silu=True)
+    np.testing.assert_allclose(ys, y * expit(y), rtol=1e-13, atol=1e-15)
+    assert np.array_equal(st, np.transpose(x[:, L - (K - 1):, :], (0, 2, 1)).reshape(B, D, K - 1))
+
+
+def test_conv_one_hot_tap_is_a_delay_and_state_is_left_context():
+    r = rnd(83)
+    B, L, D, K = 1, 9, 2, 4
+    x = r.standard_normal((B, L, D))
+    st0 = r.standard_normal((B, D, K - 1))
+    for k in range(K):
+        w = np.zeros((D, K))
+        w[:, k] = 1.0
+        y, st = oracle.conv1d_fwd(x, w, None, st0, apply_silu=False)
+        xpad = np.concatenate([np.transpose(st0, (0, 2, 1)), x], axis=1)     # (B, K-1+L, D)
+        assert np.array_equal(y, xpad[:, k:k + L])                            # delay by K-1-k
+        assert np.array_equal(st, np.transpose(xpad[:, L:], (0, 2, 1)))
+    # no bias and no state == zero bias and zero state
+    w = r.standard_normal((D, K))
+    ya, _ = oracle.conv1d_fwd(x, w, None, None)
+    yb, _ = oracle.conv1d_fwd(x, w, np.zeros(D), np.zeros((B, D, K - 1)))
+    assert np.array_equal(ya, yb)
+
+
+@pytest.mark.parametrize("L", [0, 1, 2])
+def test_conv_shorter_than_window(L):
+    r = rnd(85)
+    B, D, K = 2, 3, 4
+    x = r.standard_normal((B, L, D))
+    st0 = r.standard_normal((B, D, K - 1))
+    w = r.standard_normal((D, K))
+    y, st = oracle.conv1d_fwd(x, w, None, st0, apply_silu=False)
+    xpad = np.concatenate([np.transpose(st0, (0, 2, 1)), x], axis=1)
+    for t in range(L):
+        np.testing.assert_allclose(y[:, t], np.einsum("bkd,dk->bd", xpad[:, t:t + K], w), rtol=1e-13)
+    assert np.array_equal(st, np.transpose(xpad[:, L:L + K - 1], (0, 2, 1)))
+
+
+# ---------------------------------------------------------------- P11, P12: fork
+def test_fork_is_fancy_indexing_bytes():
+    r = rnd(91)
+    nl, n_in, n_out, D, N, K = 3, 5, 8, 6, 4, 4
+    conv = r.integers(0, 2 ** 16, (nl, n_in, D, K - 1)).astype(np.uint16)     # bf16 bit patterns
+    ssm = r.standard_normal((nl, n_in, D, N)).astype(np.float32)
+    ssm.view(np.uint32)[0, 0, 0, 0] = 0x7FC12345                              # NaN payload survives
+    parent = r.integers(0, n_in, n_out).astype(np.int32)
+    cd, sd = oracle.state_fork(conv, ssm, parent)
+    assert cd.tobytes() == conv[:, parent].tobytes()
+    assert sd.tobytes() == ssm[:, parent].tobytes()
+    ci, si = oracle.state_fork(conv, ssm, np.arange(n_in, dtype=np.int32))
+    assert ci.tobytes() == conv.tobytes() and si.tobytes() == ssm.tobytes()
+    cb, sb = oracle.state_fork(conv, ssm, np.full(7, 2, dtype=np.int32))
+    assert all(sb[:, j].tobytes() == ssm[:, 2].tobytes() for j in range(7))
+    c_only, none = oracle.state_fork(conv, None, parent)
+    assert none is None and c_only.tobytes() == cd.tobytes()
+
+
+def read_golden_trees():
+    rows = []
+    with open(os.path.join(GOLDEN, "tree_configs.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            t, b = line.split("|")
+            rows.append((tuple(int(v) for v in t.split(",")), [int(v) for v in b.split(",")]))
+    return rows
+
+
+def test_paper_tree_shapes_and_fork_chain():
+    rows = read_golden_trees()
+    assert ((3, 2, 2, 1, 1), [3, 6, 12, 12, 12]) in rows
+    r = rnd(93)
+    D, N, K = 4, 3, 4
+    for tree, sizes in rows:
+        assert synth.tree_batch_sizes(tree) == sizes
+        parents = synth.tree_parents(tree)
+        ssm = r.standard_normal((2, 1, D, N)).astype(np.float32)          # root: one state per layer
+        conv = r.standard_normal((2, 1, D, K - 1)).astype(np.float32)
+        copies = 0
+        prev = 1
+        for n_i, b_i, par in zip(tree, sizes, parents):
+            assert par.shape == (b_i,) and par.max() == prev - 1
+            assert np.array_equal(np.bincount(par, minlength=prev), np.full(prev, n_i))
+            conv, ssm = oracle.state_fork(conv, ssm, par)
+            assert ssm.shape == (2, b_i, D, N)
+            copies += b_i
+            prev = b_i
+        assert copies == sum(sizes)
+        # nothing but copies happened: every leaf still equals the root state, siblings identical
+        assert all(ssm[:, j].tobytes() == ssm[:, 0].tobytes() for j in range(prev))
+
+
+def test_bf16_widening_is_exact():
+    r = rnd(95)
+    f = r.standard_normal(1000).astype(np.float32)
+    bits = synth.f32_to_bf16_bits(f)
+    back = synth.bf16_bits_to_f32(bits)
+    assert np.array_equal(oracle.widen(bits, bf16=True), back.astype(np.float64))
+    # round to nearest even: error at most half a bf16 ulp, and values already in bf16 survive
+    assert np.all(np.abs(back - f) <= np.abs(f) * 2.0 ** -8)
+    assert np.array_equal(synth.f32_to_bf16_bits(back), bits)
+    tie = np.array([0x3F808000, 0x3F818000], dtype=np.uint32).view(np.float32)   # exact ties
+    assert list(synth.f32_to_bf16_bits(tie)) == [0x3F80, 0x3F82]
