@@ -1,0 +1,151 @@
+/*
+ * mamba_hip.h - C ABI of the selective-SSM layer core of a Mamba drafter on
+ * AMD MI355X (gfx950).
+ *
+ * The paper drafts with a Mamba model: the context is encoded once (prefill),
+ * then tokens are generated one step at a time from a fixed-size recurrent
+ * state (Sec. 1, Sec. 3.1), and a draft tree is generated as a batch in which
+ * every child starts from a copy of its parent's state (Sec. 4.1).  The four
+ * operations below are the per-layer core of that path: causal depthwise
+ * conv1d and selective scan for the prefill, a one-step state update for all
+ * branches of the tree at once, and the state copy by parent index.
+ *
+ * Conventions common to all entry points
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *    allocates nothing, keeps no global state and never synchronizes: each call
+ *    validates its arguments on the host, enqueues kernels on `hip_stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *  - Layout is row-major and contiguous, time-major for token tensors:
+ *      x, dt, z, out, y : (batch, L, D)        I/O dtype `io`
+ *      Bm, Cm           : (batch, L, N)        I/O dtype `io`
+ *      A                : (D, N)               float32, the (negative) real
+ *                                              diagonal itself, not its log
+ *      Dskip, dt_bias   : (D)                  float32
+ *      w                : (D, K), bias : (D)   float32
+ *      h (SSM state)    : (rows, D, N)         float32
+ *      conv state       : (rows, D, K-1)       I/O dtype, oldest sample first
+ *    One B_t, C_t vector per (batch row, token) is shared by all D channels.
+ *  - All arithmetic is float32; bf16 inputs are widened exactly and outputs
+ *    rounded to nearest-even once, at the store.
+ *  - Supported ranges: N in {1..32}... see MAMBA_MAX_N; K in {1..MAMBA_MAX_K};
+ *    anything else returns MAMBA_ERR_UNSUPPORTED.  Data pointers must be
+ *    16-byte aligned (MAMBA_ERR_MISALIGNED).
+ *  - Return value: MAMBA_OK (0); a negative mamba_status_t for an argument
+ *    error, detected before any HIP call (so nothing was enqueued); a positive
+ *    value is the hipError_t of a failed launch.  A call with zero work
+ *    (L == 0, batch == 0, n_out == 0, ...) succeeds and launches nothing,
+ *    except where stated (scan with L == 0 still copies h0 to h_final).
+ */
+#ifndef MAMBA_HIP_H
+#define MAMBA_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MAMBA_F32 = 0, MAMBA_BF16 = 1 } mamba_dtype_t;
+
+typedef enum {
+    MAMBA_OK = 0,
+    MAMBA_ERR_NULL_POINTER = -1, /* a required pointer is NULL */
+    MAMBA_ERR_BAD_SHAPE = -2,    /* negative size, size overflow, n_in == 0 with work to do */
+    MAMBA_ERR_UNSUPPORTED = -3,  /* dtype, N or K outside the compiled range */
+    MAMBA_ERR_MISALIGNED = -4,   /* a data pointer is not 16-byte aligned */
+    MAMBA_ERR_WORKSPACE = -5,    /* workspace NULL or smaller than the query says */
+    MAMBA_ERR_ALIAS = -6         /* output overlaps an input where that is not allowed */
+} mamba_status_t;
+
+#define MAMBA_MAX_N 64 /* N must be a multiple of 4 in [4, 64], or 1, 2 */
+#define MAMBA_MAX_K 4
+
+/* Human-readable text for a status returned by any function here (static storage). */
+const char *mamba_status_string(int status);
+
+/*
+ * Causal depthwise conv1d over time (first stage of the layer, applied to the
+ * context during encoding and to one token per branch during drafting):
+ *   y[b,t,d] = act( bias[d] + sum_{k=0..K-1} w[d,k] * xpad[b,t+k,d] ),
+ *   xpad = [ conv_state_in[b,d,0..K-2] ; x[b,0..L-1,d] ]   (zeros when NULL),
+ *   act  = SiLU if apply_silu else identity,
+ *   conv_state_out[b,d,k] = xpad[b,L+k,d], k = 0..K-2  (the last K-1 samples).
+ * With L = 1 this is the decode-time window shift.
+ *   x, y: (batch,L,D) io.  w: (D,K) f32.  bias: (D) f32 or NULL (zero).
+ *   conv_state_in: (batch,D,K-1) io or NULL.  conv_state_out: same shape or NULL.
+ * conv_state_out may be the same buffer as conv_state_in (in-place window
+ * update); then time is not split across workgroups, which is meant for short L.
+ * y must not overlap x.  Partial overlap of the two states is an error.
+ */
+int mamba_conv1d_fwd(const void *x, const float *w, const float *bias,
+                     const void *conv_state_in, void *y, void *conv_state_out,
+                     int64_t batch, int64_t L, int64_t D, int K, int apply_silu,
+                     mamba_dtype_t io, void *hip_stream);
+
+/*
+ * Selective scan over L tokens (context encoding; Sec. 3.1 "encoding"):
+ *   delta = softplus(dt + dt_bias) if dt_softplus else dt + dt_bias
+ *   h_t[d,n] = exp(delta_t[d] * A[d,n]) * h_{t-1}[d,n] + delta_t[d] * Bm_t[n] * x_t[d]
+ *   y_t[d]   = sum_n Cm_t[n] * h_t[d,n] + Dskip[d] * x_t[d]
+ *   out_t[d] = y_t[d] * silu(z_t[d])            (no gate when z is NULL)
+ *   h_{-1} = h0 (zeros when NULL);  h_final = h_{L-1}.
+ * Nullable: Dskip (no skip term), z, dt_bias (zero), h0, h_final (not written).
+ * Long sequences are cut into time chunks of `chunk_len` tokens that run in
+ * parallel, with the chunk-boundary state carried through `workspace`; the
+ * result does not depend on the chunking beyond float32 rounding order.
+ * chunk_len = 0 lets the library choose; chunk_len >= L means one chunk.
+ * mamba_scan_workspace_bytes gives the bytes needed for the same
+ * (batch, L, D, N, chunk_len); workspace may be NULL when that is 0.
+ * h_final may alias h0.  out must not overlap any input.
+ */
+size_t mamba_scan_workspace_bytes(int64_t batch, int64_t L, int64_t D, int64_t N,
+                                  int64_t chunk_len);
+int mamba_scan_fwd(const void *x, const void *dt, const float *A, const void *Bm,
+                   const void *Cm, const float *Dskip, const void *z,
+                   const float *dt_bias, const float *h0, void *out, float *h_final,
+                   void *workspace, size_t workspace_bytes, int64_t batch, int64_t L,
+                   int64_t D, int64_t N, int64_t chunk_len, int dt_softplus,
+                   mamba_dtype_t io, void *hip_stream);
+
+/*
+ * One recurrence step for all n_out live branches of a draft tree at once
+ * (Sec. 4.1: batch generation with batch size B_i at draft position i; a child
+ * continues from its parent's state).  Same equations as the scan with L = 1:
+ *   p = parent_idx[j] (j itself when parent_idx is NULL, which needs n_in == n_out)
+ *   h_out[j,d,n] = exp(delta_j[d]*A[d,n]) * h_in[p,d,n] + delta_j[d]*Bm_j[n]*x_j[d]
+ *   out[j,d] = (sum_n Cm_j[n]*h_out[j,d,n] + Dskip[d]*x_j[d]) * silu(z_j[d])
+ *   h_in: (n_in,D,N) f32.  h_out: (n_out,D,N) f32.  parent_idx: device int32[n_out],
+ *   values in [0,n_in).  x, dt, z, out: (n_out,D) io.  Bm, Cm: (n_out,N) io.
+ * With parent_idx the state copy is fused into the step: the result is bit-identical
+ * to mamba_state_fork followed by a step without parent_idx.  A parent index outside
+ * [0,n_in) never reads out of bounds: that branch's state and output become NaN.
+ * h_out == h_in is allowed only when parent_idx is NULL (in-place sequential decode).
+ */
+int mamba_state_step(float *h_out, const float *h_in, const int32_t *parent_idx,
+                     const void *x, const void *dt, const float *A, const void *Bm,
+                     const void *Cm, const float *Dskip, const void *z,
+                     const float *dt_bias, void *out, int64_t n_out, int64_t n_in,
+                     int64_t D, int64_t N, int dt_softplus, mamba_dtype_t io,
+                     void *hip_stream);
+
+/*
+ * State copy by parent index for all layers at once (Sec. 4.1: creating the children
+ * of a node "only requires copying the current state"; destination buffers are the
+ * pre-allocated caches of the next batch size, hence out of place):
+ *   conv_dst[l,j,:,:] = conv_src[l,parent_idx[j],:,:]   (n_layers,n_out,D,K-1) <- (n_layers,n_in,D,K-1)
+ *   ssm_dst [l,j,:,:] = ssm_src [l,parent_idx[j],:,:]   (n_layers,n_out,D,N)   <- (n_layers,n_in,D,N)
+ * A byte copy: bit-exact, NaN payloads included.  Either the conv pair or the ssm pair
+ * may be NULL (both pointers) to copy only the other.  Source and destination must not
+ * overlap (MAMBA_ERR_ALIAS).  A parent index outside [0,n_in) copies nothing for that
+ * branch and fills its destination rows with 0xFF bytes (NaN).
+ */
+int mamba_state_fork(void *conv_dst, const void *conv_src, float *ssm_dst,
+                     const float *ssm_src, const int32_t *parent_idx, int64_t n_layers,
+                     int64_t n_out, int64_t n_in, int64_t D, int64_t N, int K,
+                     mamba_dtype_t conv_dtype, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAMBA_HIP_H */

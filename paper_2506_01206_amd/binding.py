@@ -1,0 +1,187 @@
+"""ctypes binding of libmamba_hip.so (the C ABI in include/mamba_hip.h).
+
+Argument marshalling only: shapes and dtypes are read off the tensors, output
+tensors are allocated with torch when the caller passes none, pointers and the
+current HIP stream are handed to the C function, and a non-zero status raises.
+Every step of the computation runs in the library's kernels.  There is no
+fallback: if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmamba_hip.so")
+
+MAMBA_F32 = 0
+MAMBA_BF16 = 1
+STATUS = dict(OK=0, NULL_POINTER=-1, BAD_SHAPE=-2, UNSUPPORTED=-3, MISALIGNED=-4, WORKSPACE=-5,
+              ALIAS=-6)
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libmamba_hip.so is missing: build it with `python -m paper_2506_01206_amd.build` "
+        "(there is no CPU or PyTorch fallback for the kernels)")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i64, _int, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+lib.mamba_status_string.argtypes = [_int]
+lib.mamba_status_string.restype = ctypes.c_char_p
+lib.mamba_conv1d_fwd.argtypes = [_vp] * 6 + [_i64, _i64, _i64, _int, _int, _int, _vp]
+lib.mamba_conv1d_fwd.restype = _int
+lib.mamba_scan_workspace_bytes.argtypes = [_i64] * 5
+lib.mamba_scan_workspace_bytes.restype = _sz
+lib.mamba_scan_fwd.argtypes = [_vp] * 12 + [_sz] + [_i64] * 5 + [_int, _int, _vp]
+lib.mamba_scan_fwd.restype = _int
+lib.mamba_state_step.argtypes = [_vp] * 12 + [_i64] * 4 + [_int, _int, _vp]
+lib.mamba_state_step.restype = _int
+lib.mamba_state_fork.argtypes = [_vp] * 5 + [_i64] * 5 + [_int, _int, _vp]
+lib.mamba_state_fork.restype = _int
+
+EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
+           "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork")
+
+
+class MambaError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__("%s failed with status %d: %s" % (fn, status, mamba_status_string(status)))
+
+
+def mamba_status_string(status: int) -> str:
+    return lib.mamba_status_string(int(status)).decode()
+
+
+def _check(fn, status):
+    if status != 0:
+        raise MambaError(fn, status)
+
+
+def _io_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MAMBA_F32
+    if t.dtype == torch.bfloat16:
+        return MAMBA_BF16
+    raise TypeError("I/O tensors must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _ptr(t, dtype=None, shape=None, name="tensor"):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL), with dtype/shape checks."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return t.data_ptr() if t.numel() > 0 else None
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def mamba_conv1d_fwd(x, w, bias=None, conv_state_in=None, y=None, conv_state_out=None,
+                     apply_silu=True, want_state=True, stream=None):
+    """x (B,L,D) f32|bf16, w (D,K) f32 -> y (B,L,D), conv_state_out (B,D,K-1)."""
+    B, L, D = x.shape
+    K = w.shape[1]
+    io = _io_code(x)
+    if y is None:
+        y = torch.empty_like(x)
+    if conv_state_out is None and want_state:
+        conv_state_out = torch.empty((B, D, K - 1), dtype=x.dtype, device=x.device)
+    st = lib.mamba_conv1d_fwd(
+        _ptr(x, name="x"), _ptr(w, torch.float32, (D, K), "w"), _ptr(bias, torch.float32, (D,), "bias"),
+        _ptr(conv_state_in, x.dtype, (B, D, K - 1), "conv_state_in"), _ptr(y, x.dtype, (B, L, D), "y"),
+        _ptr(conv_state_out, x.dtype, (B, D, K - 1), "conv_state_out"),
+        B, L, D, K, int(bool(apply_silu)), io, _stream(stream))
+    _check("mamba_conv1d_fwd", st)
+    return y, conv_state_out
+
+
+def mamba_scan_workspace_bytes(batch, L, D, N, chunk_len=0) -> int:
+    return int(lib.mamba_scan_workspace_bytes(batch, L, D, N, chunk_len))
+
+
+def mamba_scan_fwd(x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, h0=None, out=None,
+                   h_final=None, workspace=None, chunk_len=0, dt_softplus=True, want_state=True,
+                   stream=None):
+    """x, dt, z (B,L,D); Bm, Cm (B,L,N); A (D,N) f32 -> out (B,L,D), h_final (B,D,N) f32."""
+    B, L, D = x.shape
+    N = A.shape[1]
+    io = _io_code(x)
+    if out is None:
+        out = torch.empty_like(x)
+    if h_final is None and want_state:
+        h_final = torch.empty((B, D, N), dtype=torch.float32, device=x.device)
+    need = mamba_scan_workspace_bytes(B, L, D, N, chunk_len)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.mamba_scan_fwd(
+        _ptr(x, name="x"), _ptr(dt, x.dtype, (B, L, D), "dt"), _ptr(A, torch.float32, (D, N), "A"),
+        _ptr(Bm, x.dtype, (B, L, N), "Bm"), _ptr(Cm, x.dtype, (B, L, N), "Cm"),
+        _ptr(Dskip, torch.float32, (D,), "Dskip"), _ptr(z, x.dtype, (B, L, D), "z"),
+        _ptr(dt_bias, torch.float32, (D,), "dt_bias"), _ptr(h0, torch.float32, (B, D, N), "h0"),
+        _ptr(out, x.dtype, (B, L, D), "out"), _ptr(h_final, torch.float32, (B, D, N), "h_final"),
+        _ptr(workspace, name="workspace"), ws_bytes, B, L, D, N, int(chunk_len),
+        int(bool(dt_softplus)), io, _stream(stream))
+    _check("mamba_scan_fwd", st)
+    return out, h_final
+
+
+def mamba_state_step(h_in, x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, parent_idx=None,
+                     h_out=None, out=None, dt_softplus=True, stream=None):
+    """h_in (n_in,D,N) f32; x, dt, z (n_out,D); Bm, Cm (n_out,N); parent_idx int32[n_out]
+    -> h_out (n_out,D,N), out (n_out,D).  Pass h_out=h_in for the in-place sequential step."""
+    n_in, D, N = h_in.shape
+    n_out = x.shape[0]
+    io = _io_code(x)
+    if h_out is None:
+        h_out = torch.empty((n_out, D, N), dtype=torch.float32, device=x.device)
+    if out is None:
+        out = torch.empty_like(x)
+    st = lib.mamba_state_step(
+        _ptr(h_out, torch.float32, (n_out, D, N), "h_out"), _ptr(h_in, torch.float32, name="h_in"),
+        _ptr(parent_idx, torch.int32, (n_out,), "parent_idx"), _ptr(x, name="x"),
+        _ptr(dt, x.dtype, (n_out, D), "dt"), _ptr(A, torch.float32, (D, N), "A"),
+        _ptr(Bm, x.dtype, (n_out, N), "Bm"), _ptr(Cm, x.dtype, (n_out, N), "Cm"),
+        _ptr(Dskip, torch.float32, (D,), "Dskip"), _ptr(z, x.dtype, (n_out, D), "z"),
+        _ptr(dt_bias, torch.float32, (D,), "dt_bias"), _ptr(out, x.dtype, (n_out, D), "out"),
+        n_out, n_in, D, N, int(bool(dt_softplus)), io, _stream(stream))
+    _check("mamba_state_step", st)
+    return h_out, out
+
+
+def mamba_state_fork(conv_src, ssm_src, parent_idx, conv_dst=None, ssm_dst=None, stream=None):
+    """conv_src (n_layers,n_in,D,K-1) f32|bf16 or None, ssm_src (n_layers,n_in,D,N) f32 or None,
+    parent_idx int32[n_out] -> gathered copies (n_layers,n_out,...)."""
+    ref = conv_src if conv_src is not None else ssm_src
+    n_layers, n_in, D = ref.shape[0], ref.shape[1], ref.shape[2]
+    n_out = parent_idx.shape[0]
+    K, N, cd = 1, 0, MAMBA_F32
+    if conv_src is not None:
+        K = conv_src.shape[3] + 1
+        cd = _io_code(conv_src)
+        if conv_dst is None:
+            conv_dst = torch.empty((n_layers, n_out, D, K - 1), dtype=conv_src.dtype, device=ref.device)
+    if ssm_src is not None:
+        N = ssm_src.shape[3]
+        if ssm_dst is None:
+            ssm_dst = torch.empty((n_layers, n_out, D, N), dtype=torch.float32, device=ref.device)
+    st = lib.mamba_state_fork(
+        _ptr(conv_dst, name="conv_dst"), _ptr(conv_src, name="conv_src"),
+        _ptr(ssm_dst, torch.float32, name="ssm_dst"), _ptr(ssm_src, torch.float32, name="ssm_src"),
+        _ptr(parent_idx, torch.int32, name="parent_idx"), n_layers, n_out, n_in, D, N, K, cd,
+        _stream(stream))
+    _check("mamba_state_fork", st)
+    return conv_dst, ssm_dst

@@ -1,0 +1,204 @@
+// Host side of the C ABI declared in include/mamba_hip.h: argument validation (all of it before
+// any HIP call, so it can be exercised without a GPU), then dispatch to the kernel launchers.
+#include "../../include/mamba_hip.h"
+#include "launch.h"
+
+#include <stdint.h>
+
+namespace {
+
+using namespace mamba;
+
+constexpr int64_t kMaxGridYZ = 65535;
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool mul_ok(int64_t a, int64_t b, int64_t *r) { return !__builtin_mul_overflow(a, b, r) && *r >= 0; }
+
+// total = a * b * c * elem without overflow, below 2^62
+bool size3(int64_t a, int64_t b, int64_t c, int64_t elem, int64_t *bytes)
+{
+    int64_t t;
+    if (a < 0 || b < 0 || c < 0) return false;
+    if (!mul_ok(a, b, &t) || !mul_ok(t, c, &t) || !mul_ok(t, elem, &t)) return false;
+    if (t > (int64_t)1 << 62) return false;
+    *bytes = t;
+    return true;
+}
+
+bool overlap(const void *p, int64_t pn, const void *q, int64_t qn)
+{
+    if (!p || !q || pn <= 0 || qn <= 0) return false;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(q);
+    return a < b + (uintptr_t)qn && b < a + (uintptr_t)pn;
+}
+
+int io_size(int io) { return io == MAMBA_F32 ? 4 : io == MAMBA_BF16 ? 2 : 0; }
+bool n_supported(int64_t N) { return N == 4 || N == 8 || N == 16 || N == 32; }
+bool k_supported(int K) { return K >= 2 && K <= MAMBA_MAX_K; }
+
+}  // namespace
+
+extern "C" {
+
+const char *mamba_status_string(int status)
+{
+    switch (status) {
+    case MAMBA_OK: return "success";
+    case MAMBA_ERR_NULL_POINTER: return "a required pointer is NULL";
+    case MAMBA_ERR_BAD_SHAPE: return "negative, overflowing or inconsistent sizes";
+    case MAMBA_ERR_UNSUPPORTED: return "dtype, d_state, d_conv or a size outside the supported range";
+    case MAMBA_ERR_MISALIGNED: return "a data pointer is not 16-byte aligned";
+    case MAMBA_ERR_WORKSPACE: return "workspace is NULL or too small";
+    case MAMBA_ERR_ALIAS: return "an output buffer overlaps an input where that is not allowed";
+    default: break;
+    }
+    if (status > 0) return hipGetErrorString(static_cast<hipError_t>(status));
+    return "unknown status";
+}
+
+int mamba_conv1d_fwd(const void *x, const float *w, const float *bias, const void *conv_state_in,
+                     void *y, void *conv_state_out, int64_t batch, int64_t L, int64_t D, int K,
+                     int apply_silu, mamba_dtype_t io, void *hip_stream)
+{
+    const int e = io_size(io);
+    if (e == 0 || !k_supported(K)) return MAMBA_ERR_UNSUPPORTED;
+    int64_t tok_bytes, st_bytes;
+    if (!size3(batch, L, D, e, &tok_bytes) || !size3(batch, D, K - 1, e, &st_bytes)) return MAMBA_ERR_BAD_SHAPE;
+    if (batch > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    if (batch == 0 || D == 0) return MAMBA_OK;
+    if (!w || (L > 0 && (!x || !y))) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(conv_state_in) ||
+        !aligned16(y) || !aligned16(conv_state_out))
+        return MAMBA_ERR_MISALIGNED;
+    if (overlap(x, tok_bytes, y, tok_bytes)) return MAMBA_ERR_ALIAS;
+    if (conv_state_in != conv_state_out && overlap(conv_state_in, st_bytes, conv_state_out, st_bytes))
+        return MAMBA_ERR_ALIAS;
+    if (overlap(y, tok_bytes, conv_state_in, st_bytes) || overlap(y, tok_bytes, conv_state_out, st_bytes) ||
+        overlap(x, tok_bytes, conv_state_out, st_bytes))
+        return MAMBA_ERR_ALIAS;
+    if (L == 0 && (!conv_state_out || conv_state_out == conv_state_in)) return MAMBA_OK;
+    ConvArgs a{x, w, bias, conv_state_in, y, conv_state_out, batch, L, D, K, apply_silu, (int)io};
+    return (int)launch_conv1d(a, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t mamba_scan_workspace_bytes(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len)
+{
+    int64_t t;
+    if (batch <= 0 || L <= 0 || D <= 0 || N <= 0 || chunk_len < 0) return 0;
+    if (!size3(batch, L, D, 4, &t) || !size3(batch, D, N + 1, 4, &t)) return 0;
+    int64_t cl, nc;
+    scan_plan(batch, L, D, N, chunk_len, &cl, &nc);
+    return scan_workspace_bytes(batch, D, N, nc);
+}
+
+int mamba_scan_fwd(const void *x, const void *dt, const float *A, const void *Bm, const void *Cm,
+                   const float *Dskip, const void *z, const float *dt_bias, const float *h0,
+                   void *out, float *h_final, void *workspace, size_t workspace_bytes,
+                   int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len,
+                   int dt_softplus, mamba_dtype_t io, void *hip_stream)
+{
+    const int e = io_size(io);
+    if (e == 0) return MAMBA_ERR_UNSUPPORTED;
+    if (N < 0 || chunk_len < 0) return MAMBA_ERR_BAD_SHAPE;
+    int64_t tok_bytes, bc_bytes, st_bytes;
+    if (!size3(batch, L, D, e, &tok_bytes) || !size3(batch, L, N, e, &bc_bytes) ||
+        !size3(batch, D, N, 4, &st_bytes))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (!n_supported(N) || batch > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    if (batch == 0 || D == 0) return MAMBA_OK;
+    if (!A || (L > 0 && (!x || !dt || !Bm || !Cm || !out))) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(x) || !aligned16(dt) || !aligned16(A) || !aligned16(Bm) || !aligned16(Cm) ||
+        !aligned16(Dskip) || !aligned16(z) || !aligned16(dt_bias) || !aligned16(h0) ||
+        !aligned16(out) || !aligned16(h_final) || !aligned16(workspace))
+        return MAMBA_ERR_MISALIGNED;
+    if (overlap(out, tok_bytes, x, tok_bytes) || overlap(out, tok_bytes, dt, tok_bytes) ||
+        overlap(out, tok_bytes, z, tok_bytes) || overlap(out, tok_bytes, Bm, bc_bytes) ||
+        overlap(out, tok_bytes, Cm, bc_bytes) || overlap(out, tok_bytes, h0, st_bytes) ||
+        overlap(out, tok_bytes, h_final, st_bytes))
+        return MAMBA_ERR_ALIAS;
+    if (h_final != h0 && overlap(h_final, st_bytes, h0, st_bytes)) return MAMBA_ERR_ALIAS;
+    int64_t cl, nc;
+    scan_plan(batch, L, D, N, chunk_len, &cl, &nc);
+    if (nc > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    const size_t need = scan_workspace_bytes(batch, D, N, nc);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return MAMBA_ERR_WORKSPACE;
+    if (need > 0 && (overlap(workspace, (int64_t)need, out, tok_bytes) ||
+                     overlap(workspace, (int64_t)need, x, tok_bytes) ||
+                     overlap(workspace, (int64_t)need, dt, tok_bytes) ||
+                     overlap(workspace, (int64_t)need, h_final, st_bytes)))
+        return MAMBA_ERR_ALIAS;
+    ScanArgs a{x, dt, Bm, Cm, z, A, Dskip, dt_bias, h0, out, h_final,
+               need > 0 ? static_cast<float *>(workspace) : nullptr,
+               batch, L, D, (int)N, (int)io, dt_softplus, cl, nc};
+    return (int)launch_scan(a, static_cast<hipStream_t>(hip_stream));
+}
+
+int mamba_state_step(float *h_out, const float *h_in, const int32_t *parent_idx, const void *x,
+                     const void *dt, const float *A, const void *Bm, const void *Cm,
+                     const float *Dskip, const void *z, const float *dt_bias, void *out,
+                     int64_t n_out, int64_t n_in, int64_t D, int64_t N, int dt_softplus,
+                     mamba_dtype_t io, void *hip_stream)
+{
+    const int e = io_size(io);
+    if (e == 0) return MAMBA_ERR_UNSUPPORTED;
+    if (N < 0) return MAMBA_ERR_BAD_SHAPE;
+    int64_t out_bytes, hin_bytes, hout_bytes;
+    if (!size3(n_out, D, 1, e, &out_bytes) || !size3(n_in, D, N, 4, &hin_bytes) ||
+        !size3(n_out, D, N, 4, &hout_bytes))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (!parent_idx && n_in != n_out) return MAMBA_ERR_BAD_SHAPE;
+    if (n_out > 0 && n_in == 0) return MAMBA_ERR_BAD_SHAPE;
+    if (!n_supported(N) || n_out > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    if (n_out == 0 || D == 0) return MAMBA_OK;
+    if (!h_out || !h_in || !x || !dt || !A || !Bm || !Cm || !out) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(h_out) || !aligned16(h_in) || !aligned16(parent_idx) || !aligned16(x) ||
+        !aligned16(dt) || !aligned16(A) || !aligned16(Bm) || !aligned16(Cm) || !aligned16(Dskip) ||
+        !aligned16(z) || !aligned16(dt_bias) || !aligned16(out))
+        return MAMBA_ERR_MISALIGNED;
+    if (!(h_out == h_in && !parent_idx) && overlap(h_out, hout_bytes, h_in, hin_bytes))
+        return MAMBA_ERR_ALIAS;
+    if (overlap(out, out_bytes, x, out_bytes) || overlap(out, out_bytes, dt, out_bytes) ||
+        overlap(out, out_bytes, z, out_bytes) || overlap(out, out_bytes, h_in, hin_bytes) ||
+        overlap(out, out_bytes, h_out, hout_bytes) || overlap(h_out, hout_bytes, x, out_bytes) ||
+        overlap(h_out, hout_bytes, dt, out_bytes) || overlap(h_out, hout_bytes, z, out_bytes))
+        return MAMBA_ERR_ALIAS;
+    StepArgs a{h_out, h_in, parent_idx, x, dt, Bm, Cm, z, A, Dskip, dt_bias, out,
+               n_out, n_in, D, (int)N, (int)io, dt_softplus};
+    return (int)launch_step(a, static_cast<hipStream_t>(hip_stream));
+}
+
+int mamba_state_fork(void *conv_dst, const void *conv_src, float *ssm_dst, const float *ssm_src,
+                     const int32_t *parent_idx, int64_t n_layers, int64_t n_out, int64_t n_in,
+                     int64_t D, int64_t N, int K, mamba_dtype_t conv_dtype, void *hip_stream)
+{
+    const bool has_conv = conv_dst || conv_src, has_ssm = ssm_dst || ssm_src;
+    const int e = io_size(conv_dtype);
+    if (has_conv && (e == 0 || K < 1)) return MAMBA_ERR_UNSUPPORTED;
+    if (N < 0 || n_layers < 0) return MAMBA_ERR_BAD_SHAPE;
+    int64_t conv_row = 0, ssm_row = 0, t, cs = 0, cd = 0, ss = 0, sd = 0;
+    if (has_conv && (!size3(D, K - 1, 1, e, &conv_row) || !size3(n_layers, n_in, conv_row, 1, &cs) ||
+                     !size3(n_layers, n_out, conv_row, 1, &cd)))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (has_ssm && (!size3(D, N, 1, 4, &ssm_row) || !size3(n_layers, n_in, ssm_row, 1, &ss) ||
+                    !size3(n_layers, n_out, ssm_row, 1, &sd)))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (!size3(n_layers, n_out, 1, 1, &t) || !size3(n_layers, n_in, 1, 1, &t) || D < 0) return MAMBA_ERR_BAD_SHAPE;
+    if (n_out > 0 && n_in == 0) return MAMBA_ERR_BAD_SHAPE;
+    if (n_out > kMaxGridYZ || n_layers > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    if (n_layers == 0 || n_out == 0 || (!has_conv && !has_ssm)) return MAMBA_OK;
+    if ((has_conv && (!conv_dst || !conv_src)) || (has_ssm && (!ssm_dst || !ssm_src)) || !parent_idx)
+        return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(conv_dst) || !aligned16(conv_src) || !aligned16(ssm_dst) || !aligned16(ssm_src) ||
+        !aligned16(parent_idx))
+        return MAMBA_ERR_MISALIGNED;
+    if (overlap(conv_dst, cd, conv_src, cs) || overlap(ssm_dst, sd, ssm_src, ss) ||
+        overlap(conv_dst, cd, ssm_src, ss) || overlap(ssm_dst, sd, conv_src, cs) ||
+        overlap(conv_dst, cd, ssm_dst, sd))
+        return MAMBA_ERR_ALIAS;
+    ForkArgs a{conv_row ? conv_dst : nullptr, conv_src, ssm_row ? ssm_dst : nullptr, ssm_src,
+               parent_idx, n_layers, n_out, n_in, conv_row, ssm_row};
+    return (int)launch_fork(a, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,63 @@
+// Internal launch interface between the host-side C ABI (api.cpp) and the kernel files.
+// Arguments are already validated; every function enqueues on `stream` and returns the
+// hipError_t of its last launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mamba {
+
+constexpr int kIoF32 = 0;
+constexpr int kIoBf16 = 1;
+
+struct ConvArgs {
+    const void *x;
+    const float *w, *bias;
+    const void *state_in;
+    void *y;
+    void *state_out;
+    int64_t batch, L, D;
+    int K, apply_silu, io;
+};
+hipError_t launch_conv1d(const ConvArgs &a, hipStream_t stream);
+
+struct ScanArgs {
+    const void *x, *dt, *Bm, *Cm, *z;
+    const float *A, *Dskip, *dt_bias, *h0;
+    void *out;
+    float *h_final;
+    float *ws;  // chunk-boundary workspace or nullptr when n_chunks == 1
+    int64_t batch, L, D;
+    int N, io, dt_softplus;
+    int64_t chunk_len, n_chunks;
+};
+// Chunking chosen for a shape when the caller passes chunk_len = 0 (pure function of the shape).
+void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len_req,
+               int64_t *chunk_len, int64_t *n_chunks);
+size_t scan_workspace_bytes(int64_t batch, int64_t D, int64_t N, int64_t n_chunks);
+hipError_t launch_scan(const ScanArgs &a, hipStream_t stream);
+
+struct StepArgs {
+    float *h_out;
+    const float *h_in;
+    const int32_t *parent;
+    const void *x, *dt, *Bm, *Cm, *z;
+    const float *A, *Dskip, *dt_bias;
+    void *out;
+    int64_t n_out, n_in, D;
+    int N, io, dt_softplus;
+};
+hipError_t launch_step(const StepArgs &a, hipStream_t stream);
+
+struct ForkArgs {
+    void *conv_dst;
+    const void *conv_src;
+    void *ssm_dst;
+    const void *ssm_src;
+    const int32_t *parent;
+    int64_t n_layers, n_out, n_in;
+    int64_t conv_row_bytes, ssm_row_bytes;
+};
+hipError_t launch_fork(const ForkArgs &a, hipStream_t stream);
+
+}  // namespace mamba

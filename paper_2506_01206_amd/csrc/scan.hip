@@ -1,0 +1,481 @@
+// Selective scan for gfx950 (context encoding; Sec. 3.1 of the paper: the drafter encodes
+// the prefix once, with memory that does not grow with its length).
+//
+//   delta = softplus(dt + dt_bias);  h_t = exp(delta_t A) h_{t-1} + delta_t B_t x_t
+//   y_t = C_t . h_t + D x_t;  out_t = y_t silu(z_t)
+//
+// Mapping.  One wavefront per workgroup; a lane owns CPL adjacent channels and keeps their
+// CPL x N float32 states (and A * log2 e) in VGPRs for the whole time range it walks.  B_t and
+// C_t are the same for all channels of a batch row, so their addresses are wave-uniform and
+// they travel through scalar loads into SGPRs.  The recurrence is elementwise: 4 VALU
+// operations and one hardware exp2 per state update, no matrix product anywhere.
+//
+// Time chunking.  A batch row offers only D / (64 CPL) wavefronts, far fewer than the 1024
+// SIMDs of the chip, so long sequences are cut into n_chunks time chunks that run in parallel:
+//   pass 1 (scan_chunk_state): every chunk but the last integrates from a zero state and
+//       writes its local end state H_c and the sum of its deltas S_c;
+//   carry (scan_carry): h_in[0] = h0, h_in[c+1] = exp(A S_c) h_in[c] + H_c, a short serial
+//       loop per (d, n) (the decay over a whole chunk needs only S_c, not a product per step);
+//   pass 2 (scan_chunk_out): every chunk runs the full recurrence from its true h_in[c].
+// With one chunk only pass 2 runs, straight from h0.
+#include "device_math.h"
+#include "launch.h"
+
+namespace mamba {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kTile = 4;  // time steps whose token loads are issued together, one tile ahead
+
+template <typename T, int CPL> struct RawT;
+template <> struct RawT<float, 1> { typedef float type; };
+template <> struct RawT<float, 2> { typedef float2 type; };
+template <> struct RawT<bf16_t, 1> { typedef uint16_t type; };
+template <> struct RawT<bf16_t, 2> { typedef uint32_t type; };
+
+template <typename T, int CPL>
+__device__ __forceinline__ typename RawT<T, CPL>::type ld_raw(const T *p)
+{
+    return *reinterpret_cast<const typename RawT<T, CPL>::type *>(p);
+}
+
+__device__ __forceinline__ void unpack(float r, float *v) { v[0] = r; }
+__device__ __forceinline__ void unpack(float2 r, float *v) { v[0] = r.x; v[1] = r.y; }
+__device__ __forceinline__ void unpack(uint16_t r, float *v) { v[0] = bf16_to_f32(r); }
+__device__ __forceinline__ void unpack(uint32_t r, float *v) { v[0] = bf16_lo(r); v[1] = bf16_hi(r); }
+
+template <int CPL> __device__ __forceinline__ void st_pack(float *p, const float *v)
+{
+    if constexpr (CPL == 1) p[0] = v[0];
+    else *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+}
+template <int CPL> __device__ __forceinline__ void st_pack(bf16_t *p, const float *v)
+{
+    if constexpr (CPL == 1) p[0] = (bf16_t)f32_to_bf16(v[0]);
+    else *reinterpret_cast<uint32_t *>(p) = f32x2_to_bf16x2(v[0], v[1]);
+}
+
+// B_t or C_t: N values at a wave-uniform address.
+template <int N> __device__ __forceinline__ void ld_uniform(const float *p, float *f)
+{
+#pragma unroll
+    for (int n = 0; n < N; ++n) f[n] = p[n];
+}
+template <int N> __device__ __forceinline__ void ld_uniform(const bf16_t *p, float *f)
+{
+    const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+#pragma unroll
+    for (int i = 0; i < N / 2; ++i) {
+        const uint32_t r = q[i];
+        f[2 * i] = bf16_lo(r);
+        f[2 * i + 1] = bf16_hi(r);
+    }
+}
+
+template <int N, int CPL> struct LaneState {
+    float h[CPL][N];
+    float a2[CPL][N];  // A * log2(e)
+    float bias[CPL];
+    float dskip[CPL];
+};
+
+template <int N, int CPL>
+__device__ __forceinline__ void load_lane_params(LaneState<N, CPL> &s, const float *__restrict__ A,
+                                                 const float *__restrict__ Dskip,
+                                                 const float *__restrict__ dt_bias, int64_t d0)
+{
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const float4 *ap = reinterpret_cast<const float4 *>(A + (d0 + c) * N);
+#pragma unroll
+        for (int q = 0; q < N / 4; ++q) {
+            const float4 v = ap[q];
+            s.a2[c][4 * q + 0] = v.x * kLog2e;
+            s.a2[c][4 * q + 1] = v.y * kLog2e;
+            s.a2[c][4 * q + 2] = v.z * kLog2e;
+            s.a2[c][4 * q + 3] = v.w * kLog2e;
+        }
+        s.bias[c] = dt_bias ? dt_bias[d0 + c] : 0.0f;
+        s.dskip[c] = Dskip ? Dskip[d0 + c] : 0.0f;
+    }
+}
+
+template <int N, int CPL>
+__device__ __forceinline__ void load_state(float (&h)[CPL][N], const float *p /* (d0, 0) */)
+{
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const float4 *hp = reinterpret_cast<const float4 *>(p + c * N);
+#pragma unroll
+        for (int q = 0; q < N / 4; ++q) {
+            const float4 v = hp[q];
+            h[c][4 * q + 0] = v.x;
+            h[c][4 * q + 1] = v.y;
+            h[c][4 * q + 2] = v.z;
+            h[c][4 * q + 3] = v.w;
+        }
+    }
+}
+
+template <int N, int CPL>
+__device__ __forceinline__ void store_state(const float (&h)[CPL][N], float *p)
+{
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        float4 *hp = reinterpret_cast<float4 *>(p + c * N);
+#pragma unroll
+        for (int q = 0; q < N / 4; ++q)
+            hp[q] = make_float4(h[c][4 * q], h[c][4 * q + 1], h[c][4 * q + 2], h[c][4 * q + 3]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// pass 2 (and the only pass when n_chunks == 1): full recurrence with outputs
+// grid: (channel groups, n_chunks, batch), block: one wavefront
+template <typename T, int N, int CPL, bool HAS_Z, bool SOFTPLUS>
+__global__ void __launch_bounds__(kWave)
+scan_chunk_out(const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
+               const T *__restrict__ Bm, const T *__restrict__ Cm, const float *__restrict__ Dskip,
+               const T *__restrict__ z, const float *__restrict__ dt_bias,
+               const float *h_start /* h0 (may be null, may alias h_final) or chunk states */,
+               int h_start_chunked, T *__restrict__ out, float *h_final, int64_t L, int64_t D,
+               int64_t chunk_len, int n_chunks)
+{
+    typedef typename RawT<T, CPL>::type raw_t;
+    const int lane = threadIdx.x;
+    const int64_t b = blockIdx.z;
+    const int chunk = blockIdx.y;
+    const int64_t d_lane = ((int64_t)blockIdx.x * kWave + lane) * CPL;
+    const bool live = d_lane < D;                 // CPL == 2 only runs with D even
+    const int64_t d0 = live ? d_lane : D - CPL;   // dead lanes shadow the last channels, store nothing
+    const int64_t t0 = (int64_t)chunk * chunk_len;
+    const int64_t t1 = (t0 + chunk_len < L) ? t0 + chunk_len : L;
+
+    LaneState<N, CPL> s;
+    load_lane_params<N, CPL>(s, A, Dskip, dt_bias, d0);
+    if (h_start_chunked) {
+        load_state<N, CPL>(s.h, h_start + (((int64_t)b * n_chunks + chunk) * D + d0) * N);
+    } else if (h_start) {
+        load_state<N, CPL>(s.h, h_start + (b * D + d0) * N);
+    } else {
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int n = 0; n < N; ++n) s.h[c][n] = 0.0f;
+    }
+
+    const int64_t row0 = b * L;
+    auto step = [&](int64_t t, raw_t xr, raw_t dr, raw_t zr) {
+        float bf[N], cf[N];
+        ld_uniform<N>(Bm + (row0 + t) * N, bf);
+        ld_uniform<N>(Cm + (row0 + t) * N, cf);
+        float xv[CPL], dv[CPL], zv[CPL], ov[CPL];
+        unpack(xr, xv);
+        unpack(dr, dv);
+        if constexpr (HAS_Z) unpack(zr, zv);
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            const float v = dv[c] + s.bias[c];
+            const float delta = SOFTPLUS ? softplus_f32(v) : v;
+            const float u = delta * xv[c];
+            float y = s.dskip[c] * xv[c];
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const float a = exp2_hw(delta * s.a2[c][n]);
+                s.h[c][n] = fmaf(a, s.h[c][n], u * bf[n]);
+                y = fmaf(s.h[c][n], cf[n], y);
+            }
+            ov[c] = HAS_Z ? y * silu_f32(zv[c]) : y;
+        }
+        if (live) st_pack<CPL>(out + (row0 + t) * D + d0, ov);
+    };
+
+    raw_t xc[kTile], dc[kTile], zc[kTile];
+    auto load_tile = [&](int64_t t, raw_t *xa, raw_t *da, raw_t *za) {
+#pragma unroll
+        for (int i = 0; i < kTile; ++i) {
+            const int64_t o = (row0 + t + i) * D + d0;
+            xa[i] = ld_raw<T, CPL>(x + o);
+            da[i] = ld_raw<T, CPL>(dt + o);
+            if constexpr (HAS_Z) za[i] = ld_raw<T, CPL>(z + o);
+        }
+    };
+    int64_t t = t0;
+    if (t + kTile <= t1) load_tile(t, xc, dc, zc);
+    for (; t + kTile <= t1; t += kTile) {
+        raw_t xn[kTile], dn[kTile], zn[kTile];
+        const bool more = t + 2 * kTile <= t1;
+        if (more) load_tile(t + kTile, xn, dn, zn);
+#pragma unroll
+        for (int i = 0; i < kTile; ++i) step(t + i, xc[i], dc[i], zc[i]);
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < kTile; ++i) {
+                xc[i] = xn[i];
+                dc[i] = dn[i];
+                if constexpr (HAS_Z) zc[i] = zn[i];
+            }
+        }
+    }
+    for (; t < t1; ++t) {
+        const int64_t o = (row0 + t) * D + d0;
+        raw_t zr = raw_t();
+        if constexpr (HAS_Z) zr = ld_raw<T, CPL>(z + o);
+        step(t, ld_raw<T, CPL>(x + o), ld_raw<T, CPL>(dt + o), zr);
+    }
+
+    if (h_final && chunk == n_chunks - 1 && live) store_state<N, CPL>(s.h, h_final + (b * D + d0) * N);
+}
+
+// ---------------------------------------------------------------------------------------
+// pass 1: local end state of a chunk from a zero state, and the sum of its deltas
+// grid: (channel groups, n_chunks - 1, batch); chunk c writes slot c + 1 of ws_state
+template <typename T, int N, int CPL, bool SOFTPLUS>
+__global__ void __launch_bounds__(kWave)
+scan_chunk_state(const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
+                 const T *__restrict__ Bm, const float *__restrict__ dt_bias,
+                 float *__restrict__ ws_state, float *__restrict__ ws_sumdt, int64_t L, int64_t D,
+                 int64_t chunk_len, int n_chunks)
+{
+    typedef typename RawT<T, CPL>::type raw_t;
+    const int lane = threadIdx.x;
+    const int64_t b = blockIdx.z;
+    const int chunk = blockIdx.y;
+    const int64_t d_lane = ((int64_t)blockIdx.x * kWave + lane) * CPL;
+    const bool live = d_lane < D;
+    const int64_t d0 = live ? d_lane : D - CPL;
+    const int64_t t0 = (int64_t)chunk * chunk_len;
+    const int64_t t1 = t0 + chunk_len;  // never the last chunk, so t1 <= L
+
+    LaneState<N, CPL> s;
+    load_lane_params<N, CPL>(s, A, nullptr, dt_bias, d0);
+    float sum[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        sum[c] = 0.0f;
+#pragma unroll
+        for (int n = 0; n < N; ++n) s.h[c][n] = 0.0f;
+    }
+
+    const int64_t row0 = b * L;
+    auto step = [&](int64_t t, raw_t xr, raw_t dr) {
+        float bf[N];
+        ld_uniform<N>(Bm + (row0 + t) * N, bf);
+        float xv[CPL], dv[CPL];
+        unpack(xr, xv);
+        unpack(dr, dv);
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            const float v = dv[c] + s.bias[c];
+            const float delta = SOFTPLUS ? softplus_f32(v) : v;
+            const float u = delta * xv[c];
+            sum[c] += delta;
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const float a = exp2_hw(delta * s.a2[c][n]);
+                s.h[c][n] = fmaf(a, s.h[c][n], u * bf[n]);
+            }
+        }
+    };
+
+    raw_t xc[kTile], dc[kTile];
+    auto load_tile = [&](int64_t t, raw_t *xa, raw_t *da) {
+#pragma unroll
+        for (int i = 0; i < kTile; ++i) {
+            const int64_t o = (row0 + t + i) * D + d0;
+            xa[i] = ld_raw<T, CPL>(x + o);
+            da[i] = ld_raw<T, CPL>(dt + o);
+        }
+    };
+    int64_t t = t0;
+    if (t + kTile <= t1) load_tile(t, xc, dc);
+    for (; t + kTile <= t1; t += kTile) {
+        raw_t xn[kTile], dn[kTile];
+        const bool more = t + 2 * kTile <= t1;
+        if (more) load_tile(t + kTile, xn, dn);
+#pragma unroll
+        for (int i = 0; i < kTile; ++i) step(t + i, xc[i], dc[i]);
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < kTile; ++i) {
+                xc[i] = xn[i];
+                dc[i] = dn[i];
+            }
+        }
+    }
+    for (; t < t1; ++t) {
+        const int64_t o = (row0 + t) * D + d0;
+        step(t, ld_raw<T, CPL>(x + o), ld_raw<T, CPL>(dt + o));
+    }
+
+    if (live) {
+        const int64_t slot = (int64_t)b * n_chunks + chunk;
+        store_state<N, CPL>(s.h, ws_state + ((slot + 1) * D + d0) * N);
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) ws_sumdt[slot * D + d0 + c] = sum[c];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// carry: slot 0 <- h0; slot c <- exp(A S_{c-1}) slot_{c-1} + slot_c.  One thread per (b, d, n).
+__global__ void __launch_bounds__(256)
+scan_carry(const float *__restrict__ A, const float *h0, float *ws_state,
+           const float *__restrict__ ws_sumdt, int64_t batch, int64_t D, int N, int n_chunks)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t DN = D * N;
+    if (idx >= batch * DN) return;
+    const int64_t b = idx / DN;
+    const int64_t dn = idx - b * DN;
+    const int64_t d = dn / N;
+    const float a2 = A[dn] * kLog2e;
+    float h = h0 ? h0[idx] : 0.0f;
+    float *st = ws_state + b * n_chunks * DN + dn;
+    const float *sd = ws_sumdt + b * n_chunks * D + d;
+    st[0] = h;
+    constexpr int U = 8;
+    int c = 1;
+    for (; c + U <= n_chunks; c += U) {
+        float loc[U], sm[U];
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            loc[i] = st[(int64_t)(c + i) * DN];
+            sm[i] = sd[(int64_t)(c + i - 1) * D];
+        }
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            h = fmaf(exp2_hw(a2 * sm[i]), h, loc[i]);
+            st[(int64_t)(c + i) * DN] = h;
+        }
+    }
+    for (; c < n_chunks; ++c) {
+        h = fmaf(exp2_hw(a2 * sd[(int64_t)(c - 1) * D]), h, st[(int64_t)c * DN]);
+        st[(int64_t)c * DN] = h;
+    }
+}
+
+// copies h0 (or zeros) to h_final when L == 0
+__global__ void copy_state(const float *h0, float *h_final, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) h_final[i] = h0 ? h0[i] : 0.0f;
+}
+
+template <typename T, int N, int CPL>
+hipError_t launch_scan_t(const ScanArgs &a, hipStream_t stream)
+{
+    const T *x = static_cast<const T *>(a.x), *dt = static_cast<const T *>(a.dt);
+    const T *Bm = static_cast<const T *>(a.Bm), *Cm = static_cast<const T *>(a.Cm);
+    const T *z = static_cast<const T *>(a.z);
+    T *out = static_cast<T *>(a.out);
+    const unsigned groups = (unsigned)((a.D + kWave * CPL - 1) / (kWave * CPL));
+    const int nc = (int)a.n_chunks;
+    const float *h_start = a.h0;
+    int chunked = 0;
+    if (nc > 1) {
+        float *ws_state = a.ws;
+        float *ws_sumdt = a.ws + (size_t)a.batch * nc * a.D * N;
+        dim3 g1(groups, nc - 1, (unsigned)a.batch);
+        if (a.dt_softplus)
+            scan_chunk_state<T, N, CPL, true><<<g1, kWave, 0, stream>>>(
+                x, dt, a.A, Bm, a.dt_bias, ws_state, ws_sumdt, a.L, a.D, a.chunk_len, nc);
+        else
+            scan_chunk_state<T, N, CPL, false><<<g1, kWave, 0, stream>>>(
+                x, dt, a.A, Bm, a.dt_bias, ws_state, ws_sumdt, a.L, a.D, a.chunk_len, nc);
+        const int64_t total = a.batch * a.D * N;
+        scan_carry<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
+            a.A, a.h0, ws_state, ws_sumdt, a.batch, a.D, N, nc);
+        h_start = ws_state;
+        chunked = 1;
+    }
+    dim3 g2(groups, nc, (unsigned)a.batch);
+#define MAMBA_LAUNCH_OUT(HZ, SP)                                                                  \
+    scan_chunk_out<T, N, CPL, HZ, SP><<<g2, kWave, 0, stream>>>(                                  \
+        x, dt, a.A, Bm, Cm, a.Dskip, z, a.dt_bias, h_start, chunked, out, a.h_final, a.L, a.D,    \
+        a.chunk_len, nc)
+    if (z) {
+        if (a.dt_softplus) MAMBA_LAUNCH_OUT(true, true);
+        else MAMBA_LAUNCH_OUT(true, false);
+    } else {
+        if (a.dt_softplus) MAMBA_LAUNCH_OUT(false, true);
+        else MAMBA_LAUNCH_OUT(false, false);
+    }
+#undef MAMBA_LAUNCH_OUT
+    return hipGetLastError();
+}
+
+template <typename T, int N>
+hipError_t launch_scan_n(const ScanArgs &a, hipStream_t stream)
+{
+    // two channels per lane need even D so that every row keeps the pair's alignment
+    if (a.D % 2 == 0) return launch_scan_t<T, N, 2>(a, stream);
+    return launch_scan_t<T, N, 1>(a, stream);
+}
+
+template <typename T> hipError_t launch_scan_io(const ScanArgs &a, hipStream_t stream)
+{
+    switch (a.N) {
+    case 4: return launch_scan_n<T, 4>(a, stream);
+    case 8: return launch_scan_n<T, 8>(a, stream);
+    case 16: return launch_scan_n<T, 16>(a, stream);
+    case 32: return launch_scan_n<T, 32>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+// Chunking policy.  A wavefront column covers 64 * CPL channels of one batch row; the chip has
+// 256 CUs x 4 SIMDs.  Sequences are cut only as far as needed to put about two wavefronts on
+// every SIMD, because every extra chunk costs a second walk over its tokens (pass 1).
+void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len_req,
+               int64_t *chunk_len, int64_t *n_chunks)
+{
+    (void)N;
+    if (L <= 0 || batch <= 0 || D <= 0) {
+        *chunk_len = L > 0 ? L : 1;
+        *n_chunks = 1;
+        return;
+    }
+    int64_t cl;
+    if (chunk_len_req > 0) {
+        cl = chunk_len_req;
+    } else {
+        const int64_t cpl = (D % 2 == 0) ? 2 : 1;
+        const int64_t columns = batch * ((D + kWave * cpl - 1) / (kWave * cpl));
+        const int64_t target_waves = 2048;
+        const int64_t min_chunk = 64;
+        int64_t want = (target_waves + columns - 1) / columns;
+        if (columns >= 640) want = 1;
+        const int64_t max_chunks = (L + min_chunk - 1) / min_chunk;
+        if (want > max_chunks) want = max_chunks;
+        if (want < 1) want = 1;
+        cl = (L + want - 1) / want;
+        cl = (cl + kTile - 1) / kTile * kTile;
+    }
+    if (cl > L) cl = L;
+    *chunk_len = cl;
+    *n_chunks = (L + cl - 1) / cl;
+}
+
+size_t scan_workspace_bytes(int64_t batch, int64_t D, int64_t N, int64_t n_chunks)
+{
+    if (n_chunks <= 1) return 0;
+    return (size_t)batch * (size_t)n_chunks * (size_t)D * (size_t)(N + 1) * sizeof(float);
+}
+
+hipError_t launch_scan(const ScanArgs &a, hipStream_t stream)
+{
+    if (a.L == 0) {
+        if (a.h_final && a.h_final != a.h0) {
+            const int64_t n = a.batch * a.D * a.N;
+            copy_state<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(a.h0, a.h_final, n);
+            return hipGetLastError();
+        }
+        return hipSuccess;
+    }
+    if (a.io == kIoBf16) return launch_scan_io<bf16_t>(a, stream);
+    return launch_scan_io<float>(a, stream);
+}
+
+}  // namespace mamba

@@ -1,0 +1,173 @@
+"""Host-side tests of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching the GPU (so all of this runs without one).
+
+Pointers passed here are fake, 16-byte aligned, non-overlapping addresses: every call below must
+return from validation with a negative status (or succeed with nothing to do) and never launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mamba_hip.h")
+
+
+@pytest.fixture(scope="module")
+def b():
+    lib_path = os.path.join(ROOT, "paper_2506_01206_amd", "libmamba_hip.so")
+    if not os.path.exists(lib_path):
+        from paper_2506_01206_amd import build
+        build.build()
+    from paper_2506_01206_amd import binding
+    return binding
+
+
+def P(i):
+    """i-th fake buffer: 1 TiB apart, 16-byte aligned, never dereferenced."""
+    return (i + 1) << 40
+
+
+def test_library_exports_every_declared_symbol(b):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(mamba_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(b.EXPORTS), declared ^ set(b.EXPORTS)
+    raw = ctypes.CDLL(b.LIB_PATH)
+    for name in declared:
+        assert getattr(raw, name) is not None
+    # the Python binding carries the same names
+    for name in declared:
+        assert callable(getattr(b, name))
+
+
+def test_status_strings(b):
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5, -6):
+        s = b.mamba_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert b.mamba_status_string(-99) == "unknown status"
+    assert b.mamba_status_string(1)            # a hipError_t text
+
+
+def scan(b, x=P(0), dt=P(1), A=P(2), Bm=P(3), Cm=P(4), Dskip=P(5), z=P(6), bias=P(7), h0=P(8),
+         out=P(9), hf=P(10), ws=P(11), ws_bytes=1 << 39, batch=1, L=4096, D=256, N=16, chunk=0,
+         sp=1, io=1):
+    return b.lib.mamba_scan_fwd(x, dt, A, Bm, Cm, Dskip, z, bias, h0, out, hf, ws, ws_bytes,
+                                batch, L, D, N, chunk, sp, io, None)
+
+
+def test_scan_validation(b):
+    S = b.STATUS
+    assert scan(b, x=None) == S["NULL_POINTER"]
+    assert scan(b, A=None) == S["NULL_POINTER"]
+    assert scan(b, out=None) == S["NULL_POINTER"]
+    assert scan(b, L=-1) == S["BAD_SHAPE"]
+    assert scan(b, batch=-2) == S["BAD_SHAPE"]
+    assert scan(b, L=1 << 40, D=1 << 30) == S["BAD_SHAPE"]          # size overflow
+    assert scan(b, N=17) == S["UNSUPPORTED"]
+    assert scan(b, N=64) == S["UNSUPPORTED"]
+    assert scan(b, io=7) == S["UNSUPPORTED"]
+    assert scan(b, batch=70000, L=8, D=8) == S["UNSUPPORTED"]
+    assert scan(b, x=P(0) + 8) == S["MISALIGNED"]
+    assert scan(b, hf=P(10) + 4) == S["MISALIGNED"]
+    assert scan(b, out=P(0)) == S["ALIAS"]                          # out == x
+    assert scan(b, out=P(1) + 64) == S["ALIAS"]                     # out inside dt
+    assert scan(b, hf=P(8) + 16) == S["ALIAS"]                      # h_final partly over h0
+    assert scan(b, ws=None) == S["WORKSPACE"]                       # this shape is chunked
+    assert scan(b, ws_bytes=16) == S["WORKSPACE"]
+    assert scan(b, chunk=-1) == S["BAD_SHAPE"]
+    # nothing to do: success without a launch
+    assert scan(b, batch=0) == 0
+    assert scan(b, D=0) == 0
+    # a single chunk needs no workspace, so a missing one is not an error there; with an invalid
+    # dtype the call still stops in validation
+    assert b.mamba_scan_workspace_bytes(1, 4096, 256, 16, 4096) == 0
+    assert b.mamba_scan_workspace_bytes(1, 4096, 256, 16, 1 << 40) == 0
+
+
+def test_scan_workspace_query(b):
+    w = b.mamba_scan_workspace_bytes
+    assert w(0, 10, 10, 16, 0) == 0 and w(1, 0, 10, 16, 0) == 0 and w(1, 10, 10, 16, -1) == 0
+    # explicit chunking: n_chunks slots of D*(N+1) floats per batch row
+    assert w(2, 1000, 100, 16, 100) == 2 * 10 * 100 * 17 * 4
+    assert w(2, 1001, 100, 16, 100) == 2 * 11 * 100 * 17 * 4
+    assert w(1, 1000, 100, 16, 1000) == 0 and w(1, 1000, 100, 16, 5000) == 0
+    # automatic chunking is a pure function of the shape, and grows no faster than L
+    a = w(1, 32768, 1536, 16, 0)
+    assert a == w(1, 32768, 1536, 16, 0) and a > 0
+    assert a % (1536 * 17 * 4) == 0
+    n_chunks = a // (1536 * 17 * 4)
+    assert 2 <= n_chunks <= 32768 // 64
+    # a batch-rich shape fills the chip without cutting time
+    assert w(64, 4096, 4096, 16, 0) == 0
+
+
+def conv(b, x=P(0), w=P(1), bias=P(2), si=P(3), y=P(4), so=P(5), batch=2, L=100, D=64, K=4,
+         silu=1, io=1):
+    return b.lib.mamba_conv1d_fwd(x, w, bias, si, y, so, batch, L, D, K, silu, io, None)
+
+
+def test_conv_validation(b):
+    S = b.STATUS
+    assert conv(b, x=None) == S["NULL_POINTER"]
+    assert conv(b, w=None) == S["NULL_POINTER"]
+    assert conv(b, y=None) == S["NULL_POINTER"]
+    assert conv(b, K=1) == S["UNSUPPORTED"]
+    assert conv(b, K=5) == S["UNSUPPORTED"]
+    assert conv(b, io=2) == S["UNSUPPORTED"]
+    assert conv(b, L=-1) == S["BAD_SHAPE"]
+    assert conv(b, D=-1) == S["BAD_SHAPE"]
+    assert conv(b, y=P(0)) == S["ALIAS"]
+    assert conv(b, so=P(3) + 16) == S["ALIAS"]                      # partial state overlap
+    assert conv(b, si=P(3) + 2, so=P(5)) == S["MISALIGNED"]
+    assert conv(b, batch=0) == 0
+    assert conv(b, L=0, so=None) == 0
+    assert conv(b, L=0, si=P(3), so=P(3)) == 0                      # in place, nothing to shift
+
+
+def step(b, ho=P(0), hi=P(1), par=P(2), x=P(3), dt=P(4), A=P(5), Bm=P(6), Cm=P(7), Dk=P(8), z=P(9),
+         bias=P(10), out=P(11), n_out=8, n_in=4, D=64, N=16, sp=1, io=1):
+    return b.lib.mamba_state_step(ho, hi, par, x, dt, A, Bm, Cm, Dk, z, bias, out, n_out, n_in, D, N,
+                                  sp, io, None)
+
+
+def test_step_validation(b):
+    S = b.STATUS
+    assert step(b, hi=None) == S["NULL_POINTER"]
+    assert step(b, Cm=None) == S["NULL_POINTER"]
+    assert step(b, par=None) == S["BAD_SHAPE"]                       # identity needs n_in == n_out
+    assert step(b, n_in=0) == S["BAD_SHAPE"]
+    assert step(b, n_out=-1) == S["BAD_SHAPE"]
+    assert step(b, N=12) == S["UNSUPPORTED"]
+    assert step(b, io=3) == S["UNSUPPORTED"]
+    assert step(b, n_out=1 << 20) == S["UNSUPPORTED"]
+    assert step(b, ho=P(1)) == S["ALIAS"]                            # in place only without parent
+    assert step(b, ho=P(1) + 64, par=None, n_in=8) == S["ALIAS"]     # partial overlap never
+    assert step(b, out=P(3)) == S["ALIAS"]
+    assert step(b, x=P(3) + 2) == S["MISALIGNED"]
+    assert step(b, n_out=0, n_in=4) == 0
+    assert step(b, D=0) == 0
+
+
+def fork(b, cd=P(0), cs=P(1), sd=P(2), ss=P(3), par=P(4), nl=24, n_out=8, n_in=4, D=64, N=16, K=4,
+         io=1):
+    return b.lib.mamba_state_fork(cd, cs, sd, ss, par, nl, n_out, n_in, D, N, K, io, None)
+
+
+def test_fork_validation(b):
+    S = b.STATUS
+    assert fork(b, par=None) == S["NULL_POINTER"]
+    assert fork(b, cd=None) == S["NULL_POINTER"]                     # half of the conv pair
+    assert fork(b, ss=None) == S["NULL_POINTER"]                     # half of the ssm pair
+    assert fork(b, n_in=0) == S["BAD_SHAPE"]
+    assert fork(b, nl=-1) == S["BAD_SHAPE"]
+    assert fork(b, io=5) == S["UNSUPPORTED"]
+    assert fork(b, n_out=1 << 17) == S["UNSUPPORTED"]
+    assert fork(b, cd=P(1)) == S["ALIAS"]
+    assert fork(b, sd=P(3) + 1024) == S["ALIAS"]
+    assert fork(b, cs=P(1) + 4) == S["MISALIGNED"]
+    assert fork(b, n_out=0) == 0
+    assert fork(b, nl=0) == 0
+    assert fork(b, cd=None, cs=None, sd=None, ss=None) == 0

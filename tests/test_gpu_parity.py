@@ -1,0 +1,471 @@
+"""GPU parity: every entry point of the C ABI against the fp64 oracle, element by element, on the
+same seeded inputs; plus the invariants that hold at any size (scan == repeated steps, chunked
+== unchunked, fused fork+step == fork then step bit for bit, run-to-run determinism)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_01206_amd import synth
+from gpu_util import DEV, TOL, W, assert_close, dev_case, oracle_scan, to_dev, to_host, values
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def m():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2506_01206_amd import binding
+    return binding
+
+
+@pytest.fixture(autouse=True)
+def announce(request):
+    print("\n[gpu-case] %s" % request.node.nodeid, flush=True)
+    sys.stdout.flush()
+    yield
+    torch.cuda.synchronize()
+
+
+def say(**kw):
+    print("    " + " ".join("%s=%s" % kv for kv in kw.items()), flush=True)
+
+
+# ------------------------------------------------------------------------------------ conv1d
+def run_conv(m, c, state_in=None, apply_silu=True, want_state=True):
+    d = dev_case(c, ("x", "conv_w", "conv_bias"))
+    y, st = m.mamba_conv1d_fwd(d["x"], d["conv_w"], d["conv_bias"], to_dev(state_in),
+                               apply_silu=apply_silu, want_state=want_state)
+    return to_host(y), to_host(st)
+
+
+def check_conv(m, c, state_in=None, apply_silu=True):
+    y, st = run_conv(m, c, state_in, apply_silu)
+    ry, rst = oracle.conv1d_fwd(W(c["x"]), W(c["conv_w"]), W(c["conv_bias"]), W(state_in), apply_silu)
+    assert_close(values(y), ry, TOL[c["io"]], "conv y")
+    # the carried state is a verbatim copy of inputs: exact in the storage dtype
+    assert np.array_equal(values(st), rst), "conv state"
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("K", [2, 3, 4])
+@pytest.mark.parametrize("B,L,D", [(1, 1, 8), (2, 3, 17), (1, 63, 64), (3, 65, 100), (1, 257, 256),
+                                   (2, 1000, 24), (1, 2, 1)])
+def test_conv_shapes(m, io, K, B, L, D):
+    say(io=io, K=K, B=B, L=L, D=D)
+    c = synth.prefill_case(B, L, D, 16, K, io, seed=1000 + L + D + K)
+    rng = np.random.default_rng(7)
+    c["conv_bias"] = rng.standard_normal(D).astype(np.float32)
+    st0 = synth.to_io(rng.standard_normal((B, D, K - 1)).astype(np.float32), io)
+    check_conv(m, c, None, True)
+    check_conv(m, c, st0, False)
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+def test_conv_carry_and_in_place_state(m, io):
+    B, L, D, K = 2, 150, 64, 4
+    c = synth.prefill_case(B, L, D, 16, K, io, seed=77)
+    d = dev_case(c, ("x", "conv_w", "conv_bias"))
+    y_full, st_full = m.mamba_conv1d_fwd(d["x"], d["conv_w"], d["conv_bias"])
+    # token by token with the window updated in place (the decode-time use)
+    state = torch.zeros((B, D, K - 1), dtype=d["x"].dtype, device=DEV)
+    ys = []
+    for t in range(L):
+        xt = d["x"][:, t:t + 1].contiguous()
+        yt, _ = m.mamba_conv1d_fwd(xt, d["conv_w"], d["conv_bias"], conv_state_in=state,
+                                   conv_state_out=state)
+        ys.append(yt)
+    y_steps = torch.cat(ys, dim=1)
+    assert torch.equal(y_steps, y_full)          # same arithmetic, same order: bit-identical
+    assert torch.equal(state, st_full)
+    # two pieces with a carried state
+    y1, s1 = m.mamba_conv1d_fwd(d["x"][:, :70].contiguous(), d["conv_w"], d["conv_bias"])
+    y2, s2 = m.mamba_conv1d_fwd(d["x"][:, 70:].contiguous(), d["conv_w"], d["conv_bias"], conv_state_in=s1)
+    assert torch.equal(torch.cat([y1, y2], 1), y_full) and torch.equal(s2, st_full)
+    # L == 0 passes the state through
+    e = d["x"][:, :0].contiguous()
+    _, s0 = m.mamba_conv1d_fwd(e, d["conv_w"], d["conv_bias"], conv_state_in=s1)
+    assert torch.equal(s0, s1)
+    _, sz = m.mamba_conv1d_fwd(e, d["conv_w"], d["conv_bias"])
+    assert torch.count_nonzero(sz.float()) == 0
+
+
+# ------------------------------------------------------------------------------------ scan
+def run_scan(m, c, h0=None, chunk_len=0, **kw):
+    d = dev_case(c)
+    args = dict(x=d["x"], dt=d["dt"], A=d["A"], Bm=d["Bm"], Cm=d["Cm"], Dskip=d["Dskip"], z=d["z"],
+                dt_bias=d["dt_bias"], h0=to_dev(h0), chunk_len=chunk_len)
+    args.update(kw)
+    out, hf = m.mamba_scan_fwd(**args)
+    return to_host(out), to_host(hf)
+
+
+def check_scan(m, c, h0=None, chunk_len=0, what="scan", **kw):
+    out, hf = run_scan(m, c, h0, chunk_len, **kw)
+    okw = {}
+    for k in ("Dskip", "z", "dt_bias"):
+        if k in kw and kw[k] is None:
+            okw[k] = None
+    if "dt_softplus" in kw:
+        okw["dt_softplus"] = kw["dt_softplus"]
+    ro, rh = oracle_scan(c, h0=None if h0 is None else h0.astype(np.float64), **okw)
+    e1 = assert_close(values(out), ro, TOL[c["io"]], what + " out")
+    e2 = assert_close(hf, rh, TOL[c["io"]], what + " h_final")
+    return e1, e2
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("L", [1, 2, 3, 63, 64, 65, 255, 257, 1000])
+@pytest.mark.parametrize("D", [1, 17, 64, 100, 256])
+def test_scan_shapes(m, io, L, D):
+    say(io=io, L=L, D=D)
+    B, N = (2 if L < 300 else 1), 16
+    c = synth.prefill_case(B, L, D, N, 4, io, seed=L * 1000 + D)
+    h0 = np.random.default_rng(L + D).standard_normal((B, D, N)).astype(np.float32)
+    check_scan(m, c, h0=h0)
+    if L in (65, 257, 1000):
+        for cl in (1, 7, 64, 100):
+            check_scan(m, c, h0=h0, chunk_len=cl, what="scan chunk_len=%d" % cl)
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("N", [4, 8, 16, 32])
+def test_scan_state_sizes_and_random_A(m, io, N):
+    say(io=io, N=N)
+    c = synth.prefill_case(2, 300, 96, N, 4, io, seed=500 + N, random_A=True)
+    check_scan(m, c)
+    check_scan(m, c, chunk_len=64, what="chunked")
+    c2 = synth.prefill_case(1, 300, 33, N, 4, io, seed=600 + N, random_A=True)   # odd D
+    check_scan(m, c2, chunk_len=50, what="odd D chunked")
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+def test_scan_optional_arguments(m, io):
+    c = synth.prefill_case(2, 200, 128, 16, 4, io, seed=42)
+    h0 = np.random.default_rng(3).standard_normal((2, 128, 16)).astype(np.float32)
+    check_scan(m, c, h0=h0, z=None, what="no gate")
+    check_scan(m, c, Dskip=None, what="no skip")
+    check_scan(m, c, dt_bias=None, what="no dt_bias")
+    c3 = dict(c)
+    c3["dt"] = synth.to_io(np.abs(synth.io_values(c["dt"], io)) + 0.01, io)
+    c3["dt_bias"] = np.abs(c["dt_bias"]) * 0.01
+    check_scan(m, c3, h0=h0, dt_softplus=False, chunk_len=64, what="delta given directly")
+    c4 = dict(c)
+    c4["A"] = np.zeros_like(c["A"])
+    check_scan(m, c4, h0=h0, chunk_len=32, what="A = 0")
+    # no state requested
+    d = dev_case(c)
+    out, hf = m.mamba_scan_fwd(d["x"], d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"],
+                               d["dt_bias"], want_state=False)
+    assert hf is None
+    ro, _ = oracle_scan(c)
+    assert_close(values(to_host(out)), ro, TOL[io], "want_state=False")
+
+
+def test_scan_delta_to_zero_keeps_state(m):
+    # dt = -1e4 under softplus: delta underflows to 0, the state must come back bit for bit
+    c = synth.prefill_case(1, 40, 64, 16, 4, synth.F32, seed=9)
+    c["dt"] = np.full_like(c["dt"], -1e4)
+    h0 = np.random.default_rng(1).standard_normal((1, 64, 16)).astype(np.float32)
+    for cl in (0, 16):
+        _, hf = run_scan(m, c, h0=h0, chunk_len=cl)
+        assert np.array_equal(hf, h0)
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+def test_scan_carry_in_place_state_and_empty(m, io):
+    c = synth.prefill_case(2, 300, 64, 16, 4, io, seed=11)
+    d = dev_case(c)
+    full, hf = m.mamba_scan_fwd(d["x"], d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"], d["dt_bias"],
+                                chunk_len=300)
+    cut = lambda k, a, b: d[k][:, a:b].contiguous()
+    state = torch.zeros((2, 64, 16), dtype=torch.float32, device=DEV)
+    outs = []
+    for a, b in ((0, 130), (130, 130), (130, 300)):      # the middle piece is empty
+        o, _ = m.mamba_scan_fwd(cut("x", a, b), cut("dt", a, b), d["A"], cut("Bm", a, b), cut("Cm", a, b),
+                                d["Dskip"], cut("z", a, b), d["dt_bias"], h0=state, h_final=state,
+                                chunk_len=64)
+        outs.append(o)
+    tol = TOL[io]
+    ro, rh = oracle_scan(c)
+    assert_close(values(to_host(torch.cat(outs, 1))), ro, tol, "pieces out")
+    assert_close(to_host(state), rh, tol, "pieces state")
+    assert_close(to_host(hf), rh, tol, "full state")
+    # empty sequence into a fresh buffer copies h0
+    o, h2 = m.mamba_scan_fwd(cut("x", 0, 0), cut("dt", 0, 0), d["A"], cut("Bm", 0, 0), cut("Cm", 0, 0),
+                             d["Dskip"], cut("z", 0, 0), d["dt_bias"], h0=state)
+    assert torch.equal(h2, state) and o.shape[1] == 0
+
+
+def test_scan_is_deterministic(m):
+    c = synth.prefill_case(1, 2048, 256, 16, 4, synth.BF16, seed=5)
+    a = run_scan(m, c, chunk_len=128)
+    b = run_scan(m, c, chunk_len=128)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+# ------------------------------------------------------------------------------------ step
+def tok_slice(c, t):
+    return {k: np.ascontiguousarray(c[k][:, t]) for k in ("x", "dt", "z", "Bm", "Cm")}
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+def test_scan_equals_repeated_steps(m, io):
+    B, L, D, N = 3, 40, 128, 16
+    c = synth.prefill_case(B, L, D, N, 4, io, seed=21)
+    d = dev_case(c)
+    h = torch.zeros((B, D, N), dtype=torch.float32, device=DEV)
+    outs = []
+    for t in range(L):
+        _, o = m.mamba_state_step(h, d["x"][:, t].contiguous(), d["dt"][:, t].contiguous(), d["A"],
+                                  d["Bm"][:, t].contiguous(), d["Cm"][:, t].contiguous(), d["Dskip"],
+                                  d["z"][:, t].contiguous(), d["dt_bias"], h_out=h)       # in place
+        outs.append(o)
+    ro, rh = oracle_scan(c)
+    assert_close(values(to_host(torch.stack(outs, 1))), ro, TOL[io], "steps out")
+    assert_close(to_host(h), rh, TOL[io], "steps state")
+    so, sh = m.mamba_scan_fwd(d["x"], d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"], d["dt_bias"])
+    assert_close(values(to_host(so)), ro, TOL[io], "scan out")
+    assert_close(to_host(sh), rh, TOL[io], "scan state")
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("N", [4, 8, 16, 32])
+@pytest.mark.parametrize("D", [1, 17, 100, 1536])
+def test_step_against_oracle(m, io, N, D):
+    say(io=io, N=N, D=D)
+    n_in, n_out = 5, 11
+    rng = np.random.default_rng(N * 100 + D)
+    p = synth.layer_params(rng, D, N, 4, random_A=True)
+    tok = synth.token_inputs(rng, (n_out,), D, N, io)
+    h_in = rng.standard_normal((n_in, D, N)).astype(np.float32)
+    parent = rng.integers(0, n_in, n_out).astype(np.int32)
+    for gate, skip in ((True, True), (False, False)):
+        ho, o = m.mamba_state_step(to_dev(h_in), to_dev(tok["x"]), to_dev(tok["dt"]), to_dev(p["A"]),
+                                   to_dev(tok["Bm"]), to_dev(tok["Cm"]),
+                                   to_dev(p["Dskip"]) if skip else None,
+                                   to_dev(tok["z"]) if gate else None, to_dev(p["dt_bias"]),
+                                   parent_idx=to_dev(parent))
+        rh, ro = oracle.state_step(W(h_in), W(tok["x"]), W(tok["dt"]), W(p["A"]), W(tok["Bm"]), W(tok["Cm"]),
+                                   W(p["Dskip"]) if skip else None, W(tok["z"]) if gate else None,
+                                   W(p["dt_bias"]), parent)
+        assert_close(to_host(ho), rh, TOL[io], "step h")
+        assert_close(values(to_host(o)), ro, TOL[io], "step out")
+
+
+def test_step_rejects_out_of_range_parent_without_reading(m):
+    D, N = 64, 16
+    rng = np.random.default_rng(0)
+    p = synth.layer_params(rng, D, N, 4)
+    tok = synth.token_inputs(rng, (3,), D, N, synth.F32)
+    h_in = to_dev(rng.standard_normal((2, D, N)).astype(np.float32))
+    parent = to_dev(np.array([1, 2, -1], dtype=np.int32))          # 2 and -1 are out of range
+    ho, o = m.mamba_state_step(h_in, to_dev(tok["x"]), to_dev(tok["dt"]), to_dev(p["A"]), to_dev(tok["Bm"]),
+                               to_dev(tok["Cm"]), parent_idx=parent)
+    assert torch.isfinite(ho[0]).all() and torch.isfinite(o[0]).all()
+    assert torch.isnan(ho[1:]).all() and torch.isnan(o[1:]).all()
+    cd, sd = m.mamba_state_fork(None, h_in.unsqueeze(0), parent)
+    assert cd is None and torch.equal(sd[0, 0], h_in[1])
+    assert (sd[0, 1:].view(torch.int32) == -1).all()               # 0xFF fill
+
+
+# ------------------------------------------------------------------------------------ fork
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("D,N,K", [(1536, 16, 4), (17, 4, 2), (5, 8, 4), (100, 32, 3), (3, 4, 2)])
+def test_fork_is_bit_exact(m, io, D, N, K):
+    say(io=io, D=D, N=N, K=K)
+    rng = np.random.default_rng(D + N + K)
+    nl, n_in, n_out = 3, 6, 13
+    ssm = rng.standard_normal((nl, n_in, D, N)).astype(np.float32)
+    ssm.view(np.uint32)[0, 0, 0, 0] = 0x7FC12345                   # a NaN payload must survive
+    conv = synth.to_io(rng.standard_normal((nl, n_in, D, K - 1)).astype(np.float32), io)
+    parent = rng.integers(0, n_in, n_out).astype(np.int32)
+    parent[0] = 0
+    cd, sd = m.mamba_state_fork(to_dev(conv), to_dev(ssm), to_dev(parent))
+    rc, rs = oracle.state_fork(conv, ssm, parent)
+    assert to_host(cd).tobytes() == rc.tobytes()
+    assert to_host(sd).tobytes() == rs.tobytes()
+    c_only, none = m.mamba_state_fork(to_dev(conv), None, to_dev(parent))
+    assert none is None and to_host(c_only).tobytes() == rc.tobytes()
+    none, s_only = m.mamba_state_fork(None, to_dev(ssm), to_dev(parent))
+    assert none is None and to_host(s_only).tobytes() == rs.tobytes()
+
+
+def test_fork_paper_trees(m):
+    # trees printed in the paper; children of node p sit at p*N_i .. p*N_i + N_i - 1
+    D, N, K = 64, 16, 4
+    rng = np.random.default_rng(12)
+    for tree in ((3, 3, 2, 1), (3, 2, 2, 1, 1), (2, 2, 2, 1, 1, 1), (1, 1, 1, 1, 1)):
+        ssm = to_dev(rng.standard_normal((2, 1, D, N)).astype(np.float32))
+        conv = to_dev(synth.to_io(rng.standard_normal((2, 1, D, K - 1)).astype(np.float32), synth.BF16))
+        root_s, root_c = ssm.clone(), conv.clone()
+        for b_i, par in zip(synth.tree_batch_sizes(tree), synth.tree_parents(tree)):
+            conv, ssm = m.mamba_state_fork(conv, ssm, to_dev(par))
+            assert ssm.shape[1] == b_i and conv.shape[1] == b_i
+        assert torch.equal(ssm, root_s.expand_as(ssm)) and torch.equal(conv, root_c.expand_as(conv))
+
+
+# ------------------------------------------------------------------------------------ configs
+def test_cfg0_conv_scan_and_256_steps(m):
+    c = synth.config_prefill("cfg0")
+    check_conv(m, c)
+    e = check_scan(m, c)
+    say(scan_err=e)
+    d = dev_case(c)
+    B, L, D, N = c["batch"], c["L"], c["D"], c["N"]
+    h = torch.zeros((B, D, N), dtype=torch.float32, device=DEV)
+    outs = []
+    for t in range(L):
+        _, o = m.mamba_state_step(h, d["x"][:, t].contiguous(), d["dt"][:, t].contiguous(), d["A"],
+                                  d["Bm"][:, t].contiguous(), d["Cm"][:, t].contiguous(), d["Dskip"],
+                                  d["z"][:, t].contiguous(), d["dt_bias"], h_out=h)
+        outs.append(o)
+    ro, rh = oracle_scan(c)
+    assert_close(to_host(torch.stack(outs, 1)), ro, TOL[synth.F32], "256 steps out")
+    assert_close(to_host(h), rh, TOL[synth.F32], "256 steps state")
+
+
+def test_cfg0_chained_conv_then_scan(m):
+    # conv output feeds the scan's x on both sides; each side runs its own chain
+    c = synth.config_prefill("cfg0")
+    d = dev_case(c)
+    xc, _ = m.mamba_conv1d_fwd(d["x"], d["conv_w"], d["conv_bias"])
+    out, hf = m.mamba_scan_fwd(xc, d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"], d["dt_bias"])
+    rxc, _ = oracle.conv1d_fwd(W(c["x"]), W(c["conv_w"]), W(c["conv_bias"]))
+    ro, rh = oracle.scan_fwd(rxc, W(c["dt"]), W(c["A"]), W(c["Bm"]), W(c["Cm"]), W(c["Dskip"]), W(c["z"]),
+                             W(c["dt_bias"]))
+    assert_close(to_host(out), ro, TOL[synth.F32], "chain out")
+    assert_close(to_host(hf), rh, TOL[synth.F32], "chain state")
+
+
+def test_cfg1_prefill_bf16(m):
+    c = synth.config_prefill("cfg1")
+    check_conv(m, c)
+    e = check_scan(m, c)
+    say(scan_err=e)
+
+
+def sample_channels(D, n, seed):
+    idx = np.sort(np.random.default_rng(seed).choice(D, size=n, replace=False))
+    idx[0], idx[-1] = 0, D - 1
+    return idx
+
+
+def test_cfg3_long_prefill_sampled_channels(m):
+    # full size on the GPU in the chunking the library picks; the oracle walks 48 sampled channels
+    c = synth.config_prefill("cfg3")
+    idx = sample_channels(c["D"], 48, 33)
+    y, st = run_conv(m, c)
+    ry, rst = oracle.conv1d_fwd(W(c["x"][..., idx]), W(c["conv_w"][idx]), W(c["conv_bias"][idx]))
+    assert_close(values(y[..., idx]), ry, TOL[c["io"]], "cfg3 conv")
+    assert np.array_equal(values(st[:, idx]), rst)
+    out, hf = run_scan(m, c)
+    ro, rh = oracle_scan(c, channels=idx)
+    e1 = assert_close(values(out[..., idx]), ro, TOL[c["io"]], "cfg3 scan out")
+    e2 = assert_close(hf[:, idx], rh, TOL[c["io"]], "cfg3 scan state")
+    say(scan_err=(e1, e2))
+    assert m.mamba_scan_workspace_bytes(c["batch"], c["L"], c["D"], c["N"]) > 0   # it was chunked
+
+
+def decode_chain_gpu(m, dc, fused):
+    """fork -> conv step -> state step for every layer and draft step; returns final states and
+    all step outputs."""
+    nl, nb = dc["n_layers"], dc["branches"]
+    ssm = to_dev(dc["ssm0"])
+    conv = to_dev(dc["conv0"])
+    P = [{k: to_dev(v) for k, v in p.items()} for p in dc["params"]]
+    outs = []
+    for s in range(dc["steps"]):
+        par = to_dev(dc["parents"][s])
+        if fused:
+            conv, _ = m.mamba_state_fork(conv, None, par)
+            ssm_next = torch.empty_like(ssm)
+        else:
+            conv, ssm = m.mamba_state_fork(conv, ssm, par)
+        for l in range(nl):
+            tok = {k: to_dev(v) for k, v in dc["tokens"][s][l].items()}
+            xc, _ = m.mamba_conv1d_fwd(tok["x"].unsqueeze(1), P[l]["conv_w"], P[l]["conv_bias"],
+                                       conv_state_in=conv[l], conv_state_out=conv[l])
+            xc = xc.squeeze(1)
+            if fused:
+                _, o = m.mamba_state_step(ssm[l], xc, tok["dt"], P[l]["A"], tok["Bm"], tok["Cm"],
+                                          P[l]["Dskip"], tok["z"], P[l]["dt_bias"], parent_idx=par,
+                                          h_out=ssm_next[l])
+            else:
+                _, o = m.mamba_state_step(ssm[l], xc, tok["dt"], P[l]["A"], tok["Bm"], tok["Cm"],
+                                          P[l]["Dskip"], tok["z"], P[l]["dt_bias"], h_out=ssm[l])
+            outs.append(o)
+        if fused:
+            ssm = ssm_next
+    return conv, ssm, torch.stack(outs)
+
+
+def decode_chain_oracle(dc, layers):
+    io = dc["io"]
+    ssm = dc["ssm0"][layers].astype(np.float64)
+    conv = dc["conv0"][layers]
+    outs = []
+    for s in range(dc["steps"]):
+        par = dc["parents"][s]
+        conv, ssm = oracle.state_fork(conv, ssm, par)
+        conv = conv.copy()
+        for i, l in enumerate(layers):
+            p, tok = dc["params"][l], dc["tokens"][s][l]
+            xc, cst = oracle.conv1d_fwd(W(tok["x"])[:, None, :], W(p["conv_w"]), W(p["conv_bias"]), W(conv[i]))
+            conv[i] = synth.to_io(cst.astype(np.float32), io)          # exact: copies of inputs
+            xc_io = W(synth.to_io(xc[:, 0].astype(np.float32), io))    # the next stage reads the I/O dtype
+            ssm[i], o = oracle.state_step(ssm[i], xc_io, W(tok["dt"]), W(p["A"]), W(tok["Bm"]), W(tok["Cm"]),
+                                          W(p["Dskip"]), W(tok["z"]), W(p["dt_bias"]))
+            outs.append(o)
+    return conv, ssm, outs
+
+
+def test_cfg2_tree_decode_fused_and_unfused(m):
+    dc = synth.config_decode("cfg2")
+    say(layers=dc["n_layers"], branches=dc["branches"], steps=dc["steps"])
+    conv_u, ssm_u, out_u = decode_chain_gpu(m, dc, fused=False)
+    conv_f, ssm_f, out_f = decode_chain_gpu(m, dc, fused=True)
+    # fusing the gather into the step changes no bit
+    assert torch.equal(ssm_u, ssm_f) and torch.equal(conv_u, conv_f) and torch.equal(out_u, out_f)
+    layers = [0, 7, 23]
+    rconv, rssm, routs = decode_chain_oracle(dc, layers)
+    nl = dc["n_layers"]
+    tol = TOL[dc["io"]]
+    for i, l in enumerate(layers):
+        assert to_host(conv_u[l]).tobytes() == rconv[i].tobytes()
+        assert_close(to_host(ssm_u[l]), rssm[i], tol, "cfg2 ssm layer %d" % l)
+        for s in range(dc["steps"]):
+            assert_close(values(to_host(out_u[s * nl + l])), routs[s * len(layers) + i], tol,
+                         "cfg2 out step %d layer %d" % (s, l))
+
+
+def test_cfg4_wide_prefill_and_decode_sampled(m):
+    cfg = synth.CONFIGS["cfg4"]
+    B, L, D, N, K = cfg["batch"], cfg["L"], cfg["D"], cfg["N"], cfg["K"]
+    say(B=B, L=L, D=D)
+    c = synth.config_prefill("cfg4")
+    idx = sample_channels(D, 24, 44)
+    d = dev_case(c)
+    y, st = m.mamba_conv1d_fwd(d["x"], d["conv_w"], d["conv_bias"])
+    ry, rst = oracle.conv1d_fwd(W(c["x"][..., idx]), W(c["conv_w"][idx]), W(c["conv_bias"][idx]))
+    assert_close(values(to_host(y[..., idx].contiguous())), ry, TOL[c["io"]], "cfg4 conv")
+    assert np.array_equal(values(to_host(st[:, idx].contiguous())), rst)
+    del y
+    out, hf = m.mamba_scan_fwd(d["x"], d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"], d["dt_bias"])
+    ro, rh = oracle_scan(c, channels=idx)
+    e1 = assert_close(values(to_host(out[..., idx].contiguous())), ro, TOL[c["io"]], "cfg4 scan out")
+    e2 = assert_close(to_host(hf[:, idx].contiguous()), rh, TOL[c["io"]], "cfg4 scan state")
+    say(scan_err=(e1, e2))
+    del out, d, c
+    torch.cuda.empty_cache()
+    dc = synth.config_decode("cfg4", n_layers=1)
+    conv_u, ssm_u, out_u = decode_chain_gpu(m, dc, fused=False)
+    conv_f, ssm_f, out_f = decode_chain_gpu(m, dc, fused=True)
+    assert torch.equal(ssm_u, ssm_f) and torch.equal(out_u, out_f)
+    rconv, rssm, routs = decode_chain_oracle(dc, [0])
+    assert to_host(conv_u[0]).tobytes() == rconv[0].tobytes()
+    assert_close(to_host(ssm_u[0]), rssm[0], TOL[dc["io"]], "cfg4 decode ssm")
+    for s in range(dc["steps"]):
+        assert_close(values(to_host(out_u[s])), routs[s], TOL[dc["io"]], "cfg4 decode out %d" % s)
