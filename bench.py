@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run three plain 1 GiB device copies: the known-size "
+                         "reference that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     ap.add_argument("--prefill", default="cfg3", help="synthetic config of the prefill leg")
     ap.add_argument("--decode", default="cfg2", help="synthetic config of the decode leg")
     args = ap.parse_args()
@@ -153,6 +156,14 @@ def main():
     scan_ms = sum(a.elapsed_time(b) for a, b in scan_ev) / args.steps
     conv_ms = sum(a.elapsed_time(b) for a, b in conv_ev) / args.steps
     dec_ms = sum(a.elapsed_time(b) for a, b in dec_ev) / args.steps
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     tokens = B * L
     sb = scan_bytes(B, L, D, N, e)

@@ -26,21 +26,27 @@ if not os.path.exists(LIB_PATH):
         "libmamba_hip.so is missing: build it with `python -m paper_2506_01206_amd.build` "
         "(there is no CPU or PyTorch fallback for the kernels)")
 
-lib = ctypes.CDLL(LIB_PATH)
-
 _vp, _i64, _int, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
-lib.mamba_status_string.argtypes = [_int]
-lib.mamba_status_string.restype = ctypes.c_char_p
-lib.mamba_conv1d_fwd.argtypes = [_vp] * 6 + [_i64, _i64, _i64, _int, _int, _int, _vp]
-lib.mamba_conv1d_fwd.restype = _int
-lib.mamba_scan_workspace_bytes.argtypes = [_i64] * 5
-lib.mamba_scan_workspace_bytes.restype = _sz
-lib.mamba_scan_fwd.argtypes = [_vp] * 12 + [_sz] + [_i64] * 5 + [_int, _int, _vp]
-lib.mamba_scan_fwd.restype = _int
-lib.mamba_state_step.argtypes = [_vp] * 12 + [_i64] * 4 + [_int, _int, _vp]
-lib.mamba_state_step.restype = _int
-lib.mamba_state_fork.argtypes = [_vp] * 5 + [_i64] * 5 + [_int, _int, _vp]
-lib.mamba_state_fork.restype = _int
+
+
+def _declare(lib):
+    """Attach the C signatures of include/mamba_hip.h to a loaded library."""
+    lib.mamba_status_string.argtypes = [_int]
+    lib.mamba_status_string.restype = ctypes.c_char_p
+    lib.mamba_conv1d_fwd.argtypes = [_vp] * 6 + [_i64, _i64, _i64, _int, _int, _int, _vp]
+    lib.mamba_conv1d_fwd.restype = _int
+    lib.mamba_scan_workspace_bytes.argtypes = [_i64] * 5
+    lib.mamba_scan_workspace_bytes.restype = _sz
+    lib.mamba_scan_fwd.argtypes = [_vp] * 12 + [_sz] + [_i64] * 5 + [_int, _int, _vp]
+    lib.mamba_scan_fwd.restype = _int
+    lib.mamba_state_step.argtypes = [_vp] * 12 + [_i64] * 4 + [_int, _int, _vp]
+    lib.mamba_state_step.restype = _int
+    lib.mamba_state_fork.argtypes = [_vp] * 5 + [_i64] * 5 + [_int, _int, _vp]
+    lib.mamba_state_fork.restype = _int
+    return lib
+
+
+lib = _declare(ctypes.CDLL(LIB_PATH))
 
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
            "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork")

@@ -25,7 +25,10 @@ namespace mamba {
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kTile = 4;  // time steps whose token loads are issued together, one tile ahead
+#ifndef MAMBA_SCAN_TILE
+#define MAMBA_SCAN_TILE 4
+#endif
+constexpr int kTile = MAMBA_SCAN_TILE;  // time steps whose token loads are issued together, one tile ahead
 
 template <typename T, int CPL> struct RawT;
 template <> struct RawT<float, 1> { typedef float type; };
@@ -55,20 +58,29 @@ template <int CPL> __device__ __forceinline__ void st_pack(bf16_t *p, const floa
     else *reinterpret_cast<uint32_t *>(p) = f32x2_to_bf16x2(v[0], v[1]);
 }
 
-// B_t or C_t: N values at a wave-uniform address.
-template <int N> __device__ __forceinline__ void ld_uniform(const float *p, float *f)
+// B_t or C_t: N values at a wave-uniform address, fetched as raw dwords (scalar loads) one time
+// step ahead of their use and unpacked to float32 when the step runs.
+template <typename T, int N> struct RawVec { uint32_t w[N * sizeof(T) / 4]; };
+
+template <typename T, int N> __device__ __forceinline__ RawVec<T, N> ld_uniform(const T *p)
 {
-#pragma unroll
-    for (int n = 0; n < N; ++n) f[n] = p[n];
-}
-template <int N> __device__ __forceinline__ void ld_uniform(const bf16_t *p, float *f)
-{
+    RawVec<T, N> r;
     const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
 #pragma unroll
+    for (int i = 0; i < (int)(N * sizeof(T) / 4); ++i) r.w[i] = q[i];
+    return r;
+}
+template <int N> __device__ __forceinline__ void unpack_uniform(const RawVec<float, N> &r, float *f)
+{
+#pragma unroll
+    for (int n = 0; n < N; ++n) f[n] = __uint_as_float(r.w[n]);
+}
+template <int N> __device__ __forceinline__ void unpack_uniform(const RawVec<bf16_t, N> &r, float *f)
+{
+#pragma unroll
     for (int i = 0; i < N / 2; ++i) {
-        const uint32_t r = q[i];
-        f[2 * i] = bf16_lo(r);
-        f[2 * i + 1] = bf16_hi(r);
+        f[2 * i] = bf16_lo(r.w[i]);
+        f[2 * i + 1] = bf16_hi(r.w[i]);
     }
 }
 
@@ -165,10 +177,16 @@ scan_chunk_out(const T *__restrict__ x, const T *__restrict__ dt, const float *_
     }
 
     const int64_t row0 = b * L;
+    RawVec<T, N> braw = ld_uniform<T, N>(Bm + (row0 + t0) * N);
+    RawVec<T, N> craw = ld_uniform<T, N>(Cm + (row0 + t0) * N);
     auto step = [&](int64_t t, raw_t xr, raw_t dr, raw_t zr) {
         float bf[N], cf[N];
-        ld_uniform<N>(Bm + (row0 + t) * N, bf);
-        ld_uniform<N>(Cm + (row0 + t) * N, cf);
+        unpack_uniform<N>(braw, bf);
+        unpack_uniform<N>(craw, cf);
+        const int64_t tn = (t + 1 < t1) ? t + 1 : t;  // next step's B, C (a harmless re-read at the end)
+        braw = ld_uniform<T, N>(Bm + (row0 + tn) * N);
+        craw = ld_uniform<T, N>(Cm + (row0 + tn) * N);
+        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of this step's arithmetic
         float xv[CPL], dv[CPL], zv[CPL], ov[CPL];
         unpack(xr, xv);
         unpack(dr, dv);
@@ -258,9 +276,13 @@ scan_chunk_state(const T *__restrict__ x, const T *__restrict__ dt, const float 
     }
 
     const int64_t row0 = b * L;
+    RawVec<T, N> braw = ld_uniform<T, N>(Bm + (row0 + t0) * N);
     auto step = [&](int64_t t, raw_t xr, raw_t dr) {
         float bf[N];
-        ld_uniform<N>(Bm + (row0 + t) * N, bf);
+        unpack_uniform<N>(braw, bf);
+        const int64_t tn = (t + 1 < t1) ? t + 1 : t;
+        braw = ld_uniform<T, N>(Bm + (row0 + tn) * N);
+        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of this step's arithmetic
         float xv[CPL], dv[CPL];
         unpack(xr, xv);
         unpack(dr, dv);
@@ -408,7 +430,9 @@ template <typename T, int N>
 hipError_t launch_scan_n(const ScanArgs &a, hipStream_t stream)
 {
     // two channels per lane need even D so that every row keeps the pair's alignment
+#ifndef MAMBA_SCAN_FORCE_CPL1
     if (a.D % 2 == 0) return launch_scan_t<T, N, 2>(a, stream);
+#endif
     return launch_scan_t<T, N, 1>(a, stream);
 }
 
@@ -441,17 +465,22 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
     if (chunk_len_req > 0) {
         cl = chunk_len_req;
     } else {
+#ifndef MAMBA_SCAN_FORCE_CPL1
         const int64_t cpl = (D % 2 == 0) ? 2 : 1;
+#else
+        const int64_t cpl = 1;
+#endif
         const int64_t columns = batch * ((D + kWave * cpl - 1) / (kWave * cpl));
-        const int64_t target_waves = 2048;
-        const int64_t min_chunk = 64;
-        int64_t want = (target_waves + columns - 1) / columns;
-        if (columns >= 640) want = 1;
-        const int64_t max_chunks = (L + min_chunk - 1) / min_chunk;
-        if (want > max_chunks) want = max_chunks;
-        if (want < 1) want = 1;
-        cl = (L + want - 1) / want;
-        cl = (cl + kTile - 1) / kTile * kTile;
+        const int64_t target_waves = 3072;  // 3 resident wavefronts on each of 1024 SIMDs
+        if (columns >= target_waves) {
+            cl = L;
+        } else {
+            const int64_t want = (target_waves + columns - 1) / columns;
+            cl = (L + want - 1) / want;
+            if (cl > 256) cl = 256;  // short chunks balance better across the chip
+            if (cl < 64) cl = 64;    // and long enough to amortize the chunk prologue and carry
+            cl = (cl + kTile - 1) / kTile * kTile;
+        }
     }
     if (cl > L) cl = L;
     *chunk_len = cl;

@@ -101,7 +101,7 @@ def test_scan_workspace_query(b):
     n_chunks = a // (1536 * 17 * 4)
     assert 2 <= n_chunks <= 32768 // 64
     # a batch-rich shape fills the chip without cutting time
-    assert w(64, 4096, 4096, 16, 0) == 0
+    assert w(128, 4096, 4096, 16, 0) == 0
 
 
 def conv(b, x=P(0), w=P(1), bias=P(2), si=P(3), y=P(4), so=P(5), batch=2, L=100, D=64, K=4,
