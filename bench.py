@@ -6,13 +6,17 @@ One "step" is one pass of the whole hot path over one batch of synthetic input:
            L = 32768 tokens, bf16 I/O, fp32 state), then
   decode   tree drafting over 24 such layers: 5 draft steps of 32 live branches; per draft step
            one conv-state fork for all layers, and per layer a conv step and a state step with
-           the SSM-state fork fused in (parent index).
+           the SSM-state fork fused in (parent index).  The 245 launches are captured once in a
+           HIP graph (every call has a fixed shape, which is what makes the paper's per-batch-size
+           graph cache possible, Sec. 4.1) and replayed; --eager-decode launches them one by one.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-The roofline object covers the dominant call, the selective scan: algorithmic bytes per launch
-(x, dt, z, out, B, C; nothing else) over its average duration, measured with HIP events on the
-launch stream inside the timed region, against the 8 TB/s HBM peak.  The oracle (fp64, CPU) is
-timed on the same prefill for cpu_baseline.
+The roofline object covers the dominant call, the selective scan (its three kernels together),
+timed with HIP events on the launch stream inside the timed region.  The scan is bound by the
+vector ALUs (one hardware exp2 and four VALU operations per state update, two walks over the
+tokens because a batch-1 sequence must be cut in time), so the object reports fp32 operations
+per second against the fp32 vector peak, and the algorithmic HBM bytes per second against the
+8 TB/s peak beside it.  The oracle (fp64, CPU) is timed on the same prefill for cpu_baseline.
 """
 import argparse
 import json
@@ -25,7 +29,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
-FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (needs packed fp32)
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published: 256 CUs x 128 FMA lanes x 2 x 2.4 GHz
+
+# HBM bytes per scan launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE summed over the scan's
+# three kernels, each scaled by what the same counter reads for the 1 GiB copy below; figures and
+# commands in profiles/).  Keyed by workload; None for a workload that has not been profiled.
+SCAN_TRAFFIC_BYTES = {("cfg3", 1, 32768, 1536, 16): 792_000_000}
 
 
 def scan_bytes(B, L, D, N, e):
@@ -44,9 +53,10 @@ def step_bytes(nb, D, N, e):
 
 
 def scan_flops(B, L, D, N):
-    """fp32 operations of the scan as defined: per state update delta*A, exp, (delta x)*B, fma, fma
-    = 7; per (token, channel) softplus, skip, gate and products ~ 16."""
-    return B * L * D * (7 * N + 16)
+    """fp32 operations of the scan as it is defined (one walk over the tokens): per state update
+    delta*A, exp, (delta x)*B, fma, fma = 7 (an fma counts 2, exp counts 1); per (token, channel)
+    softplus 6 (add, mul, exp, add, log, mul), delta*x 1, skip fma 2, silu 5, gate 1 = 15."""
+    return B * L * D * (7 * N + 15)
 
 
 def main():
@@ -55,9 +65,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="after the timed region, run three plain 1 GiB device copies: the known-size "
-                         "reference that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
+    ap.add_argument("--eager-decode", action="store_true",
+                    help="launch the decode kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--prefill", default="cfg3", help="synthetic config of the prefill leg")
     ap.add_argument("--decode", default="cfg2", help="synthetic config of the decode leg")
     args = ap.parse_args()
@@ -103,31 +112,55 @@ def main():
     LP = [{k: to_dev(v) for k, v in p.items()} for p in dc["params"]]
     TOK = [[{k: to_dev(v) for k, v in t.items()} for t in layer] for layer in dc["tokens"]]
     PAR = [to_dev(p) for p in dc["parents"]]
-    ssm = [to_dev(dc["ssm0"]), torch.empty((nl, nb, Dd, Nd), dtype=torch.float32, device=dev)]
-    conv = [to_dev(dc["conv0"]), torch.empty_like(to_dev(dc["conv0"]))]
-    dxc = torch.empty((nb, 1, Dd), dtype=conv[0].dtype, device=dev)
-    dout = torch.empty((nb, Dd), dtype=conv[0].dtype, device=dev)
+    # state caches: the initial states are only read; the draft steps ping-pong between two more
+    ssm0, conv0 = to_dev(dc["ssm0"]), to_dev(dc["conv0"])
+    ssm = [torch.empty_like(ssm0), torch.empty_like(ssm0)]
+    conv = [torch.empty_like(conv0), torch.empty_like(conv0)]
+    dxc = torch.empty((nb, 1, Dd), dtype=conv0.dtype, device=dev)
+    dout = torch.empty((nsteps, nl, nb, Dd), dtype=conv0.dtype, device=dev)
 
     def prefill():
         m.mamba_conv1d_fwd(P["x"], P["conv_w"], P["conv_bias"], None, y=xc, conv_state_out=conv_state)
         m.mamba_scan_fwd(xc, P["dt"], P["A"], P["Bm"], P["Cm"], P["Dskip"], P["z"], P["dt_bias"],
                          out=out, h_final=h_final, workspace=ws)
 
-    def decode():
-        cur = 0
+    def decode_eager():
+        src_ssm, src_conv = ssm0, conv0
         for s in range(nsteps):
-            nxt = 1 - cur
-            m.mamba_state_fork(conv[cur], None, PAR[s], conv_dst=conv[nxt])
+            dst_ssm, dst_conv = ssm[s & 1], conv[s & 1]
+            m.mamba_state_fork(src_conv, None, PAR[s], conv_dst=dst_conv)
             for l in range(nl):
                 t = TOK[s][l]
                 m.mamba_conv1d_fwd(t["x"].unsqueeze(1), LP[l]["conv_w"], LP[l]["conv_bias"],
-                                   conv_state_in=conv[nxt][l], y=dxc, conv_state_out=conv[nxt][l])
-                m.mamba_state_step(ssm[cur][l], dxc.squeeze(1), t["dt"], LP[l]["A"], t["Bm"], t["Cm"],
+                                   conv_state_in=dst_conv[l], y=dxc, conv_state_out=dst_conv[l])
+                m.mamba_state_step(src_ssm[l], dxc.squeeze(1), t["dt"], LP[l]["A"], t["Bm"], t["Cm"],
                                    LP[l]["Dskip"], t["z"], LP[l]["dt_bias"], parent_idx=PAR[s],
-                                   h_out=ssm[nxt][l], out=dout)
-            cur = nxt
+                                   h_out=dst_ssm[l], out=dout[s, l])
+            src_ssm, src_conv = dst_ssm, dst_conv
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
+    prefill()
+    decode_eager()
+    torch.cuda.synchronize()
+    decode = decode_eager
+    if not args.eager_decode:
+        ref_out, ref_ssm = dout.clone(), ssm[(nsteps - 1) & 1].clone()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                decode_eager()
+        torch.cuda.current_stream().wait_stream(side)
+        decode = graph.replay
+        # the replay must reproduce the eager result bit for bit, also after other work ran
+        for _ in range(2):
+            dout.zero_()
+            prefill()
+            decode()
+            torch.cuda.synchronize()
+            assert torch.equal(dout, ref_out) and torch.equal(ssm[(nsteps - 1) & 1], ref_ssm), \
+                "HIP graph replay of the decode loop differs from the eager launches"
     for _ in range(args.warmup):
         prefill()
         decode()
@@ -157,25 +190,33 @@ def main():
     conv_ms = sum(a.elapsed_time(b) for a, b in conv_ev) / args.steps
     dec_ms = sum(a.elapsed_time(b) for a, b in dec_ev) / args.steps
 
-    if args.calibrate_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    # plain device copy of 1 GiB (read 1 GiB + write 1 GiB): the practical streaming ceiling of this
+    # box, and the known-size reference the FETCH_SIZE / WRITE_SIZE counters are scaled by
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    c0, c1 = ev(), ev()
+    c0.record()
+    for _ in range(3):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 3 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
 
     tokens = B * L
     sb = scan_bytes(B, L, D, N, e)
     achieved = sb / (scan_ms * 1e-3) / 1e9
+    tflops = scan_flops(B, L, D, N) / (scan_ms * 1e-3) / 1e12
     roofline = {
         "kernel": "mamba_scan_fwd (scan_chunk_state + scan_carry + scan_chunk_out)",
-        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-        "algorithmic_bytes_per_launch": sb, "avg_launch_ms": round(scan_ms, 5),
-        "alu": {"achieved_tflops": round(scan_flops(B, L, D, N) / (scan_ms * 1e-3) / 1e12, 2),
-                "peak_tflops": FP32_VECTOR_PEAK_TFLOPS,
-                "frac": round(scan_flops(B, L, D, N) / (scan_ms * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, 4)},
+        "bound": "alu", "achieved": round(tflops, 2), "peak": FP32_VECTOR_PEAK_TFLOPS,
+        "unit": "TFLOP/s", "frac": round(tflops / FP32_VECTOR_PEAK_TFLOPS, 4),
+        "traffic": SCAN_TRAFFIC_BYTES.get((args.prefill, B, L, D, N)),
+        "algorithmic_flops_per_launch": scan_flops(B, L, D, N), "avg_launch_ms": round(scan_ms, 5),
+        "hbm": {"achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_launch": sb,
+                "frac_of_copy_kernel": round(achieved / copy_gbs, 4)},
     }
     units = nb * nsteps * nl
     dec_bytes = nsteps * nl * (step_bytes(nb, Dd, Nd, ed) + nb * (2 * Dd * (Kd - 1) * ed + 2 * Dd * ed)) \
@@ -188,7 +229,8 @@ def main():
         "decode_ms": round(dec_ms, 5),
         "decode_branch_steps_per_s_per_layer": round(units / (dec_ms * 1e-3), 1),
         "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
-        "decode_launches": nsteps * (1 + 2 * nl),
+        "decode_launches": nsteps * (1 + 2 * nl), "decode_mode": "eager" if args.eager_decode else "hip_graph",
+        "copy_kernel_GBps": round(copy_gbs, 1),
     }
 
     result = {
@@ -209,15 +251,19 @@ def main():
         W = lambda a: oracle.widen(a, bf16=(a.dtype == np.uint16))
         ox = {k: W(case[k]) for k in ("x", "z", "Bm", "Cm", "dt", "A", "Dskip", "dt_bias", "conv_w",
                                       "conv_bias")}
+        reps = 3
         c0 = time.perf_counter()
-        rxc, _ = oracle.conv1d_fwd(ox["x"], ox["conv_w"], ox["conv_bias"])
-        oracle.scan_fwd(rxc, ox["dt"], ox["A"], ox["Bm"], ox["Cm"], ox["Dskip"], ox["z"], ox["dt_bias"])
+        for _ in range(reps):
+            rxc, _ = oracle.conv1d_fwd(ox["x"], ox["conv_w"], ox["conv_bias"])
+            oracle.scan_fwd(rxc, ox["dt"], ox["A"], ox["Bm"], ox["Cm"], ox["Dskip"], ox["z"], ox["dt_bias"])
         c1 = time.perf_counter()
+        sec = (c1 - c0) / reps
         result["cpu_baseline"] = {
-            "value": round(tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "value": round(tokens / sec, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
             "kind": "oracle",
-            "sample": "%s prefill leg only (conv1d + scan, all %d channels, %d tokens), fp64, one run, "
-                      "%.1f s" % (args.prefill, D, tokens, c1 - c0)}
+            "sample": "%s prefill leg only (conv1d + scan, all %d channels, %d tokens), fp64, mean of "
+                      "%d runs of %.2f s wall (%.0f core-seconds in all)"
+                      % (args.prefill, D, tokens, reps, sec, reps * sec * oracle.num_threads())}
     print(json.dumps(result))
 
 

@@ -8,15 +8,21 @@
 // HBM-bound: 2 elements moved per output.  A lane owns VEC adjacent channels (16 bytes of a token
 // row), walks a tile of consecutive tokens and keeps the K-1 previous rows in registers, so every
 // input element is read once (plus K-1 halo rows per tile) and every wavefront access is a
-// contiguous run.  Loads of the next four rows are issued before the current four are used.
+// contiguous run.  Loads of the next group of rows are issued before the current group is used.
 #include "device_math.h"
 #include "launch.h"
 
 namespace mamba {
 namespace {
 
+#ifndef MAMBA_CONV_ROWS
+#define MAMBA_CONV_ROWS 8
+#endif
+#ifndef MAMBA_CONV_TILE
+#define MAMBA_CONV_TILE 32
+#endif
 constexpr int kBlock = 64;
-constexpr int kRows = 4;  // rows loaded together, one group ahead
+constexpr int kRows = MAMBA_CONV_ROWS;  // rows loaded together, one group ahead
 
 template <typename T, int VEC> struct RowVec;
 template <> struct RowVec<float, 4> { typedef float4 type; };
@@ -141,7 +147,7 @@ template <typename T, int VEC, int K> hipError_t launch_conv_k(const ConvArgs &a
     const unsigned gx = (unsigned)((vecs + kBlock - 1) / kBlock);
     // Time tiles: enough workgroups to fill the chip, long enough to amortize the K-1 halo rows.
     // An in-place state update keeps one tile so that a thread reads the state before it writes it.
-    int64_t tile_len = 64;
+    int64_t tile_len = MAMBA_CONV_TILE;
     if (a.state_out && a.state_in == a.state_out) tile_len = a.L;
     if ((a.L + tile_len - 1) / tile_len > 65535) tile_len = (a.L + 65534) / 65535;
     if (tile_len < 1) tile_len = 1;

@@ -6,9 +6,10 @@
 //
 // Mapping.  One wavefront per workgroup; a lane owns CPL adjacent channels and keeps their
 // CPL x N float32 states (and A * log2 e) in VGPRs for the whole time range it walks.  B_t and
-// C_t are the same for all channels of a batch row, so their addresses are wave-uniform and
-// they travel through scalar loads into SGPRs.  The recurrence is elementwise: 4 VALU
-// operations and one hardware exp2 per state update, no matrix product anywhere.
+// C_t are the same for all channels of a batch row: they are staged through LDS as float32 and
+// read back with wave-uniform (broadcast) loads.  The recurrence is elementwise: 4 VALU
+// operations and one hardware exp2 per state update, no matrix product anywhere, and it is this
+// instruction stream (the exp2 issues at a quarter of the FMA rate), not HBM, that bounds it.
 //
 // Time chunking.  A batch row offers only D / (64 CPL) wavefronts, far fewer than the 1024
 // SIMDs of the chip, so long sequences are cut into n_chunks time chunks that run in parallel:
@@ -58,31 +59,56 @@ template <int CPL> __device__ __forceinline__ void st_pack(bf16_t *p, const floa
     else *reinterpret_cast<uint32_t *>(p) = f32x2_to_bf16x2(v[0], v[1]);
 }
 
-// B_t or C_t: N values at a wave-uniform address, fetched as raw dwords (scalar loads) one time
-// step ahead of their use and unpacked to float32 when the step runs.
-template <typename T, int N> struct RawVec { uint32_t w[N * sizeof(T) / 4]; };
+// B_t and C_t staged through LDS as float32: a tile of kBcTile time steps is fetched with
+// coalesced vector loads one tile ahead, widened once, and written to one of two LDS buffers;
+// every step then reads its N values with wave-uniform (broadcast) 16-byte LDS reads into
+// VGPRs.  Compared with scalar loads this keeps SGPR operands (which issue slower) and the
+// bf16 unpacking out of the inner loop.  NARR = 1 stages B only, 2 stages B and C.
+constexpr int kBcTile = 16;
+static_assert(kBcTile % kTile == 0, "B/C tiles must start on a token-tile boundary");
 
-template <typename T, int N> __device__ __forceinline__ RawVec<T, N> ld_uniform(const T *p)
-{
-    RawVec<T, N> r;
-    const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+template <typename T, int N, int NARR> struct BcStage {
+    static constexpr int kPerTile = kBcTile * N;                 // elements per array per tile
+    static constexpr int kPerLane = (kPerTile + kWave - 1) / kWave;
+    static constexpr int kBufFloats = NARR * kPerTile;
+    float *lds;            // [2][NARR][kBcTile][N]
+    const T *src[NARR];    // row base of this batch row
+    int64_t last;          // index of the last valid element, t1 * N - 1
+    float raw[NARR][kPerLane];
+
+    __device__ __forceinline__ void issue(int64_t tile_t0)
+    {
 #pragma unroll
-    for (int i = 0; i < (int)(N * sizeof(T) / 4); ++i) r.w[i] = q[i];
-    return r;
-}
-template <int N> __device__ __forceinline__ void unpack_uniform(const RawVec<float, N> &r, float *f)
-{
+        for (int a = 0; a < NARR; ++a)
 #pragma unroll
-    for (int n = 0; n < N; ++n) f[n] = __uint_as_float(r.w[n]);
-}
-template <int N> __device__ __forceinline__ void unpack_uniform(const RawVec<bf16_t, N> &r, float *f)
-{
-#pragma unroll
-    for (int i = 0; i < N / 2; ++i) {
-        f[2 * i] = bf16_lo(r.w[i]);
-        f[2 * i + 1] = bf16_hi(r.w[i]);
+            for (int j = 0; j < kPerLane; ++j) {
+                int64_t i = tile_t0 * N + (int)threadIdx.x + kWave * j;
+                i = i < last ? i : last;   // steps past the chunk end are never used
+                raw[a][j] = ld_io(src[a], i);
+            }
     }
-}
+    __device__ __forceinline__ void commit(int buf)
+    {
+#pragma unroll
+        for (int a = 0; a < NARR; ++a)
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                const int e = (int)threadIdx.x + kWave * j;
+                if (kPerTile % kWave == 0 || e < kPerTile) lds[buf * kBufFloats + a * kPerTile + e] = raw[a][j];
+            }
+        __syncthreads();
+    }
+    // N values of array a for step s of buffer buf
+    __device__ __forceinline__ void read(int buf, int a, int s, float *f) const
+    {
+        const float4 *p = reinterpret_cast<const float4 *>(lds + buf * kBufFloats + a * kPerTile + s * N);
+#pragma unroll
+        for (int q = 0; q < N / 4; ++q) {
+            const float4 v = p[q];
+            f[4 * q] = v.x; f[4 * q + 1] = v.y; f[4 * q + 2] = v.z; f[4 * q + 3] = v.w;
+        }
+    }
+};
 
 template <int N, int CPL> struct LaneState {
     float h[CPL][N];
@@ -144,8 +170,11 @@ __device__ __forceinline__ void store_state(const float (&h)[CPL][N], float *p)
 // ---------------------------------------------------------------------------------------
 // pass 2 (and the only pass when n_chunks == 1): full recurrence with outputs
 // grid: (channel groups, n_chunks, batch), block: one wavefront
+#ifndef MAMBA_SCAN_WAVES_ATTR
+#define MAMBA_SCAN_WAVES_ATTR
+#endif
 template <typename T, int N, int CPL, bool HAS_Z, bool SOFTPLUS>
-__global__ void __launch_bounds__(kWave)
+__global__ void __launch_bounds__(kWave) MAMBA_SCAN_WAVES_ATTR
 scan_chunk_out(const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
                const T *__restrict__ Bm, const T *__restrict__ Cm, const float *__restrict__ Dskip,
                const T *__restrict__ z, const float *__restrict__ dt_bias,
@@ -177,16 +206,29 @@ scan_chunk_out(const T *__restrict__ x, const T *__restrict__ dt, const float *_
     }
 
     const int64_t row0 = b * L;
-    RawVec<T, N> braw = ld_uniform<T, N>(Bm + (row0 + t0) * N);
-    RawVec<T, N> craw = ld_uniform<T, N>(Cm + (row0 + t0) * N);
+    __shared__ __attribute__((aligned(16))) float lds_bc[2 * BcStage<T, N, 2>::kBufFloats];
+    BcStage<T, N, 2> bc;
+    bc.lds = lds_bc;
+    bc.src[0] = Bm + row0 * N;
+    bc.src[1] = Cm + row0 * N;
+    bc.last = t1 * N - 1;
+    bc.issue(t0);
+    bc.commit(0);
+    if (t0 + kBcTile < t1) bc.issue(t0 + kBcTile);
+    // at the first step of every later B/C tile: publish the prefetched tile, fetch the one after
+    auto bc_advance = [&](int64_t t) {
+        const int rel = (int)(t - t0);
+        if ((rel & (kBcTile - 1)) == 0 && rel != 0) {
+            bc.commit((rel / kBcTile) & 1);
+            if (t + kBcTile < t1) bc.issue(t + kBcTile);
+        }
+    };
     auto step = [&](int64_t t, raw_t xr, raw_t dr, raw_t zr) {
+        const int rel = (int)(t - t0);
+        const int buf = (rel / kBcTile) & 1, sidx = rel & (kBcTile - 1);
         float bf[N], cf[N];
-        unpack_uniform<N>(braw, bf);
-        unpack_uniform<N>(craw, cf);
-        const int64_t tn = (t + 1 < t1) ? t + 1 : t;  // next step's B, C (a harmless re-read at the end)
-        braw = ld_uniform<T, N>(Bm + (row0 + tn) * N);
-        craw = ld_uniform<T, N>(Cm + (row0 + tn) * N);
-        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of this step's arithmetic
+        bc.read(buf, 0, sidx, bf);
+        bc.read(buf, 1, sidx, cf);
         float xv[CPL], dv[CPL], zv[CPL], ov[CPL];
         unpack(xr, xv);
         unpack(dr, dv);
@@ -220,10 +262,12 @@ scan_chunk_out(const T *__restrict__ x, const T *__restrict__ dt, const float *_
     };
     int64_t t = t0;
     if (t + kTile <= t1) load_tile(t, xc, dc, zc);
+#pragma nounroll
     for (; t + kTile <= t1; t += kTile) {
         raw_t xn[kTile], dn[kTile], zn[kTile];
         const bool more = t + 2 * kTile <= t1;
         if (more) load_tile(t + kTile, xn, dn, zn);
+        bc_advance(t);
 #pragma unroll
         for (int i = 0; i < kTile; ++i) step(t + i, xc[i], dc[i], zc[i]);
         if (more) {
@@ -235,10 +279,12 @@ scan_chunk_out(const T *__restrict__ x, const T *__restrict__ dt, const float *_
             }
         }
     }
+#pragma nounroll
     for (; t < t1; ++t) {
         const int64_t o = (row0 + t) * D + d0;
         raw_t zr = raw_t();
         if constexpr (HAS_Z) zr = ld_raw<T, CPL>(z + o);
+        bc_advance(t);
         step(t, ld_raw<T, CPL>(x + o), ld_raw<T, CPL>(dt + o), zr);
     }
 
@@ -276,13 +322,25 @@ scan_chunk_state(const T *__restrict__ x, const T *__restrict__ dt, const float 
     }
 
     const int64_t row0 = b * L;
-    RawVec<T, N> braw = ld_uniform<T, N>(Bm + (row0 + t0) * N);
+    __shared__ __attribute__((aligned(16))) float lds_bc[2 * BcStage<T, N, 1>::kBufFloats];
+    BcStage<T, N, 1> bc;
+    bc.lds = lds_bc;
+    bc.src[0] = Bm + row0 * N;
+    bc.last = t1 * N - 1;
+    bc.issue(t0);
+    bc.commit(0);
+    if (t0 + kBcTile < t1) bc.issue(t0 + kBcTile);
+    auto bc_advance = [&](int64_t t) {
+        const int rel = (int)(t - t0);
+        if ((rel & (kBcTile - 1)) == 0 && rel != 0) {
+            bc.commit((rel / kBcTile) & 1);
+            if (t + kBcTile < t1) bc.issue(t + kBcTile);
+        }
+    };
     auto step = [&](int64_t t, raw_t xr, raw_t dr) {
+        const int rel = (int)(t - t0);
         float bf[N];
-        unpack_uniform<N>(braw, bf);
-        const int64_t tn = (t + 1 < t1) ? t + 1 : t;
-        braw = ld_uniform<T, N>(Bm + (row0 + tn) * N);
-        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of this step's arithmetic
+        bc.read((rel / kBcTile) & 1, 0, rel & (kBcTile - 1), bf);
         float xv[CPL], dv[CPL];
         unpack(xr, xv);
         unpack(dr, dv);
@@ -311,10 +369,12 @@ scan_chunk_state(const T *__restrict__ x, const T *__restrict__ dt, const float 
     };
     int64_t t = t0;
     if (t + kTile <= t1) load_tile(t, xc, dc);
+#pragma nounroll
     for (; t + kTile <= t1; t += kTile) {
         raw_t xn[kTile], dn[kTile];
         const bool more = t + 2 * kTile <= t1;
         if (more) load_tile(t + kTile, xn, dn);
+        bc_advance(t);
 #pragma unroll
         for (int i = 0; i < kTile; ++i) step(t + i, xc[i], dc[i]);
         if (more) {
@@ -325,8 +385,10 @@ scan_chunk_state(const T *__restrict__ x, const T *__restrict__ dt, const float 
             }
         }
     }
+#pragma nounroll
     for (; t < t1; ++t) {
         const int64_t o = (row0 + t) * D + d0;
+        bc_advance(t);
         step(t, ld_raw<T, CPL>(x + o), ld_raw<T, CPL>(dt + o));
     }
 

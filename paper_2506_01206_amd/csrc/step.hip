@@ -40,8 +40,15 @@ template <int N> __device__ __forceinline__ float4 ld4_io(const bf16_t *p)
     return make_float4(bf16_lo(r.x), bf16_hi(r.x), bf16_lo(r.y), bf16_hi(r.y));
 }
 
-// grid: (ceil(D * N / 4 / 256), n_out); lane <-> one float4 of the branch's (D, N) state
-template <typename T, int N, bool HAS_Z, bool SOFTPLUS>
+#ifndef MAMBA_STEP_UNROLL
+#define MAMBA_STEP_UNROLL 4
+#endif
+
+// grid: (ceil(D * N / 4 / (256 * U)), n_out).  A lane owns U float4s of the branch's (D, N) state,
+// 256 float4s apart, so every wavefront load or store is still one contiguous 1 KiB run; all
+// loads of the U pieces are issued before the first one is used, which keeps several KiB per
+// wavefront in flight (the step is a single pass over the state and lives on memory latency).
+template <typename T, int N, int U, bool HAS_Z, bool SOFTPLUS>
 __global__ void __launch_bounds__(kBlock)
 state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ parent,
                   const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
@@ -52,57 +59,71 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
     constexpr int Q = N / 4;
     const int64_t j = blockIdx.y;
     const int64_t row4 = D * Q;  // float4s per branch
-    const int64_t f_raw = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    const bool live = f_raw < row4;
-    const int64_t f = live ? f_raw : row4 - 1;
-    const int64_t d = f / Q;
-    const int q = (int)(f - d * Q);
-
     const int64_t p = parent ? (int64_t)parent[j] : j;
     const bool p_ok = p >= 0 && p < n_in;
+    const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
+    const float4 *a4 = reinterpret_cast<const float4 *>(A);
 
-    float4 h = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (p_ok) h = reinterpret_cast<const float4 *>(h_in)[p * row4 + f];
-    const float4 a = reinterpret_cast<const float4 *>(A)[f];
-    const float4 bv = ld4_io<N>(Bm + j * N + 4 * q);
-    const float4 cv = ld4_io<N>(Cm + j * N + 4 * q);
-    const float xv = ld_io(x, j * D + d);
-    const float v = ld_io(dt, j * D + d) + (dt_bias ? dt_bias[d] : 0.0f);
-    const float delta = SOFTPLUS ? softplus_f32(v) : v;
-    const float u = delta * xv;
-    const float dl = delta * kLog2e;
-
-    h.x = fmaf(exp2_hw(dl * a.x), h.x, u * bv.x);
-    h.y = fmaf(exp2_hw(dl * a.y), h.y, u * bv.y);
-    h.z = fmaf(exp2_hw(dl * a.z), h.z, u * bv.z);
-    h.w = fmaf(exp2_hw(dl * a.w), h.w, u * bv.w);
-    float y = h.x * cv.x;
-    y = fmaf(h.y, cv.y, y);
-    y = fmaf(h.z, cv.z, y);
-    y = fmaf(h.w, cv.w, y);
-    y = channel_sum<Q>(y);
-
-    if (!p_ok) {
-        const float nan = __int_as_float(0x7fc00000);
-        h = make_float4(nan, nan, nan, nan);
-        y = nan;
+    int64_t f[U], d[U];
+    bool live[U];
+    float4 h[U], a[U], bv[U], cv[U];
+    float xv[U], dv[U], zv[U], bias[U], dsk[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const int64_t f_raw = ((int64_t)blockIdx.x * U + i) * kBlock + threadIdx.x;
+        live[i] = f_raw < row4;
+        f[i] = live[i] ? f_raw : row4 - 1;
+        d[i] = f[i] / Q;
+        const int q = (int)(f[i] - d[i] * Q);
+        h[i] = hin4[f[i]];
+        a[i] = a4[f[i]];
+        bv[i] = ld4_io<N>(Bm + j * N + 4 * q);
+        cv[i] = ld4_io<N>(Cm + j * N + 4 * q);
+        xv[i] = ld_io(x, j * D + d[i]);
+        dv[i] = ld_io(dt, j * D + d[i]);
+        zv[i] = HAS_Z ? ld_io(z, j * D + d[i]) : 0.0f;
+        bias[i] = dt_bias ? dt_bias[d[i]] : 0.0f;
+        dsk[i] = Dskip ? Dskip[d[i]] : 0.0f;
     }
-    if (live) {
-        reinterpret_cast<float4 *>(h_out)[j * row4 + f] = h;
-        if (q == 0) {
-            if (Dskip) y = fmaf(Dskip[d], xv, y);
-            if constexpr (HAS_Z) y *= silu_f32(ld_io(z, j * D + d));
-            st_io(out, j * D + d, y);
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const float v = dv[i] + bias[i];
+        const float delta = SOFTPLUS ? softplus_f32(v) : v;
+        const float u = delta * xv[i];
+        const float dl = delta * kLog2e;
+        float4 hh = h[i];
+        hh.x = fmaf(exp2_hw(dl * a[i].x), hh.x, u * bv[i].x);
+        hh.y = fmaf(exp2_hw(dl * a[i].y), hh.y, u * bv[i].y);
+        hh.z = fmaf(exp2_hw(dl * a[i].z), hh.z, u * bv[i].z);
+        hh.w = fmaf(exp2_hw(dl * a[i].w), hh.w, u * bv[i].w);
+        float y = hh.x * cv[i].x;
+        y = fmaf(hh.y, cv[i].y, y);
+        y = fmaf(hh.z, cv[i].z, y);
+        y = fmaf(hh.w, cv[i].w, y);
+        y = channel_sum<Q>(y);
+        if (!p_ok) {
+            const float nan = __int_as_float(0x7fc00000);
+            hh = make_float4(nan, nan, nan, nan);
+            y = nan;
+        }
+        if (live[i]) {
+            reinterpret_cast<float4 *>(h_out)[j * row4 + f[i]] = hh;
+            if (f[i] - d[i] * Q == 0) {
+                y = fmaf(dsk[i], xv[i], y);
+                if constexpr (HAS_Z) y *= silu_f32(zv[i]);
+                st_io(out, j * D + d[i], y);
+            }
         }
     }
 }
 
-template <typename T, int N> hipError_t launch_step_n(const StepArgs &a, hipStream_t stream)
+template <typename T, int N, int U> hipError_t launch_step_u(const StepArgs &a, hipStream_t stream)
 {
     const int64_t row4 = a.D * (N / 4);
-    dim3 grid((unsigned)((row4 + kBlock - 1) / kBlock), (unsigned)a.n_out);
+    const int64_t per_block = (int64_t)kBlock * U;
+    dim3 grid((unsigned)((row4 + per_block - 1) / per_block), (unsigned)a.n_out);
 #define MAMBA_STEP(HZ, SP)                                                                        \
-    state_step_kernel<T, N, HZ, SP><<<grid, kBlock, 0, stream>>>(                                 \
+    state_step_kernel<T, N, U, HZ, SP><<<grid, kBlock, 0, stream>>>(                              \
         a.h_out, a.h_in, a.parent, static_cast<const T *>(a.x), static_cast<const T *>(a.dt), a.A, \
         static_cast<const T *>(a.Bm), static_cast<const T *>(a.Cm), a.Dskip,                      \
         static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D)
@@ -115,6 +136,16 @@ template <typename T, int N> hipError_t launch_step_n(const StepArgs &a, hipStre
     }
 #undef MAMBA_STEP
     return hipGetLastError();
+}
+
+template <typename T, int N> hipError_t launch_step_n(const StepArgs &a, hipStream_t stream)
+{
+    // several float4s per lane as long as that still leaves about three workgroups per CU
+    const int64_t row4 = a.D * (N / 4);
+    auto blocks = [&](int u) { return a.n_out * ((row4 + kBlock * u - 1) / (kBlock * u)); };
+    if (blocks(MAMBA_STEP_UNROLL) >= 768) return launch_step_u<T, N, MAMBA_STEP_UNROLL>(a, stream);
+    if (MAMBA_STEP_UNROLL > 2 && blocks(2) >= 768) return launch_step_u<T, N, 2>(a, stream);
+    return launch_step_u<T, N, 1>(a, stream);
 }
 
 template <typename T> hipError_t launch_step_io(const StepArgs &a, hipStream_t stream)

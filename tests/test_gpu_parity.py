@@ -469,3 +469,56 @@ def test_cfg4_wide_prefill_and_decode_sampled(m):
     assert_close(to_host(ssm_u[0]), rssm[0], TOL[dc["io"]], "cfg4 decode ssm")
     for s in range(dc["steps"]):
         assert_close(values(to_host(out_u[s])), routs[s], TOL[dc["io"]], "cfg4 decode out %d" % s)
+
+
+# ------------------------------------------------------------------------------------ HIP graph
+def test_decode_loop_replays_in_a_hip_graph(m):
+    """Every call has a fixed shape and neither allocates nor synchronizes, so a draft round can
+    be captured once and replayed (Sec. 4.1: graph cache per batch size).  Each replay, with other
+    work and synchronizations in between, must equal the eager result bit for bit."""
+    dc = synth.decode_case(3, 8, 3, 256, 16, 4, synth.BF16, seed=77)
+    nl, nb, D, N = dc["n_layers"], dc["branches"], dc["D"], dc["N"]
+    P = [{k: to_dev(v) for k, v in p.items()} for p in dc["params"]]
+    TOK = [[{k: to_dev(v) for k, v in t.items()} for t in layer] for layer in dc["tokens"]]
+    PAR = [to_dev(p) for p in dc["parents"]]
+    ssm0, conv0 = to_dev(dc["ssm0"]), to_dev(dc["conv0"])
+    ssm = [torch.empty_like(ssm0), torch.empty_like(ssm0)]
+    conv = [torch.empty_like(conv0), torch.empty_like(conv0)]
+    xc = torch.empty((nb, 1, D), dtype=conv0.dtype, device=DEV)
+    outs = torch.empty((dc["steps"], nl, nb, D), dtype=conv0.dtype, device=DEV)
+
+    def draft_round():
+        src_s, src_c = ssm0, conv0
+        for s in range(dc["steps"]):
+            dst_s, dst_c = ssm[s & 1], conv[s & 1]
+            m.mamba_state_fork(src_c, None, PAR[s], conv_dst=dst_c)
+            for l in range(nl):
+                t = TOK[s][l]
+                m.mamba_conv1d_fwd(t["x"].unsqueeze(1), P[l]["conv_w"], P[l]["conv_bias"],
+                                   conv_state_in=dst_c[l], y=xc, conv_state_out=dst_c[l])
+                m.mamba_state_step(src_s[l], xc.squeeze(1), t["dt"], P[l]["A"], t["Bm"], t["Cm"],
+                                   P[l]["Dskip"], t["z"], P[l]["dt_bias"], parent_idx=PAR[s],
+                                   h_out=dst_s[l], out=outs[s, l])
+            src_s, src_c = dst_s, dst_c
+        return src_s, src_c
+
+    fin_s, fin_c = draft_round()
+    torch.cuda.synchronize()
+    ref = (outs.clone(), fin_s.clone(), fin_c.clone())
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            draft_round()
+    torch.cuda.current_stream().wait_stream(side)
+    scratch = torch.empty(1 << 22, device=DEV)
+    for i in range(4):
+        outs.zero_()
+        ssm[0].fill_(float(i))
+        ssm[1].fill_(-1.0)
+        scratch.normal_()                       # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs, ref[0]) and torch.equal(fin_s, ref[1]) and torch.equal(fin_c, ref[2]), i
