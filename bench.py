@@ -34,7 +34,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published: 256 CUs x 128 
 # HBM bytes per scan launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE summed over the scan's
 # three kernels, each scaled by what the same counter reads for the 1 GiB copy below; figures and
 # commands in profiles/).  Keyed by workload; None for a workload that has not been profiled.
-SCAN_TRAFFIC_BYTES = {("cfg3", 1, 32768, 1536, 16): 792_000_000}
+SCAN_TRAFFIC_BYTES = {("cfg3", 1, 32768, 1536, 16): 734_800_000}
 
 
 def scan_bytes(B, L, D, N, e):
@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-wide-step", action="store_true",
+                    help="skip the separate timing of the 64-branch, D=4096 state step")
     ap.add_argument("--eager-decode", action="store_true",
                     help="launch the decode kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--prefill", default="cfg3", help="synthetic config of the prefill leg")
@@ -204,6 +206,53 @@ def main():
     copy_gbs = 3 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del src, dst
 
+    # the wide decode step on its own: 64 branches of a Mamba-1.4B-shaped layer (D = 4096), parent
+    # gather fused in, over rotating state buffers (> 512 MB in all) so that every launch streams
+    # its state from HBM; a HIP graph of R launches is replayed to take the host out of the timing
+    wide = {}
+    if not args.no_wide_step:
+        wc = synth.CONFIGS["cfg4"]
+        wnb, wD, wN = wc["branches"], wc["D"], wc["N"]
+        rngw = np.random.default_rng(404)
+        wp = synth.layer_params(rngw, wD, wN, wc["K"])
+        wt = {k: to_dev(v) for k, v in synth.token_inputs(rngw, (wnb,), wD, wN, wc["io"]).items()}
+        wP = {k: to_dev(v) for k, v in wp.items()}
+        wpar = to_dev(rngw.integers(0, wnb, wnb).astype(np.int32))
+        R = int(600e6 // (wnb * wD * wN * 4)) + 1
+        hin = [torch.randn((wnb, wD, wN), device=dev) for _ in range(R)]
+        hout = [torch.empty((wnb, wD, wN), device=dev) for _ in range(R)]
+        wout = torch.empty((wnb, wD), dtype=wt["x"].dtype, device=dev)
+
+        def wide_round():
+            for i in range(R):
+                m.mamba_state_step(hin[i], wt["x"], wt["dt"], wP["A"], wt["Bm"], wt["Cm"], wP["Dskip"],
+                                   wt["z"], wP["dt_bias"], parent_idx=wpar, h_out=hout[i], out=wout)
+        wide_round()
+        torch.cuda.synchronize()
+        wg = torch.cuda.CUDAGraph()
+        side2 = torch.cuda.Stream()
+        side2.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side2):
+            with torch.cuda.graph(wg, stream=side2):
+                wide_round()
+        torch.cuda.current_stream().wait_stream(side2)
+        wg.replay()
+        w0, w1 = ev(), ev()
+        w0.record()
+        for _ in range(3):
+            wg.replay()
+        w1.record()
+        torch.cuda.synchronize()
+        us = w0.elapsed_time(w1) * 1e3 / (3 * R)
+        wb = step_bytes(wnb, wD, wN, 2 if wc["io"] == synth.BF16 else 4)
+        wide = {"workload": "cfg4 state step: %d branches, D=%d, N=%d, %s I/O, parent gather fused, cold "
+                            "(%d rotating state buffers)" % (wnb, wD, wN, wc["io"], R),
+                "us_per_launch": round(us, 3), "algorithmic_bytes_per_launch": wb,
+                "GBps": round(wb / us / 1e3, 1), "frac_of_hbm_peak": round(wb / us / 1e3 / HBM_PEAK_GBS, 4),
+                "frac_of_copy_kernel": round(wb / us / 1e3 / copy_gbs, 4),
+                "branch_steps_per_s_per_layer": round(wnb / (us * 1e-6), 1)}
+        del hin, hout
+
     tokens = B * L
     sb = scan_bytes(B, L, D, N, e)
     achieved = sb / (scan_ms * 1e-3) / 1e9
@@ -230,7 +279,7 @@ def main():
         "decode_branch_steps_per_s_per_layer": round(units / (dec_ms * 1e-3), 1),
         "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
         "decode_launches": nsteps * (1 + 2 * nl), "decode_mode": "eager" if args.eager_decode else "hip_graph",
-        "copy_kernel_GBps": round(copy_gbs, 1),
+        "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide,
     }
 
     result = {

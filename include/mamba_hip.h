@@ -27,9 +27,11 @@
  *    One B_t, C_t vector per (batch row, token) is shared by all D channels.
  *  - All arithmetic is float32; bf16 inputs are widened exactly and outputs
  *    rounded to nearest-even once, at the store.
- *  - Supported ranges: N in {1..32}... see MAMBA_MAX_N; K in {1..MAMBA_MAX_K};
- *    anything else returns MAMBA_ERR_UNSUPPORTED.  Data pointers must be
- *    16-byte aligned (MAMBA_ERR_MISALIGNED).
+ *  - Supported ranges: N (d_state) in {4, 8, 16, 32}; K (d_conv) in {2, 3, 4};
+ *    batch, n_out and n_layers up to 65535; anything else returns
+ *    MAMBA_ERR_UNSUPPORTED.  D is arbitrary (the widest vector path is taken
+ *    when D allows it).  Data pointers must be 16-byte aligned
+ *    (MAMBA_ERR_MISALIGNED).
  *  - Return value: MAMBA_OK (0); a negative mamba_status_t for an argument
  *    error, detected before any HIP call (so nothing was enqueued); a positive
  *    value is the hipError_t of a failed launch.  A call with zero work
@@ -58,7 +60,7 @@ typedef enum {
     MAMBA_ERR_ALIAS = -6         /* output overlaps an input where that is not allowed */
 } mamba_status_t;
 
-#define MAMBA_MAX_N 64 /* N must be a multiple of 4 in [4, 64], or 1, 2 */
+#define MAMBA_MAX_N 32
 #define MAMBA_MAX_K 4
 
 /* Human-readable text for a status returned by any function here (static storage). */

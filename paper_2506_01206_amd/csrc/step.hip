@@ -59,9 +59,6 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
     constexpr int Q = N / 4;
     const int64_t j = blockIdx.y;
     const int64_t row4 = D * Q;  // float4s per branch
-    const int64_t p = parent ? (int64_t)parent[j] : j;
-    const bool p_ok = p >= 0 && p < n_in;
-    const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
     const float4 *a4 = reinterpret_cast<const float4 *>(A);
 
     int64_t f[U], d[U];
@@ -75,7 +72,6 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
         f[i] = live[i] ? f_raw : row4 - 1;
         d[i] = f[i] / Q;
         const int q = (int)(f[i] - d[i] * Q);
-        h[i] = hin4[f[i]];
         a[i] = a4[f[i]];
         bv[i] = ld4_io<N>(Bm + j * N + 4 * q);
         cv[i] = ld4_io<N>(Cm + j * N + 4 * q);
@@ -85,6 +81,12 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
         bias[i] = dt_bias ? dt_bias[d[i]] : 0.0f;
         dsk[i] = Dskip ? Dskip[d[i]] : 0.0f;
     }
+    // the state row is the only load that has to wait for the parent index
+    const int64_t p = parent ? (int64_t)parent[j] : j;
+    const bool p_ok = p >= 0 && p < n_in;
+    const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
+#pragma unroll
+    for (int i = 0; i < U; ++i) h[i] = hin4[f[i]];
 #pragma unroll
     for (int i = 0; i < U; ++i) {
         const float v = dv[i] + bias[i];
