@@ -39,20 +39,17 @@ __device__ __forceinline__ float exp2_hw(float v) { return __builtin_amdgcn_exp2
 __device__ __forceinline__ float log2_hw(float v) { return __builtin_amdgcn_logf(v); }
 __device__ __forceinline__ float rcp_hw(float v) { return __builtin_amdgcn_rcpf(v); }
 
-// softplus(v) = log(1 + e^v), relative error ~1e-6 or better over the whole range.
-// For small w = e^v the sum 1 + w loses w's low bits, so below 1/16 the alternating
-// series of log1p is used (truncation error w^5/6 relative, < 2e-7); above 20 the
-// result is v to float32 precision.
+// softplus(v) = log(1 + e^v) = max(v, 0) + log1p(w), w = e^-|v| <= 1, to ~1e-7 relative (plus the
+// rounding of the exp2 argument for large |v|).  The sum s = 1 + w drops w's low bits; they are
+// recovered exactly as r = w - (s - 1) and added back: log1p(w) = log(s) + log1p(r / s), which is
+// log(s) + r to first order (s is in [1, 2] and |r| <= 2^-24, so r and r / s differ by < 2^-25).
+// No threshold and no overflow: w never exceeds 1.
 __device__ __forceinline__ float softplus_f32(float v)
 {
-    const float w = exp2_hw(v * kLog2e);
-    const float lg = log2_hw(1.0f + w) * kLn2;
-    float s = fmaf(w, 0.2f, -0.25f);
-    s = fmaf(w, s, 0.33333334f);
-    s = fmaf(w, s, -0.5f);
-    s = fmaf(w * w, s, w);
-    float r = w < 0.0625f ? s : lg;
-    return v > 20.0f ? v : r;
+    const float w = exp2_hw(-fabsf(v) * kLog2e);
+    const float s = 1.0f + w;
+    const float r = w - (s - 1.0f);
+    return fmaxf(v, 0.0f) + fmaf(log2_hw(s), kLn2, r);
 }
 
 // silu(v) = v / (1 + e^-v)

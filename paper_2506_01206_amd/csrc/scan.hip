@@ -401,41 +401,72 @@ scan_chunk_state(const T *__restrict__ x, const T *__restrict__ dt, const float 
 }
 
 // ---------------------------------------------------------------------------------------
-// carry: slot 0 <- h0; slot c <- exp(A S_{c-1}) slot_{c-1} + slot_c.  One thread per (b, d, n).
-__global__ void __launch_bounds__(256)
-scan_carry(const float *__restrict__ A, const float *h0, float *ws_state,
-           const float *__restrict__ ws_sumdt, int64_t batch, int64_t D, int N, int n_chunks)
+// carry: slot 0 <- h0; slot c <- exp(A S_{c-1}) slot_{c-1} + slot_c for c = 1 .. n_chunks - 1.
+// The chain over chunks is serial per (b, d, n) and each link waits on a load, so it is cut into
+// kCarrySegs segments that run side by side in one workgroup: every segment first folds its own
+// chunks from a zero state (composite decay exp(A * sum S) and offset), the composites are
+// exchanged through LDS, each segment derives its incoming state from the segments before it,
+// and then walks its chunks again writing the true states.  block: (64 lanes over (b,d,n), segs)
+constexpr int kCarrySegs = 8;
+constexpr int kCarryBatch = 8;  // loads issued together
+
+template <bool WRITE>
+__device__ __forceinline__ float carry_walk(float h, float a2, float *st, const float *sd, int c0, int c1,
+                                            int64_t DN, int64_t D)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t DN = D * N;
-    if (idx >= batch * DN) return;
-    const int64_t b = idx / DN;
-    const int64_t dn = idx - b * DN;
-    const int64_t d = dn / N;
-    const float a2 = A[dn] * kLog2e;
-    float h = h0 ? h0[idx] : 0.0f;
-    float *st = ws_state + b * n_chunks * DN + dn;
-    const float *sd = ws_sumdt + b * n_chunks * D + d;
-    st[0] = h;
-    constexpr int U = 8;
-    int c = 1;
-    for (; c + U <= n_chunks; c += U) {
-        float loc[U], sm[U];
+    int c = c0;
+    for (; c + kCarryBatch <= c1; c += kCarryBatch) {
+        float loc[kCarryBatch], sm[kCarryBatch];
 #pragma unroll
-        for (int i = 0; i < U; ++i) {
+        for (int i = 0; i < kCarryBatch; ++i) {
             loc[i] = st[(int64_t)(c + i) * DN];
             sm[i] = sd[(int64_t)(c + i - 1) * D];
         }
 #pragma unroll
-        for (int i = 0; i < U; ++i) {
+        for (int i = 0; i < kCarryBatch; ++i) {
             h = fmaf(exp2_hw(a2 * sm[i]), h, loc[i]);
-            st[(int64_t)(c + i) * DN] = h;
+            if (WRITE) st[(int64_t)(c + i) * DN] = h;
         }
     }
-    for (; c < n_chunks; ++c) {
+    for (; c < c1; ++c) {
         h = fmaf(exp2_hw(a2 * sd[(int64_t)(c - 1) * D]), h, st[(int64_t)c * DN]);
-        st[(int64_t)c * DN] = h;
+        if (WRITE) st[(int64_t)c * DN] = h;
     }
+    return h;
+}
+
+__global__ void __launch_bounds__(kWave * kCarrySegs)
+scan_carry(const float *__restrict__ A, const float *h0, float *ws_state,
+           const float *__restrict__ ws_sumdt, int64_t batch, int64_t D, int N, int n_chunks)
+{
+    __shared__ float decay[kCarrySegs][kWave], offset[kCarrySegs][kWave];
+    const int lane = threadIdx.x, seg = threadIdx.y;
+    const int64_t DN = D * N;
+    const int64_t idx_raw = (int64_t)blockIdx.x * kWave + lane;
+    const bool live = idx_raw < batch * DN;
+    const int64_t idx = live ? idx_raw : batch * DN - 1;
+    const int64_t b = idx / DN;
+    const int64_t dn = idx - b * DN;
+    const int64_t d = dn / N;
+    const float a2 = A[dn] * kLog2e;
+    float *st = ws_state + b * n_chunks * DN + dn;
+    const float *sd = ws_sumdt + b * n_chunks * D + d;
+    // chunks 1 .. n_chunks-1 split evenly over the segments
+    const int per = (n_chunks - 1 + kCarrySegs - 1) / kCarrySegs;
+    int c0 = 1 + seg * per, c1 = c0 + per;
+    if (c0 > n_chunks) c0 = n_chunks;
+    if (c1 > n_chunks) c1 = n_chunks;
+
+    float sum = 0.0f;
+    for (int c = c0; c < c1; ++c) sum += sd[(int64_t)(c - 1) * D];
+    decay[seg][lane] = exp2_hw(a2 * sum);
+    offset[seg][lane] = carry_walk<false>(0.0f, a2, st, sd, c0, c1, DN, D);
+    __syncthreads();
+    float h = h0 ? h0[idx] : 0.0f;
+    for (int s = 0; s < seg; ++s) h = fmaf(decay[s][lane], h, offset[s][lane]);
+    if (!live) return;
+    if (seg == 0) st[0] = h;
+    carry_walk<true>(h, a2, st, sd, c0, c1, DN, D);
 }
 
 // copies h0 (or zeros) to h_final when L == 0
@@ -467,7 +498,7 @@ hipError_t launch_scan_t(const ScanArgs &a, hipStream_t stream)
             scan_chunk_state<T, N, CPL, false><<<g1, kWave, 0, stream>>>(
                 x, dt, a.A, Bm, a.dt_bias, ws_state, ws_sumdt, a.L, a.D, a.chunk_len, nc);
         const int64_t total = a.batch * a.D * N;
-        scan_carry<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
+        scan_carry<<<(unsigned)((total + kWave - 1) / kWave), dim3(kWave, kCarrySegs), 0, stream>>>(
             a.A, a.h0, ws_state, ws_sumdt, a.batch, a.D, N, nc);
         h_start = ws_state;
         chunked = 1;

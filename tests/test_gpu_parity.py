@@ -522,3 +522,30 @@ def test_decode_loop_replays_in_a_hip_graph(m):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(outs, ref[0]) and torch.equal(fin_s, ref[1]) and torch.equal(fin_c, ref[2]), i
+
+
+def test_softplus_and_silu_accuracy_through_the_step(m):
+    """N = 4, A = 0, zero state, B = (1,0,0,0), C = (1,0,0,0), x = 1, no skip: out = delta * silu(z)
+    and h[.,0] = delta, so the kernel's softplus and SiLU can be read off directly."""
+    v = np.concatenate([np.linspace(-30, 30, 4001), [-80.0, -19.99, 19.99, 20.01, 50.0, 87.0]]).astype(np.float32)
+    D = v.size
+    one = np.zeros((1, 4), dtype=np.float32)
+    one[0, 0] = 1.0
+    zz = np.linspace(-25, 25, D).astype(np.float32)
+    for gate in (False, True):
+        ho, o = m.mamba_state_step(to_dev(np.zeros((1, D, 4), np.float32)), to_dev(np.ones((1, D), np.float32)),
+                                   to_dev(v[None, :] - np.float32(0.25)), to_dev(np.zeros((D, 4), np.float32)),
+                                   to_dev(one), to_dev(one), None, to_dev(zz[None, :]) if gate else None,
+                                   to_dev(np.full(D, 0.25, np.float32)))
+        arg = (v - np.float32(0.25)).astype(np.float64) + 0.25
+        ref = np.logaddexp(0.0, arg)
+        got = to_host(ho)[0, :, 0].astype(np.float64)
+        rel = np.abs(got - ref) / ref
+        # 3e-6: the float32 product v * log2(e) loses ~|v| * 6e-8 in the exponent at the far ends
+        assert rel.max() < 3e-6, (float(rel.max()), float(arg[rel.argmax()]))
+        if gate:
+            z64 = zz.astype(np.float64)
+            refo = ref * z64 / (1.0 + np.exp(-z64))
+            goto = to_host(o)[0].astype(np.float64)
+            # the exp2 arguments carry ~|z| * 6e-8 and ~|v| * 6e-8 of rounding: 1e-5 covers both factors
+            assert np.all(np.abs(goto - refo) <= 1e-5 * np.abs(refo) + 1e-37)
