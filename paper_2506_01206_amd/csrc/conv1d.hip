@@ -47,6 +47,33 @@ __device__ __forceinline__ void pack_row(const float *v, uint4 &r)
                    f32x2_to_bf16x2(v[4], v[5]), f32x2_to_bf16x2(v[6], v[7]));
 }
 
+// COUNT contiguous elements, COUNT * sizeof(T) a multiple of 16 bytes and p 16-byte aligned:
+// moved as 16-byte vectors (the per-lane blocks of weights and of carried state are such blocks).
+template <int COUNT> __device__ __forceinline__ void ld_block(const float *p, float *f)
+{
+    const float4 *q = reinterpret_cast<const float4 *>(p);
+#pragma unroll
+    for (int v = 0; v < COUNT / 4; ++v) unpack_row(q[v], f + 4 * v);
+}
+template <int COUNT> __device__ __forceinline__ void ld_block(const bf16_t *p, float *f)
+{
+    const uint4 *q = reinterpret_cast<const uint4 *>(p);
+#pragma unroll
+    for (int v = 0; v < COUNT / 8; ++v) unpack_row(q[v], f + 8 * v);
+}
+template <int COUNT> __device__ __forceinline__ void st_block(float *p, const float *f)
+{
+    float4 *q = reinterpret_cast<float4 *>(p);
+#pragma unroll
+    for (int v = 0; v < COUNT / 4; ++v) pack_row(f + 4 * v, q[v]);
+}
+template <int COUNT> __device__ __forceinline__ void st_block(bf16_t *p, const float *f)
+{
+    uint4 *q = reinterpret_cast<uint4 *>(p);
+#pragma unroll
+    for (int v = 0; v < COUNT / 8; ++v) pack_row(f + 8 * v, q[v]);
+}
+
 // grid: (channel-vector groups, time tiles, batch)
 template <typename T, int VEC, int K, bool SILU>
 __global__ void __launch_bounds__(kBlock)
@@ -64,19 +91,34 @@ conv1d_kernel(const T *__restrict__ x, const float *__restrict__ w, const float 
     const int64_t t1 = (t0 + tile_len < L) ? t0 + tile_len : L;
 
     float wr[VEC][K], br[VEC];
+    if constexpr (VEC > 1) {
+        ld_block<VEC * K>(w + d0 * K, &wr[0][0]);
+    } else {
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) {
-#pragma unroll
-        for (int k = 0; k < K; ++k) wr[c][k] = w[(d0 + c) * K + k];
-        br[c] = bias ? bias[d0 + c] : 0.0f;
+        for (int k = 0; k < K; ++k) wr[0][k] = w[d0 * K + k];
     }
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) br[c] = bias ? bias[d0 + c] : 0.0f;
 
     const T *xb = x + b * L * D + d0;
     T *yb = y + b * L * D + d0;
     auto ld_row = [&](int64_t t) { return *reinterpret_cast<const row_t *>(xb + t * D); };
 
-    // window: the H rows before t0 in padded time; win[H-1] is the newest
+    // window: the H rows before t0 in padded time; win[H-1] is the newest.  Rows before token 0
+    // come from the carried state, whose (VEC, H) block of this lane is one contiguous run.
     float win[H > 0 ? H : 1][VEC];
+    float carried[VEC * (H > 0 ? H : 1)];
+    if (t0 < H) {
+        if (!state_in) {
+#pragma unroll
+            for (int i = 0; i < VEC * H; ++i) carried[i] = 0.0f;
+        } else if constexpr (VEC > 1) {
+            ld_block<VEC * H>(state_in + (b * D + d0) * H, carried);
+        } else {
+#pragma unroll
+            for (int k = 0; k < H; ++k) carried[k] = ld_io(state_in, (b * D + d0) * H + k);
+        }
+    }
 #pragma unroll
     for (int i = 0; i < H; ++i) {
         const int64_t t = t0 - H + i;  // token index of this window row, negative => carried state
@@ -84,8 +126,13 @@ conv1d_kernel(const T *__restrict__ x, const float *__restrict__ w, const float 
             unpack_row(ld_row(t), win[i]);
         } else {
 #pragma unroll
-            for (int c = 0; c < VEC; ++c)
-                win[i][c] = state_in ? ld_io(state_in, (b * D + d0 + c) * H + (H + t)) : 0.0f;
+            for (int c = 0; c < VEC; ++c) {
+                float v = 0.0f;
+#pragma unroll
+                for (int k = 0; k < H; ++k)
+                    if (k == H + t) v = carried[c * H + k];
+                win[i][c] = v;
+            }
         }
     }
 
@@ -134,10 +181,17 @@ conv1d_kernel(const T *__restrict__ x, const float *__restrict__ w, const float 
     for (; t < t1; ++t) emit(t, ld_row(t));
 
     if (state_out && t1 == L) {
+        float last[VEC * (H > 0 ? H : 1)];
 #pragma unroll
         for (int c = 0; c < VEC; ++c)
 #pragma unroll
-            for (int k = 0; k < H; ++k) st_io(state_out, (b * D + d0 + c) * H + k, win[k][c]);
+            for (int k = 0; k < H; ++k) last[c * H + k] = win[k][c];
+        if constexpr (VEC > 1) {
+            st_block<VEC * H>(state_out + (b * D + d0) * H, last);
+        } else {
+#pragma unroll
+            for (int k = 0; k < H; ++k) st_io(state_out, (b * D + d0) * H + k, last[k]);
+        }
     }
 }
 
