@@ -549,3 +549,62 @@ def test_softplus_and_silu_accuracy_through_the_step(m):
             goto = to_host(o)[0].astype(np.float64)
             # the exp2 arguments carry ~|z| * 6e-8 and ~|v| * 6e-8 of rounding: 1e-5 covers both factors
             assert np.all(np.abs(goto - refo) <= 1e-5 * np.abs(refo) + 1e-37)
+
+
+# ------------------------------------------------------------------------------------ size limits
+def test_largest_grids(m):
+    """Shapes that sit on the launch-grid limits: 65535 branches / batch rows / layers, and a
+    sequence long enough that the conv tiles must grow to stay within 65535 time tiles."""
+    rng = np.random.default_rng(2024)
+    # step: 65535 branches, tiny layer
+    nb, D, N = 65535, 4, 4
+    p = synth.layer_params(rng, D, N, 4, random_A=True)
+    tok = synth.token_inputs(rng, (nb,), D, N, synth.F32)
+    h_in = rng.standard_normal((7, D, N)).astype(np.float32)
+    parent = rng.integers(0, 7, nb).astype(np.int32)
+    ho, o = m.mamba_state_step(to_dev(h_in), to_dev(tok["x"]), to_dev(tok["dt"]), to_dev(p["A"]),
+                               to_dev(tok["Bm"]), to_dev(tok["Cm"]), to_dev(p["Dskip"]), to_dev(tok["z"]),
+                               to_dev(p["dt_bias"]), parent_idx=to_dev(parent))
+    rh, ro = oracle.state_step(W(h_in), W(tok["x"]), W(tok["dt"]), W(p["A"]), W(tok["Bm"]), W(tok["Cm"]),
+                               W(p["Dskip"]), W(tok["z"]), W(p["dt_bias"]), parent)
+    assert_close(to_host(ho), rh, TOL[synth.F32], "65535-branch step h")
+    assert_close(to_host(o), ro, TOL[synth.F32], "65535-branch step out")
+    # fork: 65535 branches x 3 layers, and 65535 layers x 2 branches
+    for nl, n_in, n_out in ((3, 5, 65535), (65535, 3, 2)):
+        ssm = rng.standard_normal((nl, n_in, 2, 4)).astype(np.float32)
+        conv = synth.to_io(rng.standard_normal((nl, n_in, 2, 3)).astype(np.float32), synth.BF16)
+        par = rng.integers(0, n_in, n_out).astype(np.int32)
+        cd, sd = m.mamba_state_fork(to_dev(conv), to_dev(ssm), to_dev(par))
+        rc, rs = oracle.state_fork(conv, ssm, par)
+        assert to_host(cd).tobytes() == rc.tobytes() and to_host(sd).tobytes() == rs.tobytes()
+    # scan and conv: 65535 batch rows of a tiny layer
+    c = synth.prefill_case(65535, 5, 2, 4, 3, synth.F32, seed=3)
+    check_scan(m, c, what="65535-row scan")
+    check_conv(m, c)
+    # scan: as many time chunks as the grid allows (one token per chunk)
+    c = synth.prefill_case(1, 65535, 2, 4, 2, synth.BF16, seed=4, random_A=True)
+    check_scan(m, c, chunk_len=1, what="65535-chunk scan")
+    # conv: 2.2 M tokens, more than 65535 tiles of the default length
+    L = 65535 * 32 + 12345
+    c = synth.prefill_case(1, L, 8, 4, 4, synth.BF16, seed=5)
+    y, st = run_conv(m, c)
+    idx = np.concatenate([np.arange(0, 5000), np.arange(L - 5000, L)])
+    ry, rst = oracle.conv1d_fwd(W(c["x"]), W(c["conv_w"]), W(c["conv_bias"]))
+    assert_close(values(y)[:, idx], ry[:, idx], TOL[synth.BF16], "2.2M-token conv (ends)")
+    step = np.arange(0, L, 997)
+    assert_close(values(y)[:, step], ry[:, step], TOL[synth.BF16], "2.2M-token conv (strided)")
+    assert np.array_equal(values(st), rst)
+
+
+def test_unsupported_sizes_are_rejected_on_the_gpu_box_too(m):
+    x = torch.zeros((1, 4, 8), device=DEV)
+    with pytest.raises(m.MambaError) as e:
+        m.mamba_scan_fwd(x, x, torch.zeros((8, 12), device=DEV), torch.zeros((1, 4, 12), device=DEV),
+                         torch.zeros((1, 4, 12), device=DEV))
+    assert e.value.status == m.STATUS["UNSUPPORTED"]
+    with pytest.raises(m.MambaError) as e:
+        m.mamba_conv1d_fwd(x, torch.zeros((8, 5), device=DEV))
+    assert e.value.status == m.STATUS["UNSUPPORTED"]
+    with pytest.raises(m.MambaError) as e:                      # out aliases x
+        m.mamba_conv1d_fwd(x, torch.zeros((8, 4), device=DEV), y=x)
+    assert e.value.status == m.STATUS["ALIAS"]
