@@ -147,6 +147,45 @@ int mamba_state_fork(void *conv_dst, const void *conv_src, float *ssm_dst,
                      int64_t n_out, int64_t n_in, int64_t D, int64_t N, int K,
                      mamba_dtype_t conv_dtype, void *hip_stream);
 
+/*
+ * Batch-wise state caches of a draft tree (Sec. 4.1, "efficient cache utilization for batch
+ * generation": for a tree configuration T = (N_1..N_gamma) the batch size at draft position i is
+ * B_i = N_1 * ... * N_i; one state cache per possible batch size is allocated in advance so that
+ * duplicating states never re-allocates).
+ *
+ * mamba_tree_plan is pure host arithmetic: from the tree (HOST int32[gamma]) and the layer
+ * shapes it lays out, inside one caller-allocated device slab, a cache per DISTINCT batch size
+ * (conv rows (n_layers,B,D,K-1) in conv_dtype and SSM rows (n_layers,B,D,N) float32; cache 0
+ * is the root's, B = 1, filled by the prefill) and an int32 parent-index array for every draft
+ * position that branches (N_i > 1).  A position with N_i = 1 keeps its batch size: it steps in
+ * place in the same cache and has no parent array (parent_offset = -1).  All offsets are
+ * multiples of 256 bytes; the slab must hold total_bytes.  Children of node p at position i
+ * occupy rows p*N_i .. p*N_i+N_i-1, so parent[j] = j / N_i.
+ * Errors: gamma outside [1, MAMBA_MAX_DEPTH] or N_i < 1 -> BAD_SHAPE; a batch size above 65535,
+ * unsupported N / K / dtype -> UNSUPPORTED; size overflow -> BAD_SHAPE.
+ *
+ * mamba_tree_parents writes those parent arrays into the slab (device), one small kernel per
+ * branching position, on hip_stream.  plan and tree are HOST pointers.
+ */
+#define MAMBA_MAX_DEPTH 16
+
+typedef struct {
+    int32_t gamma;                                /* draft length; positions are 1..gamma          */
+    int32_t n_caches;                             /* distinct batch sizes, the root's (1) included */
+    int64_t batch[MAMBA_MAX_DEPTH + 1];           /* batch[0] = 1, batch[i] = N_1 * ... * N_i       */
+    int32_t cache_of_depth[MAMBA_MAX_DEPTH + 1];  /* cache holding the states after position i     */
+    int64_t parent_offset[MAMBA_MAX_DEPTH + 1];   /* byte offset of int32[batch[i]], -1 if N_i = 1 */
+    int64_t cache_batch[MAMBA_MAX_DEPTH + 1];     /* per cache: its batch size                     */
+    int64_t conv_offset[MAMBA_MAX_DEPTH + 1];     /* per cache: byte offset of its conv rows       */
+    int64_t ssm_offset[MAMBA_MAX_DEPTH + 1];      /* per cache: byte offset of its SSM rows        */
+    int64_t total_bytes;
+} mamba_tree_plan_t;
+
+int mamba_tree_plan(const int32_t *tree, int gamma, int64_t n_layers, int64_t D, int64_t N,
+                    int K, mamba_dtype_t conv_dtype, mamba_tree_plan_t *plan);
+int mamba_tree_parents(void *slab, const mamba_tree_plan_t *plan, const int32_t *tree,
+                       void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,8 +29,26 @@ if not os.path.exists(LIB_PATH):
 _vp, _i64, _int, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
 
 
+MAMBA_MAX_DEPTH = 16
+
+
+class TreePlan(ctypes.Structure):
+    """mamba_tree_plan_t of include/mamba_hip.h."""
+    _n = MAMBA_MAX_DEPTH + 1
+    _fields_ = [("gamma", ctypes.c_int32), ("n_caches", ctypes.c_int32),
+                ("batch", ctypes.c_int64 * _n), ("cache_of_depth", ctypes.c_int32 * _n),
+                ("parent_offset", ctypes.c_int64 * _n), ("cache_batch", ctypes.c_int64 * _n),
+                ("conv_offset", ctypes.c_int64 * _n), ("ssm_offset", ctypes.c_int64 * _n),
+                ("total_bytes", ctypes.c_int64)]
+
+
 def _declare(lib):
     """Attach the C signatures of include/mamba_hip.h to a loaded library."""
+    lib.mamba_tree_plan.argtypes = [ctypes.POINTER(ctypes.c_int32), _int, _i64, _i64, _i64, _int, _int,
+                                    ctypes.POINTER(TreePlan)]
+    lib.mamba_tree_plan.restype = _int
+    lib.mamba_tree_parents.argtypes = [_vp, ctypes.POINTER(TreePlan), ctypes.POINTER(ctypes.c_int32), _vp]
+    lib.mamba_tree_parents.restype = _int
     lib.mamba_status_string.argtypes = [_int]
     lib.mamba_status_string.restype = ctypes.c_char_p
     lib.mamba_conv1d_fwd.argtypes = [_vp] * 6 + [_i64, _i64, _i64, _int, _int, _int, _vp]
@@ -49,7 +67,8 @@ def _declare(lib):
 lib = _declare(ctypes.CDLL(LIB_PATH))
 
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
-           "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork")
+           "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork", "mamba_tree_plan",
+           "mamba_tree_parents")
 
 
 class MambaError(RuntimeError):
@@ -191,3 +210,23 @@ def mamba_state_fork(conv_src, ssm_src, parent_idx, conv_dst=None, ssm_dst=None,
         _stream(stream))
     _check("mamba_state_fork", st)
     return conv_dst, ssm_dst
+
+
+def _tree_array(tree):
+    return (ctypes.c_int32 * len(tree))(*[int(n) for n in tree])
+
+
+def mamba_tree_plan(tree, n_layers, D, N, K, conv_dtype=torch.bfloat16) -> TreePlan:
+    """Batch sizes and cache layout for a tree configuration (N_1..N_gamma); host arithmetic only."""
+    plan = TreePlan()
+    code = MAMBA_F32 if conv_dtype == torch.float32 else MAMBA_BF16 if conv_dtype == torch.bfloat16 else -1
+    st = lib.mamba_tree_plan(_tree_array(tree), len(tree), n_layers, D, N, K, code, ctypes.byref(plan))
+    _check("mamba_tree_plan", st)
+    return plan
+
+
+def mamba_tree_parents(slab, plan: TreePlan, tree, stream=None):
+    """Write the parent-index arrays of every branching draft position into the slab."""
+    st = lib.mamba_tree_parents(_ptr(slab, torch.uint8, name="slab"), ctypes.byref(plan), _tree_array(tree),
+                                _stream(stream))
+    _check("mamba_tree_parents", st)

@@ -201,4 +201,79 @@ int mamba_state_fork(void *conv_dst, const void *conv_src, float *ssm_dst, const
     return (int)launch_fork(a, static_cast<hipStream_t>(hip_stream));
 }
 
+int mamba_tree_plan(const int32_t *tree, int gamma, int64_t n_layers, int64_t D, int64_t N, int K,
+                    mamba_dtype_t conv_dtype, mamba_tree_plan_t *plan)
+{
+    if (!tree || !plan) return MAMBA_ERR_NULL_POINTER;
+    const int e = io_size(conv_dtype);
+    if (e == 0 || !n_supported(N) || !k_supported(K)) return MAMBA_ERR_UNSUPPORTED;
+    if (gamma < 1 || gamma > MAMBA_MAX_DEPTH || n_layers < 0 || D < 0) return MAMBA_ERR_BAD_SHAPE;
+    int64_t conv_row, ssm_row;
+    if (!size3(n_layers, D, K - 1, e, &conv_row) || !size3(n_layers, D, N, 4, &ssm_row)) return MAMBA_ERR_BAD_SHAPE;
+    mamba_tree_plan_t p = {};
+    p.gamma = gamma;
+    p.batch[0] = 1;
+    p.cache_of_depth[0] = 0;
+    p.parent_offset[0] = -1;
+    p.n_caches = 1;
+    p.cache_batch[0] = 1;
+    for (int i = 1; i <= gamma; ++i) {
+        const int64_t fan = tree[i - 1];
+        if (fan < 1) return MAMBA_ERR_BAD_SHAPE;
+        int64_t b;
+        if (!mul_ok(p.batch[i - 1], fan, &b)) return MAMBA_ERR_BAD_SHAPE;
+        if (b > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+        p.batch[i] = b;
+        if (fan == 1) {
+            p.cache_of_depth[i] = p.cache_of_depth[i - 1];
+        } else {
+            p.cache_of_depth[i] = p.n_caches;
+            p.cache_batch[p.n_caches++] = b;
+        }
+    }
+    auto align = [](int64_t v) { return (v + 255) / 256 * 256; };
+    int64_t off = 0;
+    for (int c = 0; c < p.n_caches; ++c) {
+        int64_t cb, sb;
+        if (!mul_ok(conv_row, p.cache_batch[c], &cb) || !mul_ok(ssm_row, p.cache_batch[c], &sb) ||
+            cb > ((int64_t)1 << 60) || sb > ((int64_t)1 << 60))
+            return MAMBA_ERR_BAD_SHAPE;
+        p.conv_offset[c] = off;
+        off = align(off + cb);
+        p.ssm_offset[c] = off;
+        off = align(off + sb);
+    }
+    for (int i = 1; i <= gamma; ++i) {
+        if (tree[i - 1] == 1) {
+            p.parent_offset[i] = -1;
+        } else {
+            p.parent_offset[i] = off;
+            off = align(off + p.batch[i] * 4);
+        }
+    }
+    p.total_bytes = off;
+    *plan = p;
+    return MAMBA_OK;
+}
+
+int mamba_tree_parents(void *slab, const mamba_tree_plan_t *plan, const int32_t *tree, void *hip_stream)
+{
+    if (!slab || !plan || !tree) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(slab)) return MAMBA_ERR_MISALIGNED;
+    if (plan->gamma < 1 || plan->gamma > MAMBA_MAX_DEPTH) return MAMBA_ERR_BAD_SHAPE;
+    for (int i = 1; i <= plan->gamma; ++i) {
+        const bool forks = tree[i - 1] > 1;
+        if (tree[i - 1] < 1 || forks != (plan->parent_offset[i] >= 0) ||
+            (forks && (plan->parent_offset[i] % 16 != 0 || plan->parent_offset[i] + plan->batch[i] * 4 > plan->total_bytes)))
+            return MAMBA_ERR_BAD_SHAPE;  // the plan was not made for this tree
+    }
+    for (int i = 1; i <= plan->gamma; ++i) {
+        if (plan->parent_offset[i] < 0) continue;
+        int32_t *dst = reinterpret_cast<int32_t *>(static_cast<char *>(slab) + plan->parent_offset[i]);
+        const hipError_t err = launch_tree_parents(dst, plan->batch[i], tree[i - 1], static_cast<hipStream_t>(hip_stream));
+        if (err != hipSuccess) return (int)err;
+    }
+    return MAMBA_OK;
+}
+
 }  // extern "C"

@@ -62,6 +62,13 @@ state_fork_kernel(VC *__restrict__ conv_dst, const VC *__restrict__ conv_src,
     }
 }
 
+__global__ void __launch_bounds__(kBlock)
+tree_parents_kernel(int32_t *__restrict__ parent, int64_t n, int32_t fanout)
+{
+    const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (j < n) parent[j] = (int32_t)(j / fanout);
+}
+
 int vec_bytes(int64_t row_bytes)
 {
     if (row_bytes % 16 == 0) return 16;
@@ -97,6 +104,13 @@ template <typename VC> hipError_t launch_fork_c(const ForkArgs &a, hipStream_t s
 }
 
 }  // namespace
+
+hipError_t launch_tree_parents(int32_t *parent, int64_t n, int32_t fanout, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    tree_parents_kernel<<<(unsigned)((n + kBlock - 1) / kBlock), kBlock, 0, stream>>>(parent, n, fanout);
+    return hipGetLastError();
+}
 
 hipError_t launch_fork(const ForkArgs &a, hipStream_t stream)
 {

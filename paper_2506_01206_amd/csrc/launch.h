@@ -60,4 +60,7 @@ struct ForkArgs {
 };
 hipError_t launch_fork(const ForkArgs &a, hipStream_t stream);
 
+// parent[j] = j / fanout for j < n (children of a node sit next to each other)
+hipError_t launch_tree_parents(int32_t *parent, int64_t n, int32_t fanout, hipStream_t stream);
+
 }  // namespace mamba

@@ -171,3 +171,74 @@ def test_fork_validation(b):
     assert fork(b, n_out=0) == 0
     assert fork(b, nl=0) == 0
     assert fork(b, cd=None, cs=None, sd=None, ss=None) == 0
+
+
+def read_golden_trees():
+    rows = []
+    with open(os.path.join(ROOT, "tests", "golden", "tree_configs.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                t, bsz = line.split("|")
+                rows.append((tuple(int(v) for v in t.split(",")), [int(v) for v in bsz.split(",")]))
+    return rows
+
+
+def test_tree_plan_matches_the_paper_trees(b):
+    """Batch sizes B_i = N_1..N_i of the trees the paper prints, one cache per distinct batch size
+    (Sec. 4.1), all inside one slab without overlap."""
+    import torch
+    nl, D, N, K = 24, 1536, 16, 4
+    for tree, sizes in read_golden_trees():
+        p = b.mamba_tree_plan(tree, nl, D, N, K, torch.bfloat16)
+        assert p.gamma == len(tree)
+        assert [p.batch[i] for i in range(len(tree) + 1)] == [1] + sizes
+        distinct = sorted(set([1] + sizes))
+        assert p.n_caches == len(distinct)
+        assert [p.cache_batch[c] for c in range(p.n_caches)] == distinct
+        spans = []
+        for c in range(p.n_caches):
+            bs = p.cache_batch[c]
+            spans.append((p.conv_offset[c], nl * bs * D * (K - 1) * 2))
+            spans.append((p.ssm_offset[c], nl * bs * D * N * 4))
+        for i, n_i in enumerate(tree, start=1):
+            assert p.cache_batch[p.cache_of_depth[i]] == sizes[i - 1]
+            if n_i == 1:
+                assert p.parent_offset[i] == -1 and p.cache_of_depth[i] == p.cache_of_depth[i - 1]
+            else:
+                assert p.cache_of_depth[i] == p.cache_of_depth[i - 1] + 1
+                spans.append((p.parent_offset[i], sizes[i - 1] * 4))
+        spans.sort()
+        for (o, n), (o2, _) in zip(spans, spans[1:]):
+            assert o % 256 == 0 and o + n <= o2
+        assert spans[-1][0] + spans[-1][1] <= p.total_bytes
+        assert p.total_bytes - sum(n for _, n in spans) < 256 * len(spans)     # only alignment padding
+
+
+def test_tree_plan_validation(b):
+    import ctypes
+    S = b.STATUS
+    plan = b.TreePlan()
+
+    def call(tree, gamma=None, nl=2, D=64, N=16, K=4, io=1, out=plan):
+        arr = (ctypes.c_int32 * max(len(tree), 1))(*tree)
+        return b.lib.mamba_tree_plan(arr, len(tree) if gamma is None else gamma, nl, D, N, K, io,
+                                     ctypes.byref(out) if out is not None else None)
+    assert call([3, 2, 1]) == 0
+    assert call([]) == S["BAD_SHAPE"]
+    assert call([2] * 17) == S["BAD_SHAPE"]                   # deeper than MAMBA_MAX_DEPTH
+    assert call([3, 0, 2]) == S["BAD_SHAPE"]
+    assert call([3, -1]) == S["BAD_SHAPE"]
+    assert call([256, 256, 2]) == S["UNSUPPORTED"]            # 131072 branches
+    assert call([2], N=5) == S["UNSUPPORTED"]
+    assert call([2], K=7) == S["UNSUPPORTED"]
+    assert call([2], io=9) == S["UNSUPPORTED"]
+    assert call([2], nl=-1) == S["BAD_SHAPE"]
+    assert call([2], nl=1 << 40, D=1 << 30) == S["BAD_SHAPE"]
+    assert b.lib.mamba_tree_plan(None, 1, 1, 8, 16, 4, 1, ctypes.byref(plan)) == S["NULL_POINTER"]
+    # parents: a plan made for another tree is refused before anything is launched
+    assert call([3, 2, 1]) == 0
+    other = (ctypes.c_int32 * 3)(3, 1, 2)
+    assert b.lib.mamba_tree_parents(P(0), ctypes.byref(plan), other, None) == S["BAD_SHAPE"]
+    assert b.lib.mamba_tree_parents(None, ctypes.byref(plan), other, None) == S["NULL_POINTER"]
+    assert b.lib.mamba_tree_parents(P(0) + 4, ctypes.byref(plan), other, None) == S["MISALIGNED"]

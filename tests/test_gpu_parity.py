@@ -608,3 +608,63 @@ def test_unsupported_sizes_are_rejected_on_the_gpu_box_too(m):
     with pytest.raises(m.MambaError) as e:                      # out aliases x
         m.mamba_conv1d_fwd(x, torch.zeros((8, 4), device=DEV), y=x)
     assert e.value.status == m.STATUS["ALIAS"]
+
+
+# ------------------------------------------------------------------------------------ tree caches
+@pytest.mark.parametrize("tree", [(3, 2, 2, 1, 1), (3, 3, 2, 1), (2, 2, 2, 1, 1, 1), (1, 1, 1, 1, 1), (1, 4, 1)])
+def test_tree_draft_cache_against_oracle(m, tree):
+    """Per-batch-size state caches + one captured graph per draft position (Sec. 4.1) on the trees the
+    paper prints: every position's outputs and the final states against the oracle chain
+    (fork by parent[j] = j // N_i, conv step, state step)."""
+    from paper_2506_01206_amd.tree import TreeDraftCache
+    say(tree=tree)
+    nl, D, N, K, io = 2, 128, 16, 4, synth.BF16
+    rng = np.random.default_rng(sum(tree) * 7 + len(tree))
+    params = [synth.layer_params(rng, D, N, K, random_A=True) for _ in range(nl)]
+    P = [{k: to_dev(v) for k, v in p.items()} for p in params]
+    ssm_root = rng.standard_normal((nl, 1, D, N)).astype(np.float32)
+    conv_root = synth.to_io(rng.standard_normal((nl, 1, D, K - 1)).astype(np.float32), io)
+    cache = TreeDraftCache(tree, nl, D, N, K, torch.bfloat16, DEV)
+    sizes = synth.tree_batch_sizes(tree)
+    parents = synth.tree_parents(tree)
+    assert cache.batch == [1] + sizes
+    assert len(cache.ssm) == len(set([1] + sizes))                    # one cache per distinct batch size
+    toks = []
+    for i, b_i in enumerate(sizes, start=1):
+        if tree[i - 1] > 1:
+            assert np.array_equal(to_host(cache.parent[i]), parents[i - 1])
+        else:
+            assert cache.parent[i] is None
+        layer_toks = [synth.token_inputs(rng, (b_i,), D, N, io) for _ in range(nl)]
+        toks.append(layer_toks)
+        for l in range(nl):
+            for k in ("x", "dt", "z", "Bm", "Cm"):
+                cache.inputs[i][k][l].copy_(to_dev(layer_toks[l][k]))
+
+    def run(use_graphs):
+        cache.set_root(to_dev(conv_root), to_dev(ssm_root))
+        cache.draft(P, use_graphs=use_graphs)
+        torch.cuda.synchronize()
+        last = cache.cache_index(cache.gamma)
+        return ([o.clone() for o in cache.out[1:]], cache.ssm[last].clone(), cache.conv[last].clone())
+
+    eager = run(False)
+    for _ in range(3):                                                # capture on first use, then replays
+        again = run(True)
+        assert all(torch.equal(a, b) for a, b in zip(eager[0], again[0]))
+        assert torch.equal(eager[1], again[1]) and torch.equal(eager[2], again[2])
+
+    ssm, conv = ssm_root.astype(np.float64), conv_root
+    for i, b_i in enumerate(sizes, start=1):
+        conv, ssm = oracle.state_fork(conv, ssm, parents[i - 1])
+        conv = conv.copy()
+        for l in range(nl):
+            p, t = params[l], toks[i - 1][l]
+            xc, cst = oracle.conv1d_fwd(W(t["x"])[:, None, :], W(p["conv_w"]), W(p["conv_bias"]), W(conv[l]))
+            conv[l] = synth.to_io(cst.astype(np.float32), io)
+            xc_io = W(synth.to_io(xc[:, 0].astype(np.float32), io))
+            ssm[l], o = oracle.state_step(ssm[l], xc_io, W(t["dt"]), W(p["A"]), W(t["Bm"]), W(t["Cm"]),
+                                          W(p["Dskip"]), W(t["z"]), W(p["dt_bias"]))
+            assert_close(values(to_host(eager[0][i - 1][l])), o, TOL[io], "tree %s position %d layer %d" % (tree, i, l))
+    assert_close(to_host(eager[1]), ssm, TOL[io], "tree final ssm")
+    assert to_host(eager[2]).tobytes() == conv.tobytes()
