@@ -39,6 +39,14 @@ def test_library_exports_every_declared_symbol(b):
     # the Python binding carries the same names
     for name in declared:
         assert callable(getattr(b, name))
+    # second header: host-side tree search
+    from paper_2506_01206_amd import tree_search
+    text = open(os.path.join(ROOT, "include", "sd_tree_search.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(sd_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(tree_search.EXPORTS), declared ^ set(tree_search.EXPORTS)
+    for name in declared:
+        assert getattr(raw, name) is not None and callable(getattr(tree_search, name))
 
 
 def test_status_strings(b):
