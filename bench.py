@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-wide-step", action="store_true",
                     help="skip the separate timing of the 64-branch, D=4096 state step")
+    ap.add_argument("--no-tree-draft", action="store_true",
+                    help="skip the sequential-versus-tree draft round timing")
     ap.add_argument("--eager-decode", action="store_true",
                     help="launch the decode kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--prefill", default="cfg3", help="synthetic config of the prefill leg")
@@ -253,6 +255,38 @@ def main():
                 "branch_steps_per_s_per_layer": round(wnb / (us * 1e-6), 1)}
         del hin, hout
 
+    # sequential drafting (1,1,1,1,1) against the paper's default tree (3,2,2,1,1) on per-batch-size
+    # state caches with one captured graph per draft position (Sec. 4.1): time of one draft round of
+    # the layer core over all layers.  The paper's table on tree drafting reports the whole drafter's
+    # latency growing from 6.62 to 8.30 for the same pair of shapes (other hardware, context only).
+    tree_detail = {}
+    if not args.no_tree_draft:
+        from paper_2506_01206_amd.tree import TreeDraftCache
+        for name, tree in (("sequential_1_1_1_1_1", (1, 1, 1, 1, 1)), ("tree_3_2_2_1_1", (3, 2, 2, 1, 1))):
+            tc = TreeDraftCache(tree, nl, Dd, Nd, Kd, conv0.dtype, dev)
+            g = torch.Generator(device=dev)
+            g.manual_seed(7)
+            for i in range(1, tc.gamma + 1):
+                for k, buf in tc.inputs[i].items():
+                    buf.copy_((torch.randn(buf.shape, device=dev, generator=g) * (0.1 if k == "dt" else 1.0)).to(buf.dtype))
+            tc.set_root(conv0[:, :1], ssm0[:, :1])
+            tc.draft(LP, use_graphs=False)            # loads the kernels before any capture
+            tc.set_root(conv0[:, :1], ssm0[:, :1])
+            tc.draft(LP, use_graphs=True)
+            torch.cuda.synchronize()
+            t0_, t1_ = ev(), ev()
+            reps = 10
+            t0_.record()
+            for _ in range(reps):
+                tc.draft(LP, use_graphs=True)
+            t1_.record()
+            torch.cuda.synchronize()
+            tree_detail[name + "_ms"] = round(t0_.elapsed_time(t1_) / reps, 4)
+            tree_detail[name + "_branch_steps"] = sum(tc.batch[1:]) * nl
+            del tc
+        tree_detail["tree_over_sequential"] = round(tree_detail["tree_3_2_2_1_1_ms"] /
+                                                    tree_detail["sequential_1_1_1_1_1_ms"], 3)
+
     tokens = B * L
     sb = scan_bytes(B, L, D, N, e)
     achieved = sb / (scan_ms * 1e-3) / 1e9
@@ -280,6 +314,7 @@ def main():
         "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
         "decode_launches": nsteps * (1 + 2 * nl), "decode_mode": "eager" if args.eager_decode else "hip_graph",
         "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide,
+        "tree_draft_round": tree_detail,
     }
 
     result = {
