@@ -571,7 +571,7 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
             const int64_t want = (target_waves + columns - 1) / columns;
             cl = (L + want - 1) / want;
             if (cl > 256) cl = 256;  // short chunks balance better across the chip
-            if (cl < 64) cl = 64;    // and long enough to amortize the chunk prologue and carry
+            if (cl < 32) cl = 32;    // and long enough to amortize the chunk prologue and carry
             cl = (cl + kTile - 1) / kTile * kTile;
         }
     }

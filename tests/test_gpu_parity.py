@@ -668,3 +668,30 @@ def test_tree_draft_cache_against_oracle(m, tree):
             assert_close(values(to_host(eager[0][i - 1][l])), o, TOL[io], "tree %s position %d layer %d" % (tree, i, l))
     assert_close(to_host(eager[1]), ssm, TOL[io], "tree final ssm")
     assert to_host(eager[2]).tobytes() == conv.tobytes()
+
+
+# ------------------------------------------------------------------------------------ invariants
+def test_scan_invariants_at_size(m):
+    """Properties of the recurrence that hold at any size, checked on the GPU at a Mamba-130M layer
+    shape (fp32 I/O): linear in x from a zero state, C = 0 leaves the gated skip, z = 0 gives 0."""
+    B, L, D, N = 1, 4096, 1536, 16
+    c = synth.prefill_case(B, L, D, N, 4, synth.F32, seed=808)
+    d = dev_case(c)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(1)
+    x2 = torch.randn((B, L, D), device=DEV, generator=g)
+    scan = lambda x, **kw: m.mamba_scan_fwd(x, d["dt"], d["A"], kw.get("Bm", d["Bm"]), kw.get("Cm", d["Cm"]),
+                                           d["Dskip"], kw.get("z", d["z"]), d["dt_bias"])
+    o1, h1 = scan(d["x"])
+    o2, h2 = scan(x2)
+    a, b = 0.75, -1.5
+    o3, h3 = scan(a * d["x"] + b * x2)
+    ref_o, ref_h = (a * o1.double() + b * o2.double()).cpu().numpy(), (a * h1.double() + b * h2.double()).cpu().numpy()
+    assert_close(to_host(o3), ref_o, 1e-4, "linearity out")
+    assert_close(to_host(h3), ref_h, 1e-4, "linearity state")
+    o4, _ = scan(d["x"], Cm=torch.zeros_like(d["Cm"]))
+    zz = d["z"].double()
+    ref = (d["x"].double() * zz / (1 + torch.exp(-zz))).cpu().numpy()        # D = 1
+    assert_close(to_host(o4), ref, 1e-5, "C = 0")
+    o5, h5 = scan(d["x"], z=torch.zeros_like(d["z"]))
+    assert torch.count_nonzero(o5) == 0 and torch.equal(h5, h1)             # the gate never touches the state
