@@ -148,6 +148,27 @@ int mamba_state_fork(void *conv_dst, const void *conv_src, float *ssm_dst,
                      mamba_dtype_t conv_dtype, void *hip_stream);
 
 /*
+ * The dense parts of a Mamba block around the four operations above (the paper's drafter is a
+ * Mamba-130M, Sec. 3.1: per layer RMSNorm, in_proj, conv1d, x_proj, dt_proj, selective SSM,
+ * out_proj, residual).  bfloat16 tensors only (MAMBA_ERR_UNSUPPORTED otherwise), fp32 accumulation.
+ *
+ * mamba_linear_fwd:  out[m,n] = sum_k x[m,k] * w[n,k] (+ bias[n]) (+ residual[m,n])
+ *   x: (M,K) bf16; w: (N,K) bf16, N = n0 + n1 + n2; bias: (N) f32 or NULL.
+ *   The N output columns go to up to three dense tensors out0 (M,n0), out1 (M,n1), out2 (M,n2)
+ *   (n1, n2 may be 0 with NULL pointers): in_proj writes x | z, x_proj writes dt_low | B | C.
+ *   residual: (M,N) bf16 or NULL, only with a single output (n1 = n2 = 0); may be out0 itself.
+ *   K must be a multiple of 8; M up to 65535 * 128 rows.  Outputs must not overlap x or w.
+ *
+ * mamba_rmsnorm_fwd:  y[m,:] = x[m,:] * rsqrt(mean(x[m,:]^2) + eps) * w,  x, y: (M,C) bf16, w: (C) f32,
+ *   C a multiple of 8, C <= 4096.  y may be x itself.
+ */
+int mamba_linear_fwd(const void *x, const void *w, const float *bias, const void *residual,
+                     void *out0, int64_t n0, void *out1, int64_t n1, void *out2, int64_t n2,
+                     int64_t M, int64_t K, mamba_dtype_t io, void *hip_stream);
+int mamba_rmsnorm_fwd(const void *x, const float *w, void *y, int64_t M, int64_t C, float eps,
+                      mamba_dtype_t io, void *hip_stream);
+
+/*
  * Batch-wise state caches of a draft tree (Sec. 4.1, "efficient cache utilization for batch
  * generation": for a tree configuration T = (N_1..N_gamma) the batch size at draft position i is
  * B_i = N_1 * ... * N_i; one state cache per possible batch size is allocated in advance so that

@@ -183,3 +183,23 @@ def state_fork(conv_src, ssm_src, parent):
     _load().oracle_state_fork(_p(cd), _p(cs), _p(sd), _p(ss), _p(parent),
                               n_layers, n_out, n_in, rows[0], rows[1])
     return cd, sd
+
+
+# ---------------------------------------------------------------------------------------------
+# Dense parts of the block (plain numpy, float64).  The Mamba-130M drafter of the paper (Sec. 3.1)
+# wraps the selective SSM core in RMSNorm, in_proj, x_proj, dt_proj and out_proj with a residual.
+def linear(x, w, bias=None, residual=None):
+    """x (M,K), w (N,K) -> x @ w^T (+ bias) (+ residual), float64 (numpy.matmul is the contraction)."""
+    out = np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+    if bias is not None:
+        out = out + np.asarray(bias, dtype=np.float64)[None, :]
+    if residual is not None:
+        out = out + np.asarray(residual, dtype=np.float64)
+    return out
+
+
+def rmsnorm(x, w, eps):
+    """y[m,:] = x[m,:] / sqrt(mean(x[m,:]^2) + eps) * w."""
+    x = np.asarray(x, dtype=np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + float(eps)) * np.asarray(w, dtype=np.float64)

@@ -9,7 +9,8 @@ the library has not been built; using any kernel without it raises.
 from . import synth  # noqa: F401
 
 _BINDING_NAMES = ("mamba_conv1d_fwd", "mamba_scan_fwd", "mamba_scan_workspace_bytes",
-                  "mamba_state_step", "mamba_state_fork", "mamba_status_string", "binding")
+                  "mamba_state_step", "mamba_state_fork", "mamba_status_string", "mamba_tree_plan",
+                  "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "binding")
 
 
 def __getattr__(name):

@@ -49,6 +49,10 @@ def _declare(lib):
     lib.mamba_tree_plan.restype = _int
     lib.mamba_tree_parents.argtypes = [_vp, ctypes.POINTER(TreePlan), ctypes.POINTER(ctypes.c_int32), _vp]
     lib.mamba_tree_parents.restype = _int
+    lib.mamba_linear_fwd.argtypes = [_vp] * 5 + [_i64, _vp, _i64, _vp, _i64, _i64, _i64, _int, _vp]
+    lib.mamba_linear_fwd.restype = _int
+    lib.mamba_rmsnorm_fwd.argtypes = [_vp, _vp, _vp, _i64, _i64, ctypes.c_float, _int, _vp]
+    lib.mamba_rmsnorm_fwd.restype = _int
     lib.mamba_status_string.argtypes = [_int]
     lib.mamba_status_string.restype = ctypes.c_char_p
     lib.mamba_conv1d_fwd.argtypes = [_vp] * 6 + [_i64, _i64, _i64, _int, _int, _int, _vp]
@@ -68,7 +72,7 @@ lib = _declare(ctypes.CDLL(LIB_PATH))
 
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
            "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork", "mamba_tree_plan",
-           "mamba_tree_parents")
+           "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd")
 
 
 class MambaError(RuntimeError):
@@ -230,3 +234,35 @@ def mamba_tree_parents(slab, plan: TreePlan, tree, stream=None):
     st = lib.mamba_tree_parents(_ptr(slab, torch.uint8, name="slab"), ctypes.byref(plan), _tree_array(tree),
                                 _stream(stream))
     _check("mamba_tree_parents", st)
+
+
+def mamba_linear_fwd(x, w, bias=None, residual=None, splits=None, outs=None, stream=None):
+    """x (M,K) bf16, w (N,K) bf16 -> x @ w.T (+ bias) (+ residual).  ``splits`` = widths of up to three
+    output tensors that share the N columns (default: one tensor of width N); returns a tuple."""
+    M, K = x.shape
+    N = w.shape[0]
+    widths = [N] if splits is None else list(splits)
+    assert sum(widths) == N and 1 <= len(widths) <= 3
+    if outs is None:
+        outs = [torch.empty((M, n), dtype=x.dtype, device=x.device) for n in widths]
+    widths += [0] * (3 - len(widths))
+    outs = list(outs) + [None] * (3 - len(outs))
+    st = lib.mamba_linear_fwd(
+        _ptr(x, name="x"), _ptr(w, x.dtype, (N, K), "w"), _ptr(bias, torch.float32, (N,), "bias"),
+        _ptr(residual, x.dtype, (M, N), "residual"),
+        _ptr(outs[0], x.dtype, (M, widths[0]), "out0"), widths[0],
+        _ptr(outs[1], x.dtype, (M, widths[1]), "out1"), widths[1],
+        _ptr(outs[2], x.dtype, (M, widths[2]), "out2"), widths[2], M, K, _io_code(x), _stream(stream))
+    _check("mamba_linear_fwd", st)
+    return tuple(o for o in outs if o is not None)
+
+
+def mamba_rmsnorm_fwd(x, w, eps=1e-5, y=None, stream=None):
+    """x (M,C) bf16, w (C) f32 -> x * rsqrt(mean(x^2) + eps) * w."""
+    M, C = x.shape
+    if y is None:
+        y = torch.empty_like(x)
+    st = lib.mamba_rmsnorm_fwd(_ptr(x, name="x"), _ptr(w, torch.float32, (C,), "w"), _ptr(y, x.dtype, (M, C), "y"),
+                               M, C, float(eps), _io_code(x), _stream(stream))
+    _check("mamba_rmsnorm_fwd", st)
+    return y

@@ -201,6 +201,56 @@ int mamba_state_fork(void *conv_dst, const void *conv_src, float *ssm_dst, const
     return (int)launch_fork(a, static_cast<hipStream_t>(hip_stream));
 }
 
+int mamba_linear_fwd(const void *x, const void *w, const float *bias, const void *residual, void *out0,
+                     int64_t n0, void *out1, int64_t n1, void *out2, int64_t n2, int64_t M, int64_t K,
+                     mamba_dtype_t io, void *hip_stream)
+{
+    if (io != MAMBA_BF16) return MAMBA_ERR_UNSUPPORTED;
+    if (n0 < 0 || n1 < 0 || n2 < 0 || M < 0 || K < 0) return MAMBA_ERR_BAD_SHAPE;
+    int64_t N;
+    if (__builtin_add_overflow(n0, n1, &N) || __builtin_add_overflow(N, n2, &N)) return MAMBA_ERR_BAD_SHAPE;
+    int64_t xb, wb, ob[3];
+    const int64_t widths[3] = {n0, n1, n2};
+    void *outs[3] = {out0, out1, out2};
+    if (!size3(M, K, 1, 2, &xb) || !size3(N, K, 1, 2, &wb)) return MAMBA_ERR_BAD_SHAPE;
+    for (int i = 0; i < 3; ++i)
+        if (!size3(M, widths[i], 1, 2, &ob[i])) return MAMBA_ERR_BAD_SHAPE;
+    if (K % 8 != 0 || M > kMaxGridYZ * 128) return MAMBA_ERR_UNSUPPORTED;
+    if (residual && (n1 != 0 || n2 != 0)) return MAMBA_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return MAMBA_OK;
+    if (K == 0) return MAMBA_ERR_BAD_SHAPE;
+    if (!x || !w) return MAMBA_ERR_NULL_POINTER;
+    for (int i = 0; i < 3; ++i)
+        if (widths[i] > 0 && !outs[i]) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(residual) || !aligned16(out0) ||
+        !aligned16(out1) || !aligned16(out2))
+        return MAMBA_ERR_MISALIGNED;
+    for (int i = 0; i < 3; ++i) {
+        if (widths[i] == 0) continue;
+        if (overlap(outs[i], ob[i], x, xb) || overlap(outs[i], ob[i], w, wb)) return MAMBA_ERR_ALIAS;
+        for (int j = i + 1; j < 3; ++j)
+            if (widths[j] > 0 && overlap(outs[i], ob[i], outs[j], ob[j])) return MAMBA_ERR_ALIAS;
+    }
+    if (residual && residual != out0 && overlap(residual, ob[0], out0, ob[0])) return MAMBA_ERR_ALIAS;
+    LinearArgs a{x, w, bias, residual, {out0, out1, out2}, {n0, n1, n2}, M, K};
+    return (int)launch_linear(a, static_cast<hipStream_t>(hip_stream));
+}
+
+int mamba_rmsnorm_fwd(const void *x, const float *w, void *y, int64_t M, int64_t C, float eps,
+                      mamba_dtype_t io, void *hip_stream)
+{
+    if (io != MAMBA_BF16) return MAMBA_ERR_UNSUPPORTED;
+    int64_t bytes;
+    if (!size3(M, C, 1, 2, &bytes) || !(eps >= 0.0f)) return MAMBA_ERR_BAD_SHAPE;
+    if (C % 8 != 0 || C > 4096 || M > (int64_t)1 << 31) return MAMBA_ERR_UNSUPPORTED;
+    if (M == 0 || C == 0) return MAMBA_OK;
+    if (!x || !w || !y) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MAMBA_ERR_MISALIGNED;
+    if (x != y && overlap(x, bytes, y, bytes)) return MAMBA_ERR_ALIAS;
+    NormArgs a{x, w, y, M, C, eps};
+    return (int)launch_rmsnorm(a, static_cast<hipStream_t>(hip_stream));
+}
+
 int mamba_tree_plan(const int32_t *tree, int gamma, int64_t n_layers, int64_t D, int64_t N, int K,
                     mamba_dtype_t conv_dtype, mamba_tree_plan_t *plan)
 {

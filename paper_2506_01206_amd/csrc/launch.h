@@ -63,4 +63,23 @@ hipError_t launch_fork(const ForkArgs &a, hipStream_t stream);
 // parent[j] = j / fanout for j < n (children of a node sit next to each other)
 hipError_t launch_tree_parents(int32_t *parent, int64_t n, int32_t fanout, hipStream_t stream);
 
+struct LinearArgs {
+    const void *x, *w;       // (M, K), (N, K) bf16
+    const float *bias;       // (N) or nullptr
+    const void *residual;    // (M, N) bf16 or nullptr (single output only)
+    void *out[3];            // up to three output tensors (M, width[i]) bf16
+    int64_t width[3];
+    int64_t M, K;
+};
+hipError_t launch_linear(const LinearArgs &a, hipStream_t stream);
+
+struct NormArgs {
+    const void *x;           // (M, C) bf16
+    const float *w;          // (C)
+    void *y;                 // (M, C) bf16
+    int64_t M, C;
+    float eps;
+};
+hipError_t launch_rmsnorm(const NormArgs &a, hipStream_t stream);
+
 }  // namespace mamba

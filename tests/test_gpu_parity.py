@@ -695,3 +695,36 @@ def test_scan_invariants_at_size(m):
     assert_close(to_host(o4), ref, 1e-5, "C = 0")
     o5, h5 = scan(d["x"], z=torch.zeros_like(d["z"]))
     assert torch.count_nonzero(o5) == 0 and torch.equal(h5, h1)             # the gate never touches the state
+
+
+# ------------------------------------------------------------------------------------ dense parts
+@pytest.mark.parametrize("M,N,K,splits", [(1, 1, 8, None), (5, 80, 48, (48, 16, 16)), (130, 200, 72, None),
+                                          (257, 3072, 768, (1536, 1536)), (1000, 80, 1536, (48, 16, 16)),
+                                          (384, 768, 1536, None), (64, 1536, 48, None), (129, 129, 1032, (1, 128))])
+def test_linear_against_oracle(m, M, N, K, splits):
+    say(M=M, N=N, K=K, splits=splits)
+    rng = np.random.default_rng(M + N + K)
+    x = synth.to_io(rng.standard_normal((M, K)).astype(np.float32), synth.BF16)
+    w = synth.to_io((rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32), synth.BF16)
+    bias = rng.standard_normal(N).astype(np.float32)
+    ref = oracle.linear(W(x), W(w), W(bias))
+    outs = m.mamba_linear_fwd(to_dev(x), to_dev(w), to_dev(bias), splits=splits)
+    got = np.concatenate([values(to_host(o)) for o in outs], axis=1)
+    assert_close(got, ref, TOL[synth.BF16], "linear")
+    if splits is None:
+        res = synth.to_io(rng.standard_normal((M, N)).astype(np.float32), synth.BF16)
+        buf = to_dev(res)
+        (o,) = m.mamba_linear_fwd(to_dev(x), to_dev(w), None, residual=buf, outs=[buf])      # in place on the residual
+        assert_close(values(to_host(o)), oracle.linear(W(x), W(w), None, W(res)), TOL[synth.BF16], "linear + residual")
+
+
+@pytest.mark.parametrize("M,C", [(1, 8), (7, 768), (1000, 768), (33, 2048), (5, 4096), (3, 40)])
+def test_rmsnorm_against_oracle(m, M, C):
+    rng = np.random.default_rng(M + C)
+    x = synth.to_io((rng.standard_normal((M, C)) * rng.uniform(0.01, 30, (M, 1))).astype(np.float32), synth.BF16)
+    w = rng.standard_normal(C).astype(np.float32)
+    y = m.mamba_rmsnorm_fwd(to_dev(x), to_dev(w), eps=1e-5)
+    assert_close(values(to_host(y)), oracle.rmsnorm(W(x), W(w), 1e-5), TOL[synth.BF16], "rmsnorm")
+    xin = to_dev(x)
+    m.mamba_rmsnorm_fwd(xin, to_dev(w), eps=1e-5, y=xin)                                   # in place
+    assert torch.equal(xin, y)

@@ -409,3 +409,35 @@ def test_bf16_widening_is_exact():
     assert np.array_equal(synth.f32_to_bf16_bits(back), bits)
     tie = np.array([0x3F808000, 0x3F818000], dtype=np.uint32).view(np.float32)   # exact ties
     assert list(synth.f32_to_bf16_bits(tie)) == [0x3F80, 0x3F82]
+
+
+# ---------------------------------------------------------------- dense parts of the block
+def test_linear_against_explicit_sums():
+    r = rnd(101)
+    M, N, K = 5, 4, 7
+    x, w, b, res = r.standard_normal((M, K)), r.standard_normal((N, K)), r.standard_normal(N), r.standard_normal((M, N))
+    out = oracle.linear(x, w, b, res)
+    for m in range(M):
+        for n in range(N):
+            s = sum(x[m, k] * w[n, k] for k in range(K)) + b[n] + res[m, n]
+            assert out[m, n] == pytest.approx(s, rel=1e-13, abs=1e-13)
+    assert np.array_equal(oracle.linear(x, np.eye(K)), x)              # identity weights
+    assert oracle.linear(x, w).shape == (M, N)
+
+
+def test_rmsnorm_closed_forms():
+    r = rnd(103)
+    C = 16
+    w = r.standard_normal(C)
+    # a constant row c: mean square c^2, so y = w * c / sqrt(c^2 + eps)
+    y = oracle.rmsnorm(np.full((1, C), 3.0), w, 0.5)
+    np.testing.assert_allclose(y[0], w * 3.0 / np.sqrt(9.5), rtol=1e-14)
+    # eps = 0: scale invariant, and the normalized row has unit mean square before the weight
+    x = r.standard_normal((4, C))
+    np.testing.assert_allclose(oracle.rmsnorm(7.0 * x, w, 0.0), oracle.rmsnorm(x, w, 0.0), rtol=1e-13)
+    np.testing.assert_allclose(np.mean(oracle.rmsnorm(x, np.ones(C), 0.0) ** 2, axis=1), 1.0, rtol=1e-13)
+    # a one-hot row e_j * a: mean square a^2 / C
+    e = np.zeros((1, C))
+    e[0, 5] = -2.0
+    y = oracle.rmsnorm(e, w, 0.0)
+    assert y[0, 5] == pytest.approx(-np.sqrt(C) * w[5], rel=1e-14) and np.count_nonzero(y) == 1
