@@ -169,6 +169,49 @@ int mamba_rmsnorm_fwd(const void *x, const float *w, void *y, int64_t M, int64_t
                       mamba_dtype_t io, void *hip_stream);
 
 /*
+ * One whole Mamba block of the drafter (Mamba-130M shape in the paper, Sec. 3.1), built from the
+ * entry points above; bf16 activations, fp32 parameters of the SSM core, bf16 projection weights:
+ *   u = rmsnorm(hidden) ; [x | z] = u W_in^T ; x_c = silu(conv1d(x)) ;
+ *   [dt_low | B | C] = x_c W_x^T ; dt = dt_low W_dt^T ; y = selective_scan(x_c, dt, A, B, C, D, z, dt_bias) ;
+ *   hidden_out = hidden + y W_out^T
+ * Tensors between the stages live in the workspace in bf16 (rounded once when stored).
+ *
+ * mamba_block_fwd encodes L tokens of `batch` sequences (prefill): hidden, hidden_out (batch,L,d_model);
+ * conv_state_in / h0 (nullable) carry a previous piece of the sequence, conv_state_out / h_final
+ * (nullable) receive the states after the last token.  hidden_out may be hidden itself.
+ * mamba_block_step advances n_out draft branches by one token (decode): branch j continues from
+ * the states of branch parent_idx[j] of the source caches (n_in rows); with parent_idx NULL the
+ * step is in place (sources == destinations, n_in == n_out).  hidden, hidden_out: (n_out, d_model).
+ * workspace: device memory of at least mamba_block_workspace_bytes(p, rows) bytes for
+ * rows = batch * L (or n_out), 16-byte aligned.  d_model, d_inner, dt_rank multiples of 8.
+ */
+typedef struct {
+    int64_t d_model, d_inner, d_state, dt_rank;
+    int32_t d_conv;
+    float eps;                 /* RMSNorm epsilon */
+    const float *norm_w;       /* (d_model)                                              */
+    const void *in_proj_w;     /* (2 d_inner, d_model) bf16: rows of x, then rows of z   */
+    const float *conv_w;       /* (d_inner, d_conv)                                      */
+    const float *conv_b;       /* (d_inner) or NULL                                      */
+    const void *x_proj_w;      /* (dt_rank + 2 d_state, d_inner) bf16: dt_low | B | C    */
+    const void *dt_proj_w;     /* (d_inner, dt_rank) bf16                                */
+    const float *dt_bias;      /* (d_inner)                                              */
+    const float *A;            /* (d_inner, d_state)                                     */
+    const float *Dskip;        /* (d_inner)                                              */
+    const void *out_proj_w;    /* (d_model, d_inner) bf16                                */
+} mamba_block_params_t;
+
+size_t mamba_block_workspace_bytes(const mamba_block_params_t *p, int64_t batch, int64_t L);
+int mamba_block_fwd(const mamba_block_params_t *p, const void *hidden, void *hidden_out,
+                    const void *conv_state_in, void *conv_state_out, const float *h0,
+                    float *h_final, void *workspace, size_t workspace_bytes, int64_t batch,
+                    int64_t L, void *hip_stream);
+int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hidden_out,
+                     const void *conv_src, void *conv_dst, const float *ssm_src, float *ssm_dst,
+                     const int32_t *parent_idx, void *workspace, size_t workspace_bytes,
+                     int64_t n_out, int64_t n_in, void *hip_stream);
+
+/*
  * Batch-wise state caches of a draft tree (Sec. 4.1, "efficient cache utilization for batch
  * generation": for a tree configuration T = (N_1..N_gamma) the batch size at draft position i is
  * B_i = N_1 * ... * N_i; one state cache per possible batch size is allocated in advance so that

@@ -203,3 +203,37 @@ def rmsnorm(x, w, eps):
     x = np.asarray(x, dtype=np.float64)
     ms = np.mean(x * x, axis=-1, keepdims=True)
     return x / np.sqrt(ms + float(eps)) * np.asarray(w, dtype=np.float64)
+
+
+def _round_bf16(a):
+    """float64 -> nearest bfloat16 value (ties to even), as float64: the rounding a tensor gets when a
+    stage stores it in bf16."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32)
+    r = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return (((u + r) >> np.uint32(16)) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def block_fwd(w, hidden, conv_state_in=None, h0=None, eps=1e-5, round_between=True):
+    """One Mamba block on (B,L,d_model) float64 activations: rmsnorm, in_proj -> x | z, conv1d + silu,
+    x_proj -> dt_low | B | C, dt_proj, selective scan gated by silu(z), out_proj, residual.
+    round_between=True rounds every tensor that passes between two stages to bf16 (the storage
+    type of the activations); False evaluates the block in float64 throughout.
+    ``w``: norm_w, in_proj_w (2D,dm), conv_w, conv_b, x_proj_w (R+2N,D), dt_proj_w (D,R), dt_bias, A,
+    Dskip, out_proj_w (dm,D), all float64 values.  Returns hidden_out, conv_state, ssm_state."""
+    rb = _round_bf16 if round_between else (lambda a: np.asarray(a, dtype=np.float64))
+    B, L, dm = hidden.shape
+    D, N = w["A"].shape
+    R = w["dt_proj_w"].shape[1]
+    u = rb(rmsnorm(hidden.reshape(B * L, dm), w["norm_w"], eps))
+    xz = rb(linear(u, w["in_proj_w"]))
+    x, z = xz[:, :D].reshape(B, L, D), xz[:, D:].reshape(B, L, D)
+    xc, conv_state = conv1d_fwd(x, w["conv_w"], w.get("conv_b"), conv_state_in, apply_silu=True)
+    xc = rb(xc)
+    proj = rb(linear(xc.reshape(B * L, D), w["x_proj_w"]))
+    dtl, Bm, Cm = proj[:, :R], proj[:, R:R + N].reshape(B, L, N), proj[:, R + N:].reshape(B, L, N)
+    dt = rb(linear(dtl, w["dt_proj_w"])).reshape(B, L, D)
+    y, h_final = scan_fwd(xc, dt, w["A"], Bm, Cm, w["Dskip"], z, w["dt_bias"], h0)
+    y = rb(y)
+    out = linear(y.reshape(B * L, D), w["out_proj_w"], None, hidden.reshape(B * L, dm)).reshape(B, L, dm)
+    return out, conv_state, h_final

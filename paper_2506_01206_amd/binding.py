@@ -42,8 +42,25 @@ class TreePlan(ctypes.Structure):
                 ("total_bytes", ctypes.c_int64)]
 
 
+class BlockParams(ctypes.Structure):
+    """mamba_block_params_t of include/mamba_hip.h."""
+    _fields_ = [("d_model", ctypes.c_int64), ("d_inner", ctypes.c_int64), ("d_state", ctypes.c_int64),
+                ("dt_rank", ctypes.c_int64), ("d_conv", ctypes.c_int32), ("eps", ctypes.c_float),
+                ("norm_w", ctypes.c_void_p), ("in_proj_w", ctypes.c_void_p), ("conv_w", ctypes.c_void_p),
+                ("conv_b", ctypes.c_void_p), ("x_proj_w", ctypes.c_void_p), ("dt_proj_w", ctypes.c_void_p),
+                ("dt_bias", ctypes.c_void_p), ("A", ctypes.c_void_p), ("Dskip", ctypes.c_void_p),
+                ("out_proj_w", ctypes.c_void_p)]
+
+
 def _declare(lib):
     """Attach the C signatures of include/mamba_hip.h to a loaded library."""
+    _bpp = ctypes.POINTER(BlockParams)
+    lib.mamba_block_workspace_bytes.argtypes = [_bpp, _i64, _i64]
+    lib.mamba_block_workspace_bytes.restype = _sz
+    lib.mamba_block_fwd.argtypes = [_bpp] + [_vp] * 7 + [_sz, _i64, _i64, _vp]
+    lib.mamba_block_fwd.restype = _int
+    lib.mamba_block_step.argtypes = [_bpp] + [_vp] * 8 + [_sz, _i64, _i64, _vp]
+    lib.mamba_block_step.restype = _int
     lib.mamba_tree_plan.argtypes = [ctypes.POINTER(ctypes.c_int32), _int, _i64, _i64, _i64, _int, _int,
                                     ctypes.POINTER(TreePlan)]
     lib.mamba_tree_plan.restype = _int
@@ -72,7 +89,8 @@ lib = _declare(ctypes.CDLL(LIB_PATH))
 
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
            "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork", "mamba_tree_plan",
-           "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd")
+           "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "mamba_block_workspace_bytes",
+           "mamba_block_fwd", "mamba_block_step")
 
 
 class MambaError(RuntimeError):
@@ -266,3 +284,87 @@ def mamba_rmsnorm_fwd(x, w, eps=1e-5, y=None, stream=None):
                                M, C, float(eps), _io_code(x), _stream(stream))
     _check("mamba_rmsnorm_fwd", st)
     return y
+
+
+class Block:
+    """Parameters of one Mamba block on the device (a mamba_block_params_t plus the tensors it points
+    to, kept alive).  ``w`` maps names to device tensors: norm_w (d_model) f32, in_proj_w (2 d_inner,
+    d_model) bf16, conv_w (d_inner, d_conv) f32, conv_b (d_inner) f32 or None, x_proj_w (dt_rank + 2
+    d_state, d_inner) bf16, dt_proj_w (d_inner, dt_rank) bf16, dt_bias, Dskip (d_inner) f32, A (d_inner,
+    d_state) f32, out_proj_w (d_model, d_inner) bf16."""
+
+    def __init__(self, w, eps=1e-5):
+        self.w = dict(w)
+        d_inner, d_conv = w["conv_w"].shape
+        d_model = w["norm_w"].shape[0]
+        d_state = w["A"].shape[1]
+        dt_rank = w["dt_proj_w"].shape[1]
+        f32, bf = torch.float32, torch.bfloat16
+        self.c = BlockParams(
+            d_model, d_inner, d_state, dt_rank, d_conv, float(eps),
+            _ptr(w["norm_w"], f32, (d_model,), "norm_w"), _ptr(w["in_proj_w"], bf, (2 * d_inner, d_model), "in_proj_w"),
+            _ptr(w["conv_w"], f32, name="conv_w"), _ptr(w.get("conv_b"), f32, (d_inner,), "conv_b"),
+            _ptr(w["x_proj_w"], bf, (dt_rank + 2 * d_state, d_inner), "x_proj_w"),
+            _ptr(w["dt_proj_w"], bf, (d_inner, dt_rank), "dt_proj_w"), _ptr(w["dt_bias"], f32, (d_inner,), "dt_bias"),
+            _ptr(w["A"], f32, (d_inner, d_state), "A"), _ptr(w["Dskip"], f32, (d_inner,), "Dskip"),
+            _ptr(w["out_proj_w"], bf, (d_model, d_inner), "out_proj_w"))
+        self.d_model, self.d_inner, self.d_state, self.dt_rank, self.d_conv = d_model, d_inner, d_state, dt_rank, d_conv
+
+
+def mamba_block_workspace_bytes(block: Block, batch, L) -> int:
+    return int(lib.mamba_block_workspace_bytes(ctypes.byref(block.c), batch, L))
+
+
+def mamba_block_fwd(block: Block, hidden, hidden_out=None, conv_state_in=None, h0=None, conv_state_out=None,
+                    h_final=None, workspace=None, want_state=True, stream=None):
+    """hidden (B,L,d_model) bf16 -> hidden + mixer(rmsnorm(hidden)); also the conv and SSM states."""
+    B, L, dm = hidden.shape
+    D, N, K = block.d_inner, block.d_state, block.d_conv
+    if hidden_out is None:
+        hidden_out = torch.empty_like(hidden)
+    if want_state and conv_state_out is None:
+        conv_state_out = torch.empty((B, D, K - 1), dtype=hidden.dtype, device=hidden.device)
+    if want_state and h_final is None:
+        h_final = torch.empty((B, D, N), dtype=torch.float32, device=hidden.device)
+    need = mamba_block_workspace_bytes(block, B, L)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=hidden.device)
+    st = lib.mamba_block_fwd(
+        ctypes.byref(block.c), _ptr(hidden, torch.bfloat16, name="hidden"),
+        _ptr(hidden_out, torch.bfloat16, (B, L, dm), "hidden_out"),
+        _ptr(conv_state_in, torch.bfloat16, (B, D, K - 1), "conv_state_in"),
+        _ptr(conv_state_out, torch.bfloat16, (B, D, K - 1), "conv_state_out"),
+        _ptr(h0, torch.float32, (B, D, N), "h0"), _ptr(h_final, torch.float32, (B, D, N), "h_final"),
+        _ptr(workspace, name="workspace"), workspace.numel() * workspace.element_size(), B, L, _stream(stream))
+    _check("mamba_block_fwd", st)
+    return hidden_out, conv_state_out, h_final
+
+
+def mamba_block_step(block: Block, hidden, conv_src, ssm_src, parent_idx=None, conv_dst=None, ssm_dst=None,
+                     hidden_out=None, workspace=None, stream=None):
+    """One token for n_out draft branches: hidden (n_out,d_model); states (n_in,D,K-1) / (n_in,D,N).
+    With parent_idx the children's states go to conv_dst / ssm_dst; without, the step is in place."""
+    n_out, dm = hidden.shape
+    n_in = conv_src.shape[0]
+    D, N, K = block.d_inner, block.d_state, block.d_conv
+    if hidden_out is None:
+        hidden_out = torch.empty_like(hidden)
+    if parent_idx is None:
+        conv_dst, ssm_dst = conv_src, ssm_src
+    else:
+        if conv_dst is None:
+            conv_dst = torch.empty((n_out, D, K - 1), dtype=conv_src.dtype, device=hidden.device)
+        if ssm_dst is None:
+            ssm_dst = torch.empty((n_out, D, N), dtype=torch.float32, device=hidden.device)
+    need = mamba_block_workspace_bytes(block, n_out, 1)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=hidden.device)
+    st = lib.mamba_block_step(
+        ctypes.byref(block.c), _ptr(hidden, torch.bfloat16, name="hidden"),
+        _ptr(hidden_out, torch.bfloat16, (n_out, dm), "hidden_out"),
+        _ptr(conv_src, torch.bfloat16, (n_in, D, K - 1), "conv_src"), _ptr(conv_dst, torch.bfloat16, (n_out, D, K - 1), "conv_dst"),
+        _ptr(ssm_src, torch.float32, (n_in, D, N), "ssm_src"), _ptr(ssm_dst, torch.float32, (n_out, D, N), "ssm_dst"),
+        _ptr(parent_idx, torch.int32, (n_out,), "parent_idx"), _ptr(workspace, name="workspace"),
+        workspace.numel() * workspace.element_size(), n_out, n_in, _stream(stream))
+    _check("mamba_block_step", st)
+    return hidden_out, conv_dst, ssm_dst

@@ -251,6 +251,132 @@ int mamba_rmsnorm_fwd(const void *x, const float *w, void *y, int64_t M, int64_t
     return (int)launch_rmsnorm(a, static_cast<hipStream_t>(hip_stream));
 }
 
+namespace {
+
+struct BlockBuffers {
+    char *a, *b, *c, *d;        // four (rows, d_inner) bf16 buffers: x then dt | z | x_c | normed then y
+    char *dtl, *bm, *cm;        // (rows, dt_rank), (rows, d_state), (rows, d_state) bf16
+    char *scan_ws;
+    size_t scan_ws_bytes, total;
+};
+
+int64_t align256(int64_t v) { return (v + 255) / 256 * 256; }
+
+// lays the intermediate tensors of a block out in the workspace; false on a size overflow
+bool block_layout(const mamba_block_params_t *p, int64_t batch, int64_t L, void *base, BlockBuffers *bb)
+{
+    int64_t rows, big, dtl, bc;
+    if (!mul_ok(batch, L, &rows)) return false;
+    const int64_t wide = p->d_inner > p->d_model ? p->d_inner : p->d_model;
+    if (!size3(rows, wide, 1, 2, &big) || !size3(rows, p->dt_rank, 1, 2, &dtl) || !size3(rows, p->d_state, 1, 2, &bc))
+        return false;
+    int64_t cl, nc;
+    scan_plan(batch, L, p->d_inner, p->d_state, 0, &cl, &nc);
+    const size_t sws = scan_workspace_bytes(batch, p->d_inner, p->d_state, nc);
+    char *q = static_cast<char *>(base);
+    int64_t off = 0;
+    auto take = [&](int64_t n) { char *r = q + off; off += align256(n); return r; };
+    bb->a = take(big); bb->b = take(big); bb->c = take(big); bb->d = take(big);
+    bb->dtl = take(dtl); bb->bm = take(bc); bb->cm = take(bc);
+    bb->scan_ws = take((int64_t)sws);
+    bb->scan_ws_bytes = sws;
+    bb->total = (size_t)off;
+    return true;
+}
+
+int block_params_ok(const mamba_block_params_t *p)
+{
+    if (!p) return MAMBA_ERR_NULL_POINTER;
+    if (p->d_model < 1 || p->d_inner < 1 || p->d_state < 1 || p->dt_rank < 1 || !(p->eps >= 0.0f)) return MAMBA_ERR_BAD_SHAPE;
+    if (!n_supported(p->d_state) || !k_supported(p->d_conv) || p->d_model % 8 || p->d_inner % 8 || p->dt_rank % 8 ||
+        p->d_model > 4096)
+        return MAMBA_ERR_UNSUPPORTED;
+    if (!p->norm_w || !p->in_proj_w || !p->conv_w || !p->x_proj_w || !p->dt_proj_w || !p->A || !p->out_proj_w)
+        return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(p->norm_w) || !aligned16(p->in_proj_w) || !aligned16(p->conv_w) || !aligned16(p->conv_b) ||
+        !aligned16(p->x_proj_w) || !aligned16(p->dt_proj_w) || !aligned16(p->dt_bias) || !aligned16(p->A) ||
+        !aligned16(p->Dskip) || !aligned16(p->out_proj_w))
+        return MAMBA_ERR_MISALIGNED;
+    return MAMBA_OK;
+}
+
+}  // namespace
+
+size_t mamba_block_workspace_bytes(const mamba_block_params_t *p, int64_t batch, int64_t L)
+{
+    if (block_params_ok(p) != MAMBA_OK || batch <= 0 || L <= 0) return 0;
+    BlockBuffers bb;
+    if (!block_layout(p, batch, L, nullptr, &bb)) return 0;
+    return bb.total;
+}
+
+int mamba_block_fwd(const mamba_block_params_t *p, const void *hidden, void *hidden_out,
+                    const void *conv_state_in, void *conv_state_out, const float *h0, float *h_final,
+                    void *workspace, size_t workspace_bytes, int64_t batch, int64_t L, void *hip_stream)
+{
+    const int st = block_params_ok(p);
+    if (st != MAMBA_OK) return st;
+    if (batch < 0 || L < 0) return MAMBA_ERR_BAD_SHAPE;
+    if (batch == 0 || L == 0) return MAMBA_OK;
+    if (!hidden || !hidden_out) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(hidden) || !aligned16(hidden_out) || !aligned16(workspace)) return MAMBA_ERR_MISALIGNED;
+    BlockBuffers bb;
+    if (!block_layout(p, batch, L, workspace, &bb)) return MAMBA_ERR_BAD_SHAPE;
+    if (!workspace || workspace_bytes < bb.total) return MAMBA_ERR_WORKSPACE;
+    const int64_t rows = batch * L, Di = p->d_inner, N = p->d_state, R = p->dt_rank;
+    const mamba_dtype_t io = MAMBA_BF16;
+    int rc;
+    // u = rmsnorm(hidden)                                   -> d
+    if ((rc = mamba_rmsnorm_fwd(hidden, p->norm_w, bb.d, rows, p->d_model, p->eps, io, hip_stream))) return rc;
+    // [x | z] = u W_in^T                                    -> a, b
+    if ((rc = mamba_linear_fwd(bb.d, p->in_proj_w, nullptr, nullptr, bb.a, Di, bb.b, Di, nullptr, 0, rows, p->d_model, io, hip_stream))) return rc;
+    // x_c = silu(conv1d(x))                                 -> c
+    if ((rc = mamba_conv1d_fwd(bb.a, p->conv_w, p->conv_b, conv_state_in, bb.c, conv_state_out, batch, L, Di, p->d_conv, 1, io, hip_stream))) return rc;
+    // [dt_low | B | C] = x_c W_x^T
+    if ((rc = mamba_linear_fwd(bb.c, p->x_proj_w, nullptr, nullptr, bb.dtl, R, bb.bm, N, bb.cm, N, rows, Di, io, hip_stream))) return rc;
+    // dt = dt_low W_dt^T                                    -> a (x is dead)
+    if ((rc = mamba_linear_fwd(bb.dtl, p->dt_proj_w, nullptr, nullptr, bb.a, Di, nullptr, 0, nullptr, 0, rows, R, io, hip_stream))) return rc;
+    // y = scan(...) gated by silu(z)                        -> d (u is dead)
+    if ((rc = mamba_scan_fwd(bb.c, bb.a, p->A, bb.bm, bb.cm, p->Dskip, bb.b, p->dt_bias, h0, bb.d, h_final,
+                             bb.scan_ws_bytes ? bb.scan_ws : nullptr, bb.scan_ws_bytes, batch, L, Di, N, 0, 1, io, hip_stream)))
+        return rc;
+    // hidden_out = hidden + y W_out^T
+    return mamba_linear_fwd(bb.d, p->out_proj_w, nullptr, hidden, hidden_out, p->d_model, nullptr, 0, nullptr, 0, rows, Di, io, hip_stream);
+}
+
+int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hidden_out, const void *conv_src,
+                     void *conv_dst, const float *ssm_src, float *ssm_dst, const int32_t *parent_idx,
+                     void *workspace, size_t workspace_bytes, int64_t n_out, int64_t n_in, void *hip_stream)
+{
+    const int st = block_params_ok(p);
+    if (st != MAMBA_OK) return st;
+    if (n_out < 0 || n_in < 0 || (n_out > 0 && n_in == 0)) return MAMBA_ERR_BAD_SHAPE;
+    if (!parent_idx && (n_in != n_out || conv_src != conv_dst || ssm_src != ssm_dst)) return MAMBA_ERR_BAD_SHAPE;
+    if (parent_idx && (conv_src == conv_dst || ssm_src == ssm_dst)) return MAMBA_ERR_ALIAS;
+    if (n_out == 0) return MAMBA_OK;
+    if (!hidden || !hidden_out || !conv_src || !conv_dst || !ssm_src || !ssm_dst) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(hidden) || !aligned16(hidden_out) || !aligned16(workspace)) return MAMBA_ERR_MISALIGNED;
+    BlockBuffers bb;
+    if (!block_layout(p, n_out, 1, workspace, &bb)) return MAMBA_ERR_BAD_SHAPE;
+    if (!workspace || workspace_bytes < bb.total) return MAMBA_ERR_WORKSPACE;
+    const int64_t Di = p->d_inner, N = p->d_state, R = p->dt_rank;
+    const mamba_dtype_t io = MAMBA_BF16;
+    int rc;
+    if ((rc = mamba_rmsnorm_fwd(hidden, p->norm_w, bb.d, n_out, p->d_model, p->eps, io, hip_stream))) return rc;
+    if ((rc = mamba_linear_fwd(bb.d, p->in_proj_w, nullptr, nullptr, bb.a, Di, bb.b, Di, nullptr, 0, n_out, p->d_model, io, hip_stream))) return rc;
+    // children take their parent's conv window, then the window is shifted in place in the destination cache
+    if (parent_idx &&
+        (rc = mamba_state_fork(conv_dst, conv_src, nullptr, nullptr, parent_idx, 1, n_out, n_in, Di, N, p->d_conv, io, hip_stream)))
+        return rc;
+    if ((rc = mamba_conv1d_fwd(bb.a, p->conv_w, p->conv_b, conv_dst, bb.c, conv_dst, n_out, 1, Di, p->d_conv, 1, io, hip_stream))) return rc;
+    if ((rc = mamba_linear_fwd(bb.c, p->x_proj_w, nullptr, nullptr, bb.dtl, R, bb.bm, N, bb.cm, N, n_out, Di, io, hip_stream))) return rc;
+    if ((rc = mamba_linear_fwd(bb.dtl, p->dt_proj_w, nullptr, nullptr, bb.a, Di, nullptr, 0, nullptr, 0, n_out, R, io, hip_stream))) return rc;
+    if ((rc = mamba_state_step(ssm_dst, ssm_src, parent_idx, bb.c, bb.a, p->A, bb.bm, bb.cm, p->Dskip, bb.b, p->dt_bias, bb.d,
+                               n_out, n_in, Di, N, 1, io, hip_stream)))
+        return rc;
+    return mamba_linear_fwd(bb.d, p->out_proj_w, nullptr, hidden, hidden_out, p->d_model, nullptr, 0, nullptr, 0, n_out, Di, io, hip_stream);
+}
+
 int mamba_tree_plan(const int32_t *tree, int gamma, int64_t n_layers, int64_t D, int64_t N, int K,
                     mamba_dtype_t conv_dtype, mamba_tree_plan_t *plan)
 {

@@ -140,3 +140,19 @@ def tree_parents(tree):
     node p at depth i occupy slots p*N_i .. p*N_i + N_i - 1, so parent[j] = j // N_i."""
     return [np.arange(b, dtype=np.int32) // np.int32(n)
             for b, n in zip(tree_batch_sizes(tree), tree)]
+
+
+def block_weights(rng: np.random.Generator, d_model: int, D: int, N: int, K: int, dt_rank: int):
+    """Random weights of one Mamba block in storage form: the SSM-core parameters of ``layer_params``
+    plus RMSNorm weight ~ 1 + 0.1 N(0,1) (fp32) and projection matrices ~ N(0, 1/fan_in) as bf16 bit
+    patterns: in_proj (2D, d_model), x_proj (dt_rank + 2N, D), dt_proj (D, dt_rank), out_proj (d_model, D)."""
+    w = layer_params(rng, D, N, K, random_A=True)
+    w["conv_b"] = (0.1 * rng.standard_normal(D)).astype(np.float32)
+    w.pop("conv_bias")
+    w["norm_w"] = (1.0 + 0.1 * rng.standard_normal(d_model)).astype(np.float32)
+    mat = lambda n, k: f32_to_bf16_bits((rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32))
+    w["in_proj_w"] = mat(2 * D, d_model)
+    w["x_proj_w"] = mat(dt_rank + 2 * N, D)
+    w["dt_proj_w"] = mat(D, dt_rank)
+    w["out_proj_w"] = mat(d_model, D)
+    return w

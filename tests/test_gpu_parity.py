@@ -728,3 +728,68 @@ def test_rmsnorm_against_oracle(m, M, C):
     xin = to_dev(x)
     m.mamba_rmsnorm_fwd(xin, to_dev(w), eps=1e-5, y=xin)                                   # in place
     assert torch.equal(xin, y)
+
+
+# ------------------------------------------------------------------------------------ whole block
+def make_block(m, rng, dm, D, N, K, R):
+    w = synth.block_weights(rng, dm, D, N, K, R)
+    dev = {k: to_dev(v) for k, v in w.items()}
+    return w, {k: W(v) for k, v in w.items()}, m.Block(dev, eps=1e-5)
+
+
+@pytest.mark.parametrize("B,L,dm,D,N,K,R", [(2, 96, 64, 128, 16, 4, 8), (1, 700, 768, 1536, 16, 4, 48),
+                                           (3, 33, 256, 512, 8, 3, 16)])
+def test_block_prefill_against_oracle(m, B, L, dm, D, N, K, R):
+    """RMSNorm -> in_proj -> conv1d -> x_proj -> dt_proj -> selective scan -> out_proj + residual as one
+    call; the oracle rounds the tensors between stages to bf16 as the workspace does.  Also checked
+    in two pieces with carried conv / SSM states."""
+    say(B=B, L=L, dm=dm, D=D, N=N, K=K, R=R)
+    rng = np.random.default_rng(B * 1000 + L + D)
+    w, w64, blk = make_block(m, rng, dm, D, N, K, R)
+    hid = synth.to_io(rng.standard_normal((B, L, dm)).astype(np.float32), synth.BF16)
+    out, cst, hf = m.mamba_block_fwd(blk, to_dev(hid))
+    ro, rc, rh = oracle.block_fwd(w64, W(hid))
+    tol = TOL[synth.BF16]
+    assert_close(values(to_host(out)), ro, tol, "block out")
+    assert_close(to_host(hf), rh, tol, "block ssm state")
+    # the conv state holds bf16 values of x; a rounding flip upstream moves one by at most an ulp
+    assert_close(values(to_host(cst)), rc, tol, "block conv state")
+    # the unrounded float64 block stays close as well (looser: six bf16 roundings on the way)
+    ro64, _, rh64 = oracle.block_fwd(w64, W(hid), round_between=False)
+    assert_close(values(to_host(out)), ro64, 3 * tol, "block out vs unrounded float64")
+    # two pieces with carried states
+    cut = L // 3
+    h = to_dev(hid)
+    o1, c1, s1 = m.mamba_block_fwd(blk, h[:, :cut].contiguous())
+    o2, c2, s2 = m.mamba_block_fwd(blk, h[:, cut:].contiguous(), conv_state_in=c1, h0=s1)
+    assert_close(values(to_host(torch.cat([o1, o2], 1))), ro, tol, "block pieces out")
+    assert_close(to_host(s2), rh, tol, "block pieces state")
+    # in place on the residual stream
+    h2 = h.clone()
+    m.mamba_block_fwd(blk, h2, hidden_out=h2)
+    assert torch.equal(h2, out)
+
+
+@pytest.mark.parametrize("tree", [(3, 2, 1), (1, 1), (4,)])
+def test_block_decode_steps_against_oracle(m, tree):
+    """Tree drafting through whole blocks: at every draft position each branch continues from its
+    parent's conv and SSM state (fork fused into the step) and produces the next hidden row."""
+    dm, D, N, K, R = 768, 1536, 16, 4, 48
+    rng = np.random.default_rng(sum(tree) + 100)
+    w, w64, blk = make_block(m, rng, dm, D, N, K, R)
+    conv = synth.to_io(rng.standard_normal((1, D, K - 1)).astype(np.float32), synth.BF16)
+    ssm = rng.standard_normal((1, D, N)).astype(np.float32)
+    g_conv, g_ssm = to_dev(conv), to_dev(ssm)
+    r_conv, r_ssm = W(conv), ssm.astype(np.float64)
+    tol = TOL[synth.BF16]
+    for n_i, b_i, par in zip(tree, synth.tree_batch_sizes(tree), synth.tree_parents(tree)):
+        hid = synth.to_io(rng.standard_normal((b_i, dm)).astype(np.float32), synth.BF16)
+        if n_i > 1:
+            out, g_conv, g_ssm = m.mamba_block_step(blk, to_dev(hid), g_conv, g_ssm, parent_idx=to_dev(par))
+        else:
+            out, g_conv, g_ssm = m.mamba_block_step(blk, to_dev(hid), g_conv, g_ssm)       # in place
+        ro, r_conv, r_ssm = oracle.block_fwd(w64, W(hid)[:, None, :], conv_state_in=r_conv[par], h0=r_ssm[par])
+        assert_close(values(to_host(out)), ro[:, 0], tol, "block step out (batch %d)" % b_i)
+        assert_close(to_host(g_ssm), r_ssm, tol, "block step ssm")
+        assert_close(values(to_host(g_conv)), r_conv, tol, "block step conv")
+        r_conv = W(synth.to_io(r_conv.astype(np.float32), synth.BF16))
