@@ -8,12 +8,15 @@
 // split over up to three contiguous output tensors (in_proj -> x | z; x_proj -> dt_low | B | C), so
 // that the consumers get the dense (tokens, features) tensors they expect without a copy.
 //
-// Tiling: a workgroup of 4 wavefronts owns a 128 x 128 output tile, each wavefront a 64 x 64
-// quadrant as 2 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (64 fp32 accumulators per lane).  K is
-// walked in slabs of 32: the x and w slabs (128 rows x 64 B each) are fetched with 16-byte loads
-// one slab ahead into registers, parked in one of two LDS buffers (rows padded to 80 B), and read
-// back as MFMA fragments with 16-byte LDS reads: lane l holds row l % 32, k = 8 * (l / 32) .. + 7.
+// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a BM x 128 output tile, BM = 128 or 64; each
+// wavefront a (BM/2) x 64 part as MFMA tiles of v_mfma_f32_32x32x16_bf16.  K is walked in slabs of
+// 64: the x and w slabs (rows of 128 B, one cache line each) are fetched with 16-byte loads one
+// slab ahead into registers, parked in LDS (rows padded to 144 B) and read back as MFMA fragments
+// with 16-byte LDS reads: lane l holds row l % 32, k = 8 * (l / 32) .. + 7 of each k16 step.
 // Rows past M or N re-read the last valid row and are never stored; a K tail is zero-filled.
+// Epilogue: the accumulators (+ bias) are rounded to bf16 into LDS, then leave as 16-byte row
+// chunks (+ residual), so that stores are coalesced; output splits that are not multiples of 8
+// columns take an element-wise path.
 #include "device_math.h"
 #include "launch.h"
 
@@ -23,138 +26,158 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 128, kBN = 128, kBK = 32;
+constexpr int kBN = 128, kBK = 64;
 constexpr int kThreads = 256;
-constexpr int kRowBytes = 80;                 // 64 B of data + 16 B pad against bank conflicts
-constexpr int kTileBytes = 128 * kRowBytes;   // one operand slab in LDS
+constexpr int kRowBytes = kBK * 2 + 16;       // 128 B of data + 16 B pad against bank conflicts
+constexpr int kOutRowBytes = kBN * 2 + 16;    // staged output tile rows
 
 struct OutSplit {
     bf16_t *ptr[3];
     int64_t width[3];
 };
 
-__device__ __forceinline__ void store_out(const OutSplit &o, int64_t m, int64_t n, float v)
+// column n of the virtual (M, N) output -> tensor and column inside it
+__device__ __forceinline__ int locate(const OutSplit &o, int64_t n, int64_t *col)
 {
     int64_t c = n;
-#pragma unroll
-    for (int s = 0; s < 3; ++s) {
-        if (c < o.width[s]) {
-            o.ptr[s][m * o.width[s] + c] = (bf16_t)f32_to_bf16(v);
-            return;
-        }
-        c -= o.width[s];
-    }
+    int s = 0;
+    if (c >= o.width[0]) { c -= o.width[0]; s = 1; if (c >= o.width[1]) { c -= o.width[1]; s = 2; } }
+    *col = c;
+    return s;
 }
 
-__device__ __forceinline__ float load_res(const OutSplit &o, const bf16_t *const *res, int64_t m, int64_t n)
-{
-    int64_t c = n;
-#pragma unroll
-    for (int s = 0; s < 3; ++s) {
-        if (c < o.width[s]) return res[s] ? bf16_to_f32(res[s][m * o.width[s] + c]) : 0.0f;
-        c -= o.width[s];
-    }
-    return 0.0f;
-}
-
-// grid: (ceil(N / 128), ceil(M / 128))
+// grid: (ceil(N / 128), ceil(M / BM))
+template <int BM>
 __global__ void __launch_bounds__(kThreads)
 linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const float *__restrict__ bias,
-              const bf16_t *res0, OutSplit out, int64_t M, int64_t N, int64_t K)
+              const bf16_t *residual, OutSplit out, int64_t M, int64_t N, int64_t K, int vector_out)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][2][kTileBytes];  // [buffer][x | w]
+    constexpr int MT = BM / 64;                               // 32-row MFMA tiles per wavefront along m
+    constexpr int kOperandBytes = (BM + kBN) * kRowBytes;
+    constexpr int kStageBytes = BM * kOutRowBytes;
+    constexpr int kLdsBytes = kOperandBytes > kStageBytes ? kOperandBytes : kStageBytes;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kLdsBytes];
+    unsigned char *lds_x = lds, *lds_w = lds + BM * kRowBytes;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;                  // quadrant of the wavefront
-    const int64_t m0 = (int64_t)blockIdx.y * kBM, n0 = (int64_t)blockIdx.x * kBN;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * kBN;
 
-    // global -> LDS staging: 128 rows x 4 chunks of 16 B per operand, 2 chunks per thread each
-    int ld_row[2], ld_chunk[2];
-    const uint4 *xg[2], *wg[2];
+    // global -> LDS staging: (BM + 128) rows x 8 chunks of 16 B, NCH chunks per thread
+    constexpr int NCH = (BM + kBN) * 8 / kThreads;
+    const uint4 *src[NCH];
+    int dst_off[NCH], chunk[NCH];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int c = tid + i * kThreads;      // 0 .. 511
-        ld_row[i] = c >> 2;
-        ld_chunk[i] = c & 3;
-        int64_t xm = m0 + ld_row[i], wn_ = n0 + ld_row[i];
-        xm = xm < M ? xm : M - 1;
-        wn_ = wn_ < N ? wn_ : N - 1;
-        xg[i] = reinterpret_cast<const uint4 *>(x + xm * K);
-        wg[i] = reinterpret_cast<const uint4 *>(w + wn_ * K);
+    for (int i = 0; i < NCH; ++i) {
+        const int c = tid + i * kThreads;
+        const int row = c >> 3;                               // 0 .. BM + 127: x rows first, then w rows
+        chunk[i] = c & 7;
+        if (row < BM) {
+            int64_t r = m0 + row;
+            r = r < M ? r : M - 1;
+            src[i] = reinterpret_cast<const uint4 *>(x + r * K);
+        } else {
+            int64_t r = n0 + (row - BM);
+            r = r < N ? r : N - 1;
+            src[i] = reinterpret_cast<const uint4 *>(w + r * K);
+        }
+        dst_off[i] = row * kRowBytes + chunk[i] * 16;
     }
-    const int64_t kchunks = K / 8;             // K is a multiple of 8 (checked on the host)
-    auto fetch = [&](int64_t k0, uint4 *xr, uint4 *wr) {
+    const int64_t kchunks = K / 8;                            // K is a multiple of 8 (checked on the host)
+    uint4 regs[NCH];
+    auto fetch = [&](int64_t k0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int64_t ch = k0 / 8 + ld_chunk[i];
-            const bool in = ch < kchunks;
-            xr[i] = in ? xg[i][ch] : make_uint4(0, 0, 0, 0);
-            wr[i] = in ? wg[i][ch] : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < NCH; ++i) {
+            const int64_t ch = k0 / 8 + chunk[i];
+            regs[i] = ch < kchunks ? src[i][ch] : make_uint4(0, 0, 0, 0);
         }
     };
-    auto park = [&](int buf, const uint4 *xr, const uint4 *wr) {
+    auto park = [&]() {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int off = ld_row[i] * kRowBytes + ld_chunk[i] * 16;
-            *reinterpret_cast<uint4 *>(&lds[buf][0][off]) = xr[i];
-            *reinterpret_cast<uint4 *>(&lds[buf][1][off]) = wr[i];
-        }
+        for (int i = 0; i < NCH; ++i) *reinterpret_cast<uint4 *>(lds + dst_off[i]) = regs[i];
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[MT][2];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MT; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
-    uint4 xr[2], wr[2];
-    fetch(0, xr, wr);
-    park(0, xr, wr);
-    __syncthreads();
-    const int frag_row = lane & 31, frag_k = (lane >> 5) * 16;   // byte offset of the lane's 8 k values
-    int buf = 0;
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 16;    // byte offset of the lane's 8 k values
+    fetch(0);
     for (int64_t k0 = 0; k0 < K; k0 += kBK) {
-        const bool more = k0 + kBK < K;
-        if (more) fetch(k0 + kBK, xr, wr);
+        __syncthreads();                                          // everyone is done reading the last slab
+        park();
+        __syncthreads();
+        if (k0 + kBK < K) fetch(k0 + kBK);                        // in flight while this slab is multiplied
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {                          // two k16 sub-steps per slab
-            bf16x8 af[2], bfr[2];
+        for (int ks = 0; ks < kBK / 16; ++ks) {
+            bf16x8 af[MT], bfr[2];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int ar = wm * 64 + t * 32 + frag_row, br = wn * 64 + t * 32 + frag_row;
-                af[t] = *reinterpret_cast<const bf16x8 *>(&lds[buf][0][ar * kRowBytes + ks * 32 + frag_k]);
-                bfr[t] = *reinterpret_cast<const bf16x8 *>(&lds[buf][1][br * kRowBytes + ks * 32 + frag_k]);
-            }
+            for (int t = 0; t < MT; ++t)
+                af[t] = *reinterpret_cast<const bf16x8 *>(lds_x + (wm * (BM / 2) + t * 32 + frag_row) * kRowBytes + ks * 32 + frag_k);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int t = 0; t < 2; ++t)
+                bfr[t] = *reinterpret_cast<const bf16x8 *>(lds_w + (wn * 64 + t * 32 + frag_row) * kRowBytes + ks * 32 + frag_k);
+#pragma unroll
+            for (int a = 0; a < MT; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
         }
-        if (more) park(buf ^ 1, xr, wr);
-        __syncthreads();
-        buf ^= 1;
     }
 
-    // epilogue: acc[a][b][i] is C[8 * (i / 4) + 4 * (lane / 32) + i % 4][lane % 32] of its 32 x 32 tile
-    const bf16_t *res[3] = {res0, nullptr, nullptr};
+    // epilogue.  acc[a][b][i] is C[8 * (i / 4) + 4 * (lane / 32) + i % 4][lane % 32] of its 32 x 32 tile.
+    __syncthreads();                                              // operands are dead, LDS becomes the staged tile
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MT; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            const int64_t n = n0 + wn * 64 + b * 32 + (lane & 31);
-            if (n >= N) continue;
-            const float bv = bias ? bias[n] : 0.0f;
+            const int col = wn * 64 + b * 32 + (lane & 31);
+            const int64_t n = n0 + col;
+            const float bv = (bias && n < N) ? bias[n] : 0.0f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int64_t m = m0 + wm * 64 + a * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
-                if (m >= M) continue;
-                float v = acc[a][b][i] + bv;
-                if (res0) v += load_res(out, res, m, n);
-                store_out(out, m, n, v);
+                const int row = wm * (BM / 2) + a * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                *reinterpret_cast<uint16_t *>(lds + row * kOutRowBytes + col * 2) = (uint16_t)f32_to_bf16(acc[a][b][i] + bv);
             }
         }
+    __syncthreads();
+    if (vector_out) {
+        // every output width is a multiple of 8 columns: 16-byte chunks never straddle two tensors
+        constexpr int kChunks = BM * (kBN / 8);
+#pragma unroll
+        for (int c = tid; c < kChunks; c += kThreads) {
+            const int row = c / (kBN / 8), cc = c % (kBN / 8);
+            const int64_t m = m0 + row, n = n0 + cc * 8;
+            if (m >= M || n >= N) continue;
+            uint4 v = *reinterpret_cast<const uint4 *>(lds + row * kOutRowBytes + cc * 16);
+            int64_t col;
+            const int s = locate(out, n, &col);
+            const int64_t off = m * out.width[s] + col;
+            if (residual) {
+                const uint4 r = *reinterpret_cast<const uint4 *>(residual + off);   // single output: same offset
+                v.x = f32x2_to_bf16x2(bf16_lo(v.x) + bf16_lo(r.x), bf16_hi(v.x) + bf16_hi(r.x));
+                v.y = f32x2_to_bf16x2(bf16_lo(v.y) + bf16_lo(r.y), bf16_hi(v.y) + bf16_hi(r.y));
+                v.z = f32x2_to_bf16x2(bf16_lo(v.z) + bf16_lo(r.z), bf16_hi(v.z) + bf16_hi(r.z));
+                v.w = f32x2_to_bf16x2(bf16_lo(v.w) + bf16_lo(r.w), bf16_hi(v.w) + bf16_hi(r.w));
+            }
+            *reinterpret_cast<uint4 *>(out.ptr[s] + off) = v;
+        }
+    } else {
+        for (int e = tid; e < BM * kBN; e += kThreads) {
+            const int row = e / kBN, cl = e % kBN;
+            const int64_t m = m0 + row, n = n0 + cl;
+            if (m >= M || n >= N) continue;
+            float v = bf16_to_f32(*reinterpret_cast<const uint16_t *>(lds + row * kOutRowBytes + cl * 2));
+            int64_t col;
+            const int s = locate(out, n, &col);
+            const int64_t off = m * out.width[s] + col;
+            if (residual) v += bf16_to_f32(residual[off]);
+            out.ptr[s][off] = (bf16_t)f32_to_bf16(v);
+        }
+    }
 }
 
 }  // namespace
@@ -167,9 +190,18 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
         o.width[s] = a.width[s];
     }
     const int64_t N = a.width[0] + a.width[1] + a.width[2];
-    dim3 grid((unsigned)((N + kBN - 1) / kBN), (unsigned)((a.M + kBM - 1) / kBM));
-    linear_kernel<<<grid, kThreads, 0, stream>>>(static_cast<const bf16_t *>(a.x), static_cast<const bf16_t *>(a.w),
-                                                 a.bias, static_cast<const bf16_t *>(a.residual), o, a.M, N, a.K);
+    const int vec = (a.width[0] % 8 == 0 && a.width[1] % 8 == 0 && a.width[2] % 8 == 0) ? 1 : 0;
+    const int64_t ncols = (N + kBN - 1) / kBN;
+    const bf16_t *x = static_cast<const bf16_t *>(a.x), *w = static_cast<const bf16_t *>(a.w);
+    const bf16_t *res = static_cast<const bf16_t *>(a.residual);
+    // 128-row tiles when they still give every CU a few workgroups, else 64-row tiles
+    if (ncols * ((a.M + 127) / 128) >= 1024) {
+        dim3 grid((unsigned)ncols, (unsigned)((a.M + 127) / 128));
+        linear_kernel<128><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
+    } else {
+        dim3 grid((unsigned)ncols, (unsigned)((a.M + 63) / 64));
+        linear_kernel<64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
+    }
     return hipGetLastError();
 }
 
