@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-wide-step", action="store_true",
                     help="skip the separate timing of the 64-branch, D=4096 state step")
+    ap.add_argument("--no-block", action="store_true", help="skip the whole-block prefill timing")
     ap.add_argument("--no-tree-draft", action="store_true",
                     help="skip the sequential-versus-tree draft round timing")
     ap.add_argument("--eager-decode", action="store_true",
@@ -287,6 +288,36 @@ def main():
         tree_detail["tree_over_sequential"] = round(tree_detail["tree_3_2_2_1_1_ms"] /
                                                     tree_detail["sequential_1_1_1_1_1_ms"], 3)
 
+    # the whole Mamba-130M-shaped block around the core (RMSNorm, in_proj, conv1d, x_proj, dt_proj, scan,
+    # out_proj, residual; d_model 768, dt_rank 48) on the same prefill shape, and one decode step of it
+    block_detail = {}
+    if not args.no_block and pc["io"] == synth.BF16 and "dt_rank" in pc:
+        dm = D // 2
+        rngb = np.random.default_rng(909)
+        bw = {k: to_dev(v) for k, v in synth.block_weights(rngb, dm, D, N, K, pc["dt_rank"]).items()}
+        blk = m.Block(bw)
+        hid = torch.randn((B, L, dm), device=dev).to(torch.bfloat16)
+        hout = torch.empty_like(hid)
+        bws = torch.empty(max(m.mamba_block_workspace_bytes(blk, B, L), 16), dtype=torch.uint8, device=dev)
+        cso = torch.empty((B, D, K - 1), dtype=torch.bfloat16, device=dev)
+        hfo = torch.empty((B, D, N), dtype=torch.float32, device=dev)
+        run_blk = lambda: m.mamba_block_fwd(blk, hid, hidden_out=hout, conv_state_out=cso, h_final=hfo, workspace=bws)
+        for _ in range(2):
+            run_blk()
+        b0, b1 = ev(), ev()
+        b0.record()
+        for _ in range(5):
+            run_blk()
+        b1.record()
+        torch.cuda.synchronize()
+        blk_ms = b0.elapsed_time(b1) / 5
+        gemm_flops = 2.0 * B * L * (2 * D * dm + (pc["dt_rank"] + 2 * N) * D + D * pc["dt_rank"] + dm * D)
+        block_detail = {"workload": "one block, %d x %d tokens, d_model %d, d_inner %d, dt_rank %d" % (B, L, dm, D, pc["dt_rank"]),
+                        "prefill_ms": round(blk_ms, 4), "tokens_per_s": round(B * L / (blk_ms * 1e-3), 1),
+                        "ssm_core_share": round((conv_ms + scan_ms) / blk_ms, 3),
+                        "projection_GFLOP": round(gemm_flops / 1e9, 2)}
+        del hid, hout, bws
+
     tokens = B * L
     sb = scan_bytes(B, L, D, N, e)
     achieved = sb / (scan_ms * 1e-3) / 1e9
@@ -314,7 +345,7 @@ def main():
         "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
         "decode_launches": nsteps * (1 + 2 * nl), "decode_mode": "eager" if args.eager_decode else "hip_graph",
         "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide,
-        "tree_draft_round": tree_detail,
+        "tree_draft_round": tree_detail, "whole_block": block_detail,
     }
 
     result = {
