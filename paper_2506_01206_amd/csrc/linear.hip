@@ -8,11 +8,13 @@
 // split over up to three contiguous output tensors (in_proj -> x | z; x_proj -> dt_low | B | C), so
 // that the consumers get the dense (tokens, features) tensors they expect without a copy.
 //
-// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a BM x 128 output tile, BM = 128 or 64; each
-// wavefront a (BM/2) x 64 part as MFMA tiles of v_mfma_f32_32x32x16_bf16.  K is walked in slabs of
-// 64: the x and w slabs (rows of 128 B, one cache line each) are fetched with 16-byte loads one
-// slab ahead into registers, parked in LDS (rows padded to 144 B) and read back as MFMA fragments
-// with 16-byte LDS reads: lane l holds row l % 32, k = 8 * (l / 32) .. + 7 of each k16 step.
+// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a BM x BN output tile (128 x 128, or 64 x 128
+// when that is needed to give every CU a few workgroups); each wavefront a (BM/2) x (BN/2) part as
+// MFMA tiles of v_mfma_f32_32x32x16_bf16.  K is walked in slabs of BK = 64: the x and w slabs are
+// fetched with 16-byte loads one slab ahead into registers, parked in LDS (rows padded by 16 B)
+// and read back as MFMA fragments with 16-byte LDS reads: lane l holds row l % 32,
+// k = 8 * (l / 32) .. + 7 of each k16 step.  (A 128 x 256 tile halves the LDS reads per MFMA but
+// leaves one wavefront per SIMD and measured slower: three resident workgroups hide more latency.)
 // Rows past M or N re-read the last valid row and are never stored; a K tail is zero-filled.
 // Epilogue: the accumulators (+ bias) are rounded to bf16 into LDS, then leave as 16-byte row
 // chunks (+ residual), so that stores are coalesced; output splits that are not multiples of 8
@@ -26,10 +28,9 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBN = 128, kBK = 64;
 constexpr int kThreads = 256;
-constexpr int kRowBytes = kBK * 2 + 16;       // 128 B of data + 16 B pad against bank conflicts
-constexpr int kOutRowBytes = kBN * 2 + 16;    // staged output tile rows
+constexpr int kStageCols = 128;                       // the output tile is staged 128 columns at a time
+constexpr int kOutRowBytes = kStageCols * 2 + 16;
 
 struct OutSplit {
     bf16_t *ptr[3];
@@ -46,13 +47,15 @@ __device__ __forceinline__ int locate(const OutSplit &o, int64_t n, int64_t *col
     return s;
 }
 
-// grid: (ceil(N / 128), ceil(M / BM))
-template <int BM>
+// grid: (ceil(N / BN), ceil(M / BM))
+template <int BM, int BN, int BK>
 __global__ void __launch_bounds__(kThreads)
 linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const float *__restrict__ bias,
               const bf16_t *residual, OutSplit out, int64_t M, int64_t N, int64_t K, int vector_out)
 {
-    constexpr int MT = BM / 64;                               // 32-row MFMA tiles per wavefront along m
+    constexpr int MT = BM / 64, NT = BN / 64;                 // 32 x 32 MFMA tiles per wavefront along m, n
+    constexpr int kBN = BN, kBK = BK;
+    constexpr int kRowBytes = BK * 2 + 16;                    // data + 16 B pad against bank conflicts
     constexpr int kOperandBytes = (BM + kBN) * kRowBytes;
     constexpr int kStageBytes = BM * kOutRowBytes;
     constexpr int kLdsBytes = kOperandBytes > kStageBytes ? kOperandBytes : kStageBytes;
@@ -62,15 +65,16 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * kBN;
 
-    // global -> LDS staging: (BM + 128) rows x 8 chunks of 16 B, NCH chunks per thread
-    constexpr int NCH = (BM + kBN) * 8 / kThreads;
+    // global -> LDS staging: (BM + BN) rows x BK/8 chunks of 16 B, NCH chunks per thread
+    constexpr int kCpr = BK / 8;                              // chunks per row
+    constexpr int NCH = (BM + kBN) * kCpr / kThreads;
     const uint4 *src[NCH];
     int dst_off[NCH], chunk[NCH];
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         const int c = tid + i * kThreads;
-        const int row = c >> 3;                               // 0 .. BM + 127: x rows first, then w rows
-        chunk[i] = c & 7;
+        const int row = c / kCpr;                             // 0 .. BM + BN - 1: x rows first, then w rows
+        chunk[i] = c % kCpr;
         if (row < BM) {
             int64_t r = m0 + row;
             r = r < M ? r : M - 1;
@@ -96,11 +100,11 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
         for (int i = 0; i < NCH; ++i) *reinterpret_cast<uint4 *>(lds + dst_off[i]) = regs[i];
     };
 
-    f32x16 acc[MT][2];
+    f32x16 acc[MT][NT];
 #pragma unroll
     for (int a = 0; a < MT; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NT; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
@@ -113,69 +117,76 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
         if (k0 + kBK < K) fetch(k0 + kBK);                        // in flight while this slab is multiplied
 #pragma unroll
         for (int ks = 0; ks < kBK / 16; ++ks) {
-            bf16x8 af[MT], bfr[2];
+            bf16x8 af[MT], bfr[NT];
 #pragma unroll
             for (int t = 0; t < MT; ++t)
                 af[t] = *reinterpret_cast<const bf16x8 *>(lds_x + (wm * (BM / 2) + t * 32 + frag_row) * kRowBytes + ks * 32 + frag_k);
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-                bfr[t] = *reinterpret_cast<const bf16x8 *>(lds_w + (wn * 64 + t * 32 + frag_row) * kRowBytes + ks * 32 + frag_k);
+            for (int t = 0; t < NT; ++t)
+                bfr[t] = *reinterpret_cast<const bf16x8 *>(lds_w + (wn * (BN / 2) + t * 32 + frag_row) * kRowBytes + ks * 32 + frag_k);
 #pragma unroll
             for (int a = 0; a < MT; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
+                for (int b = 0; b < NT; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
         }
     }
 
     // epilogue.  acc[a][b][i] is C[8 * (i / 4) + 4 * (lane / 32) + i % 4][lane % 32] of its 32 x 32 tile.
-    __syncthreads();                                              // operands are dead, LDS becomes the staged tile
+    // The tile leaves through LDS 128 columns at a time.
 #pragma unroll
-    for (int a = 0; a < MT; ++a)
+    for (int half = 0; half < BN / kStageCols; ++half) {
+        __syncthreads();                                          // LDS (operands or the last half) is free
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int col = wn * 64 + b * 32 + (lane & 31);
-            const int64_t n = n0 + col;
-            const float bv = (bias && n < N) ? bias[n] : 0.0f;
+        for (int a = 0; a < MT; ++a)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = wm * (BM / 2) + a * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
-                *reinterpret_cast<uint16_t *>(lds + row * kOutRowBytes + col * 2) = (uint16_t)f32_to_bf16(acc[a][b][i] + bv);
+            for (int b = 0; b < NT; ++b) {
+                const int tile_col = wn * (BN / 2) + b * 32;      // column of this MFMA tile in the BN-wide tile
+                if (tile_col / kStageCols != half) continue;      // compile-time per (wn is uniform per wavefront)
+                const int col = tile_col - half * kStageCols + (lane & 31);
+                const int64_t n = n0 + half * kStageCols + col;
+                const float bv = (bias && n < N) ? bias[n] : 0.0f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = wm * (BM / 2) + a * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                    *reinterpret_cast<uint16_t *>(lds + row * kOutRowBytes + col * 2) = (uint16_t)f32_to_bf16(acc[a][b][i] + bv);
+                }
             }
-        }
-    __syncthreads();
-    if (vector_out) {
-        // every output width is a multiple of 8 columns: 16-byte chunks never straddle two tensors
-        constexpr int kChunks = BM * (kBN / 8);
+        __syncthreads();
+        const int64_t nh = n0 + half * kStageCols;
+        if (vector_out) {
+            // every output width is a multiple of 8 columns: 16-byte chunks never straddle two tensors
+            constexpr int kChunks = BM * (kStageCols / 8);
 #pragma unroll
-        for (int c = tid; c < kChunks; c += kThreads) {
-            const int row = c / (kBN / 8), cc = c % (kBN / 8);
-            const int64_t m = m0 + row, n = n0 + cc * 8;
-            if (m >= M || n >= N) continue;
-            uint4 v = *reinterpret_cast<const uint4 *>(lds + row * kOutRowBytes + cc * 16);
-            int64_t col;
-            const int s = locate(out, n, &col);
-            const int64_t off = m * out.width[s] + col;
-            if (residual) {
-                const uint4 r = *reinterpret_cast<const uint4 *>(residual + off);   // single output: same offset
-                v.x = f32x2_to_bf16x2(bf16_lo(v.x) + bf16_lo(r.x), bf16_hi(v.x) + bf16_hi(r.x));
-                v.y = f32x2_to_bf16x2(bf16_lo(v.y) + bf16_lo(r.y), bf16_hi(v.y) + bf16_hi(r.y));
-                v.z = f32x2_to_bf16x2(bf16_lo(v.z) + bf16_lo(r.z), bf16_hi(v.z) + bf16_hi(r.z));
-                v.w = f32x2_to_bf16x2(bf16_lo(v.w) + bf16_lo(r.w), bf16_hi(v.w) + bf16_hi(r.w));
+            for (int c = tid; c < kChunks; c += kThreads) {
+                const int row = c / (kStageCols / 8), cc = c % (kStageCols / 8);
+                const int64_t m = m0 + row, n = nh + cc * 8;
+                if (m >= M || n >= N) continue;
+                uint4 v = *reinterpret_cast<const uint4 *>(lds + row * kOutRowBytes + cc * 16);
+                int64_t col;
+                const int s = locate(out, n, &col);
+                const int64_t off = m * out.width[s] + col;
+                if (residual) {
+                    const uint4 r = *reinterpret_cast<const uint4 *>(residual + off);   // single output: same offset
+                    v.x = f32x2_to_bf16x2(bf16_lo(v.x) + bf16_lo(r.x), bf16_hi(v.x) + bf16_hi(r.x));
+                    v.y = f32x2_to_bf16x2(bf16_lo(v.y) + bf16_lo(r.y), bf16_hi(v.y) + bf16_hi(r.y));
+                    v.z = f32x2_to_bf16x2(bf16_lo(v.z) + bf16_lo(r.z), bf16_hi(v.z) + bf16_hi(r.z));
+                    v.w = f32x2_to_bf16x2(bf16_lo(v.w) + bf16_lo(r.w), bf16_hi(v.w) + bf16_hi(r.w));
+                }
+                *reinterpret_cast<uint4 *>(out.ptr[s] + off) = v;
             }
-            *reinterpret_cast<uint4 *>(out.ptr[s] + off) = v;
-        }
-    } else {
-        for (int e = tid; e < BM * kBN; e += kThreads) {
-            const int row = e / kBN, cl = e % kBN;
-            const int64_t m = m0 + row, n = n0 + cl;
-            if (m >= M || n >= N) continue;
-            float v = bf16_to_f32(*reinterpret_cast<const uint16_t *>(lds + row * kOutRowBytes + cl * 2));
-            int64_t col;
-            const int s = locate(out, n, &col);
-            const int64_t off = m * out.width[s] + col;
-            if (residual) v += bf16_to_f32(residual[off]);
-            out.ptr[s][off] = (bf16_t)f32_to_bf16(v);
+        } else {
+            for (int e = tid; e < BM * kStageCols; e += kThreads) {
+                const int row = e / kStageCols, cl = e % kStageCols;
+                const int64_t m = m0 + row, n = nh + cl;
+                if (m >= M || n >= N) continue;
+                float v = bf16_to_f32(*reinterpret_cast<const uint16_t *>(lds + row * kOutRowBytes + cl * 2));
+                int64_t col;
+                const int s = locate(out, n, &col);
+                const int64_t off = m * out.width[s] + col;
+                if (residual) v += bf16_to_f32(residual[off]);
+                out.ptr[s][off] = (bf16_t)f32_to_bf16(v);
+            }
         }
     }
 }
@@ -191,16 +202,15 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     }
     const int64_t N = a.width[0] + a.width[1] + a.width[2];
     const int vec = (a.width[0] % 8 == 0 && a.width[1] % 8 == 0 && a.width[2] % 8 == 0) ? 1 : 0;
-    const int64_t ncols = (N + kBN - 1) / kBN;
     const bf16_t *x = static_cast<const bf16_t *>(a.x), *w = static_cast<const bf16_t *>(a.w);
     const bf16_t *res = static_cast<const bf16_t *>(a.residual);
-    // 128-row tiles when they still give every CU a few workgroups, else 64-row tiles
-    if (ncols * ((a.M + 127) / 128) >= 1024) {
-        dim3 grid((unsigned)ncols, (unsigned)((a.M + 127) / 128));
-        linear_kernel<128><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
+    auto tiles = [&](int64_t bm, int64_t bn) { return ((N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
+    if (tiles(128, 128) >= 1024) {
+        dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 127) / 128));
+        linear_kernel<128, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
     } else {
-        dim3 grid((unsigned)ncols, (unsigned)((a.M + 63) / 64));
-        linear_kernel<64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
+        dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 63) / 64));
+        linear_kernel<64, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
     }
     return hipGetLastError();
 }
