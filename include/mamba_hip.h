@@ -212,6 +212,22 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
                      int64_t n_out, int64_t n_in, void *hip_stream);
 
 /*
+ * Token-side ends of the drafter (a language model: embedding in front of the blocks, LM head =
+ * mamba_linear_fwd with the (V, d_model) vocabulary matrix behind them).
+ * mamba_embedding_fwd: out[m,:] = table[tokens[m],:]; tokens: device int32[M]; table: (V,dm) bf16,
+ *   dm a multiple of 8; M up to 2^31 - 1.  A token outside [0,V) gives a row of NaN (0xFF bytes).
+ * mamba_topk_fwd: for every row of logits (M,V) bf16 the k largest entries, largest first, ties to
+ *   the lower index; idx: device int32 (M,k), val: device float (M,k); 1 <= k <= 8; NaN logits
+ *   never win; with fewer than k finite-or-infinite entries the tail is idx -1.  These are the
+ *   children every node of a draft tree proposes (Sec. 4.1) when the N_i candidates are taken
+ *   greedily instead of sampled.
+ */
+int mamba_embedding_fwd(const int32_t *tokens, const void *table, void *out, int64_t M, int64_t V,
+                        int64_t dm, mamba_dtype_t io, void *hip_stream);
+int mamba_topk_fwd(const void *logits, int32_t *idx, float *val, int64_t M, int64_t V, int k,
+                   mamba_dtype_t io, void *hip_stream);
+
+/*
  * Batch-wise state caches of a draft tree (Sec. 4.1, "efficient cache utilization for batch
  * generation": for a tree configuration T = (N_1..N_gamma) the batch size at draft position i is
  * B_i = N_1 * ... * N_i; one state cache per possible batch size is allocated in advance so that

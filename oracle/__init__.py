@@ -237,3 +237,23 @@ def block_fwd(w, hidden, conv_state_in=None, h0=None, eps=1e-5, round_between=Tr
     y = rb(y)
     out = linear(y.reshape(B * L, D), w["out_proj_w"], None, hidden.reshape(B * L, dm)).reshape(B, L, dm)
     return out, conv_state, h_final
+
+
+def embedding(tokens, table):
+    """Rows of the vocabulary table for each token (a gather)."""
+    return np.asarray(table)[np.asarray(tokens, dtype=np.int64)]
+
+
+def topk(logits, k):
+    """Per row the k largest logits, largest first, equal values ordered by index (numpy.lexsort);
+    NaN never wins.  Returns (idx int32 (M,k), val float64 (M,k)); missing entries are idx -1, val -inf."""
+    x = np.array(logits, dtype=np.float64)
+    x[np.isnan(x)] = -np.inf
+    M, V = x.shape
+    idx = np.full((M, k), -1, dtype=np.int32)
+    val = np.full((M, k), -np.inf)
+    for m in range(M):
+        order = np.lexsort((np.arange(V), -x[m]))[:k]          # primary: value descending, then index
+        idx[m, :order.size] = order
+        val[m, :order.size] = x[m, order]
+    return idx, val

@@ -61,6 +61,10 @@ def _declare(lib):
     lib.mamba_block_fwd.restype = _int
     lib.mamba_block_step.argtypes = [_bpp] + [_vp] * 8 + [_sz, _i64, _i64, _vp]
     lib.mamba_block_step.restype = _int
+    lib.mamba_embedding_fwd.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]
+    lib.mamba_embedding_fwd.restype = _int
+    lib.mamba_topk_fwd.argtypes = [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]
+    lib.mamba_topk_fwd.restype = _int
     lib.mamba_tree_plan.argtypes = [ctypes.POINTER(ctypes.c_int32), _int, _i64, _i64, _i64, _int, _int,
                                     ctypes.POINTER(TreePlan)]
     lib.mamba_tree_plan.restype = _int
@@ -90,7 +94,7 @@ lib = _declare(ctypes.CDLL(LIB_PATH))
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
            "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork", "mamba_tree_plan",
            "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "mamba_block_workspace_bytes",
-           "mamba_block_fwd", "mamba_block_step")
+           "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd")
 
 
 class MambaError(RuntimeError):
@@ -368,3 +372,28 @@ def mamba_block_step(block: Block, hidden, conv_src, ssm_src, parent_idx=None, c
         workspace.numel() * workspace.element_size(), n_out, n_in, _stream(stream))
     _check("mamba_block_step", st)
     return hidden_out, conv_dst, ssm_dst
+
+
+def mamba_embedding_fwd(tokens, table, out=None, stream=None):
+    """tokens int32[M], table (V,dm) bf16 -> (M,dm) rows."""
+    M = tokens.shape[0]
+    V, dm = table.shape
+    if out is None:
+        out = torch.empty((M, dm), dtype=table.dtype, device=table.device)
+    st = lib.mamba_embedding_fwd(_ptr(tokens, torch.int32, (M,), "tokens"), _ptr(table, name="table"),
+                                 _ptr(out, table.dtype, (M, dm), "out"), M, V, dm, _io_code(table), _stream(stream))
+    _check("mamba_embedding_fwd", st)
+    return out
+
+
+def mamba_topk_fwd(logits, k, idx=None, val=None, stream=None):
+    """logits (M,V) bf16 -> idx int32 (M,k), val float32 (M,k), largest first, ties to the lower index."""
+    M, V = logits.shape
+    if idx is None:
+        idx = torch.empty((M, k), dtype=torch.int32, device=logits.device)
+    if val is None:
+        val = torch.empty((M, k), dtype=torch.float32, device=logits.device)
+    st = lib.mamba_topk_fwd(_ptr(logits, name="logits"), _ptr(idx, torch.int32, (M, k), "idx"),
+                            _ptr(val, torch.float32, (M, k), "val"), M, V, int(k), _io_code(logits), _stream(stream))
+    _check("mamba_topk_fwd", st)
+    return idx, val

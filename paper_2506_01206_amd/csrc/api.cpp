@@ -377,6 +377,37 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
     return mamba_linear_fwd(bb.d, p->out_proj_w, nullptr, hidden, hidden_out, p->d_model, nullptr, 0, nullptr, 0, n_out, Di, io, hip_stream);
 }
 
+int mamba_embedding_fwd(const int32_t *tokens, const void *table, void *out, int64_t M, int64_t V, int64_t dm,
+                        mamba_dtype_t io, void *hip_stream)
+{
+    if (io != MAMBA_BF16) return MAMBA_ERR_UNSUPPORTED;
+    int64_t tb, ob;
+    if (!size3(V, dm, 1, 2, &tb) || !size3(M, dm, 1, 2, &ob)) return MAMBA_ERR_BAD_SHAPE;
+    if (dm % 8 != 0 || M > 0x7fffffff) return MAMBA_ERR_UNSUPPORTED;
+    if (M == 0 || dm == 0) return MAMBA_OK;
+    if (V == 0) return MAMBA_ERR_BAD_SHAPE;
+    if (!tokens || !table || !out) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(tokens) || !aligned16(table) || !aligned16(out)) return MAMBA_ERR_MISALIGNED;
+    if (overlap(out, ob, table, tb) || overlap(out, ob, tokens, M * 4)) return MAMBA_ERR_ALIAS;
+    return (int)launch_embedding(tokens, table, out, M, V, dm, static_cast<hipStream_t>(hip_stream));
+}
+
+int mamba_topk_fwd(const void *logits, int32_t *idx, float *val, int64_t M, int64_t V, int k, mamba_dtype_t io,
+                   void *hip_stream)
+{
+    if (io != MAMBA_BF16) return MAMBA_ERR_UNSUPPORTED;
+    int64_t lb;
+    if (!size3(M, V, 1, 2, &lb)) return MAMBA_ERR_BAD_SHAPE;
+    if (k < 1 || k > 8 || M > 0x7fffffff || V > 0x7ffffffe) return MAMBA_ERR_UNSUPPORTED;
+    if (M == 0) return MAMBA_OK;
+    if (V == 0) return MAMBA_ERR_BAD_SHAPE;
+    if (!logits || !idx || !val) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(logits) || !aligned16(idx) || !aligned16(val)) return MAMBA_ERR_MISALIGNED;
+    if (overlap(idx, M * k * 4, logits, lb) || overlap(val, M * k * 4, logits, lb) || overlap(idx, M * k * 4, val, M * k * 4))
+        return MAMBA_ERR_ALIAS;
+    return (int)launch_topk(logits, idx, val, M, V, k, static_cast<hipStream_t>(hip_stream));
+}
+
 int mamba_tree_plan(const int32_t *tree, int gamma, int64_t n_layers, int64_t D, int64_t N, int K,
                     mamba_dtype_t conv_dtype, mamba_tree_plan_t *plan)
 {

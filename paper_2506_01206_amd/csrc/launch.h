@@ -82,4 +82,8 @@ struct NormArgs {
 };
 hipError_t launch_rmsnorm(const NormArgs &a, hipStream_t stream);
 
+hipError_t launch_embedding(const int32_t *tokens, const void *table, void *out, int64_t M, int64_t V, int64_t dm,
+                            hipStream_t stream);
+hipError_t launch_topk(const void *logits, int32_t *idx, float *val, int64_t M, int64_t V, int k, hipStream_t stream);
+
 }  // namespace mamba

@@ -793,3 +793,87 @@ def test_block_decode_steps_against_oracle(m, tree):
         assert_close(to_host(g_ssm), r_ssm, tol, "block step ssm")
         assert_close(values(to_host(g_conv)), r_conv, tol, "block step conv")
         r_conv = W(synth.to_io(r_conv.astype(np.float32), synth.BF16))
+
+
+# ------------------------------------------------------------------------------------ vocabulary ends
+@pytest.mark.parametrize("M,V,k", [(1, 5, 3), (7, 1000, 8), (32, 50280, 3), (3, 257, 1), (2, 4, 8)])
+def test_topk_is_exact(m, M, V, k):
+    rng = np.random.default_rng(M + V + k)
+    x = synth.to_io(rng.standard_normal((M, V)).astype(np.float32), synth.BF16)      # bf16: many exact ties
+    vals = values(x)
+    idx, val = m.mamba_topk_fwd(to_dev(x), k)
+    ri, rv = oracle.topk(vals, k)
+    assert np.array_equal(to_host(idx), ri)                                           # integer work: bit-exact
+    assert np.array_equal(to_host(val).astype(np.float64), rv)
+    if V > 10:
+        xn = vals.astype(np.float32).copy()
+        xn[0, 1] = np.nan
+        xn[0, 2] = np.inf
+        i2, _ = m.mamba_topk_fwd(torch.from_numpy(xn).to(DEV).to(torch.bfloat16), k)
+        assert to_host(i2)[0, 0] == 2 and 1 not in to_host(i2)[0]
+
+
+def test_embedding_is_a_gather(m):
+    rng = np.random.default_rng(3)
+    V, dm = 1000, 768
+    table = synth.to_io(rng.standard_normal((V, dm)).astype(np.float32), synth.BF16)
+    tok = rng.integers(0, V, 77).astype(np.int32)
+    out = m.mamba_embedding_fwd(to_dev(tok), to_dev(table))
+    assert to_host(out).tobytes() == oracle.embedding(tok, table).tobytes()
+    bad = m.mamba_embedding_fwd(to_dev(np.array([5, V, -1], dtype=np.int32)), to_dev(table))
+    assert torch.equal(bad[0], to_dev(table)[5]) and torch.isnan(bad[1:].float()).all()
+
+
+# ------------------------------------------------------------------------------------ whole drafter
+def make_drafter(m, seed, V, dm, D, N, K, R, nl, L):
+    rng = np.random.default_rng(seed)
+    blocks = [synth.block_weights(rng, dm, D, N, K, R) for _ in range(nl)]
+    emb = synth.f32_to_bf16_bits(rng.standard_normal((V, dm)).astype(np.float32))
+    head = synth.f32_to_bf16_bits(rng.standard_normal((V, dm)).astype(np.float32))
+    norm_f = (1 + 0.1 * rng.standard_normal(dm)).astype(np.float32)
+    toks = rng.integers(0, V, L).astype(np.int32)
+    w64 = dict(embedding=W(emb), lm_head=W(head), norm_f=W(norm_f), blocks=[{k: W(v) for k, v in b.items()} for b in blocks])
+    from paper_2506_01206_amd.drafter import MambaDrafter
+    gpu = MambaDrafter(to_dev(emb), [m.Block({k: to_dev(v) for k, v in b.items()}, eps=1e-5) for b in blocks],
+                       to_dev(norm_f), lm_head=to_dev(head))
+    return w64, gpu, toks
+
+
+def test_drafter_tree_tokens_match_the_oracle(m):
+    """Prefix encoding, then a (2, 2, 1, 1) tree drafted end to end on the device (top-N_i candidates ->
+    embedding -> blocks with the state fork -> final norm -> LM head), eagerly and as one captured
+    graph replayed twice.  Token choices are integer results decided by bf16 logits, so the comparison
+    is exact only where the oracle's candidates are clearly separated: the seed is one where every gap
+    between ranked candidates exceeds 0.15 of the logits' rms, checked first, eight times the tolerance."""
+    from oracle import drafter as od
+    tree = (2, 2, 1, 1)
+    w64, gpu, toks = make_drafter(m, 106, V=48, dm=64, D=128, N=16, K=4, R=8, nl=2, L=40)
+    lg, cs, hs = od.prefill(w64, toks)
+    r_tok, r_logits, gap = od.draft(w64, tree, lg, cs, hs)
+    rms = np.sqrt(np.mean(r_logits[-1] ** 2))
+    assert gap > 0.15 * rms, "the seed no longer separates the candidates; pick another"
+    tol = TOL[synth.BF16]
+    g_lg = gpu.prefill(to_dev(toks))
+    assert_close(values(to_host(g_lg)), lg, tol, "prefix logits")
+    # the tolerance is for one stage on identical inputs; block l + 1 already sees inputs that differ by
+    # bf16 rounding flips of block l, so the bound on its state grows with the depth
+    for l in range(len(hs)):
+        assert_close(to_host(gpu.root_ssm[l]), hs[l], (l + 1) * tol, "prefix ssm state of block %d" % l)
+    for mode, use_graph in (("eager", False), ("graph capture", True), ("graph replay", True)):
+        say(mode=mode)
+        g_tok, g_last = gpu.draft(tree, use_graph=use_graph)
+        torch.cuda.synchronize()
+        for i, (gt, rt) in enumerate(zip(g_tok, r_tok)):
+            assert np.array_equal(to_host(gt), rt), "%s: draft tokens at position %d" % (mode, i + 1)
+        assert_close(values(to_host(g_last)), r_logits[-1], tol, mode + ": logits after the last position")
+    # a second prefix through the same captured graph: the root is an input, not baked in
+    toks2 = np.roll(toks, 14)
+    lg2, cs2, hs2 = od.prefill(w64, toks2)
+    r_tok2, r_logits2, gap2 = od.draft(w64, tree, lg2, cs2, hs2)
+    assert gap2 > 0.12 * rms
+    gpu.prefill(to_dev(toks2))
+    g_tok2, g_last2 = gpu.draft(tree)
+    torch.cuda.synchronize()
+    for gt, rt in zip(g_tok2, r_tok2):
+        assert np.array_equal(to_host(gt), rt)
+    assert_close(values(to_host(g_last2)), r_logits2[-1], tol, "second prefix, last logits")

@@ -441,3 +441,56 @@ def test_rmsnorm_closed_forms():
     e[0, 5] = -2.0
     y = oracle.rmsnorm(e, w, 0.0)
     assert y[0, 5] == pytest.approx(-np.sqrt(C) * w[5], rel=1e-14) and np.count_nonzero(y) == 1
+
+
+def test_topk_and_embedding_reduce_to_library_routines():
+    r = rnd(107)
+    x = r.standard_normal((6, 50))
+    x[2, 7] = x[2, 31] = x[2].max() + 1.0                  # a tie at the top: the lower index first
+    x[3, 5] = np.nan
+    idx, val = oracle.topk(x, 4)
+    for m in range(6):
+        row = np.where(np.isnan(x[m]), -np.inf, x[m])
+        assert np.array_equal(val[m], np.sort(row)[::-1][:4])
+        assert np.array_equal(row[idx[m]], val[m]) and len(set(idx[m])) == 4
+    assert list(idx[2, :2]) == [7, 31] and 5 not in idx[3]
+    i2, v2 = oracle.topk(np.array([[1.0, 3.0]]), 3)
+    assert list(i2[0]) == [1, 0, -1] and v2[0, 2] == -np.inf
+    table = r.standard_normal((9, 4))
+    tok = np.array([3, 3, 0, 8])
+    assert np.array_equal(oracle.embedding(tok, table), np.stack([table[3], table[3], table[0], table[8]]))
+
+
+def test_drafter_tree_reduces_to_greedy_decoding_and_to_prefill():
+    """The drafter oracle against what it must reduce to: (a) along a (1, 1, 1) tree it is greedy
+    decoding, so encoding prefix + drafted tokens in one pass gives the same next-token logits
+    (the recurrent step and the sequence form agree, Sec. 3.1); (b) the first child of every node of
+    a wider tree is the greedy path; (c) children of one parent start from the same states, so two
+    siblings that are fed the same token would agree: checked through the parents' j // N_i order by
+    comparing the branch that follows the second-best first token with a fresh run on that token."""
+    from oracle import drafter as od
+    from paper_2506_01206_amd import synth
+    rng = np.random.default_rng(5)
+    V, dm, D, N, K, R, nl = 40, 32, 64, 8, 4, 4, 2
+    wid = lambda a: oracle.widen(a, bf16=(a.dtype == np.uint16))
+    w = dict(embedding=wid(synth.f32_to_bf16_bits(rng.standard_normal((V, dm)).astype(np.float32))),
+             lm_head=wid(synth.f32_to_bf16_bits(rng.standard_normal((V, dm)).astype(np.float32))),
+             norm_f=np.ones(dm), blocks=[{k: wid(v) for k, v in synth.block_weights(rng, dm, D, N, K, R).items()}
+                                         for _ in range(nl)])
+    prefix = rng.integers(0, V, 12).astype(np.int32)
+    lg, cs, hs = od.prefill(w, prefix)
+    tok, logits, _ = od.draft(w, (1, 1, 1), lg, cs, hs)
+    assert tok[0][0] == np.argmax(lg[0])
+    greedy = np.concatenate([prefix] + tok)
+    for i in range(3):
+        again, _, _ = od.prefill(w, greedy[:len(prefix) + i + 1])
+        rms = np.sqrt(np.mean(again ** 2))
+        assert np.max(np.abs(again - logits[i])) <= 2e-2 * rms          # a bf16 rounding flip at most
+    wide, wl, _ = od.draft(w, (2, 2, 1), lg, cs, hs)
+    assert [int(t[0]) for t in wide] == [int(t[0]) for t in tok]          # branch 0 is the greedy path
+    assert [t.size for t in wide] == [2, 4, 4]
+    # branch 1 at depth 1 carries the second-best first token; rows 2, 3 at depth 2 are its children
+    second = int(wide[0][1])
+    lg2, _, _ = od.prefill(w, np.concatenate([prefix, [second]]).astype(np.int32))
+    order = np.argsort(-lg2[0], kind="stable")[:2]
+    assert list(wide[1][2:4]) == list(order)
