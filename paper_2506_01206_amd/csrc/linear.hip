@@ -191,6 +191,97 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// Few rows (M <= 64: the branches of one draft position, Sec. 4.1).  The product is then bound by
+// reading w once and by latency, so the work is cut finely: one workgroup per 32 output columns,
+// its NW wavefronts take the 64-wide k blocks of the row round robin and their partial 32 x 32 tiles
+// are added through LDS.  Operands go from global memory straight into MFMA fragments.  Inside a
+// k block the half-wavefront h owns the contiguous 64 bytes k = 32 h .. 32 h + 31 of its row and
+// feeds them to four k16 steps, 16 bytes each: both operands use the same assignment, so the sum
+// over k is complete, and every lane pair reads one whole 128-byte line of w.
+// grid: ceil(N / 32)
+template <int NW, int MB>
+__global__ void __launch_bounds__(NW * 64)
+linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const float *__restrict__ bias,
+                     const bf16_t *residual, OutSplit out, int64_t M, int64_t N, int64_t K)
+{
+    __shared__ float part[NW][16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int64_t n0 = (int64_t)blockIdx.x * 32;
+    const int64_t kchunks = K / 8, kblocks = (K + 63) / 64;
+    int64_t wr = n0 + r;
+    wr = wr < N ? wr : N - 1;
+    const uint4 *wrow = reinterpret_cast<const uint4 *>(w + wr * K);
+    const uint4 *xrow[MB];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) {
+        int64_t m = b * 32 + r;
+        m = m < M ? m : M - 1;
+        xrow[b] = reinterpret_cast<const uint4 *>(x + m * K);
+    }
+    f32x16 acc[MB];
+#pragma unroll
+    for (int b = 0; b < MB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+
+    uint4 wf[4], xf[MB][4];
+    auto fetch = [&](int64_t blk) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int64_t c = blk * 8 + h * 4 + s;
+            const bool ok = c < kchunks;
+            wf[s] = ok ? wrow[c] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < MB; ++b) xf[b][s] = ok ? xrow[b][c] : make_uint4(0, 0, 0, 0);
+        }
+    };
+    int64_t blk = wave;
+    if (blk < kblocks) fetch(blk);
+    while (blk < kblocks) {
+        bf16x8 wv[4], xv[MB][4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            wv[s] = __builtin_bit_cast(bf16x8, wf[s]);
+#pragma unroll
+            for (int b = 0; b < MB; ++b) xv[b][s] = __builtin_bit_cast(bf16x8, xf[b][s]);
+        }
+        blk += NW;
+        if (blk < kblocks) fetch(blk);                            // in flight during the MFMAs
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[b][s], wv[s], acc[b], 0, 0, 0);
+    }
+
+    // acc[b][i] is C[m = 32 b + 8 (i / 4) + 4 (lane / 32) + i % 4][n = n0 + lane % 32]
+#pragma unroll
+    for (int b = 0; b < MB; ++b) {
+        if (b > 0) __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; ++i) part[wave][i][lane] = acc[b][i];
+        __syncthreads();
+        for (int o = tid; o < 16 * 64; o += NW * 64) {
+            const int i = o >> 6, l = o & 63;
+            float v = 0.0f;
+#pragma unroll
+            for (int q = 0; q < NW; ++q) v += part[q][i][l];
+            const int64_t m = b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
+            if (m >= M || n >= N) continue;
+            if (bias) v += bias[n];
+            v = bf16_to_f32(f32_to_bf16(v));                      // same two roundings as the tiled kernel
+            int64_t col;
+            const int sp = locate(out, n, &col);
+            const int64_t off = m * out.width[sp] + col;
+            if (residual) v += bf16_to_f32(residual[off]);
+            out.ptr[sp][off] = (bf16_t)f32_to_bf16(v);
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
@@ -204,6 +295,18 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     const int vec = (a.width[0] % 8 == 0 && a.width[1] % 8 == 0 && a.width[2] % 8 == 0) ? 1 : 0;
     const bf16_t *x = static_cast<const bf16_t *>(a.x), *w = static_cast<const bf16_t *>(a.w);
     const bf16_t *res = static_cast<const bf16_t *>(a.residual);
+    if (a.M <= 64) {
+        const unsigned grid = (unsigned)((N + 31) / 32);
+        const bool deep = a.K > 512;                              // more wavefronts share a long k loop
+        if (a.M <= 32) {
+            if (deep) linear_skinny_kernel<8, 1><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K);
+            else      linear_skinny_kernel<4, 1><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K);
+        } else {
+            if (deep) linear_skinny_kernel<8, 2><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K);
+            else      linear_skinny_kernel<4, 2><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K);
+        }
+        return hipGetLastError();
+    }
     auto tiles = [&](int64_t bm, int64_t bn) { return ((N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
     if (tiles(128, 128) >= 1024) {
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 127) / 128));

@@ -700,7 +700,11 @@ def test_scan_invariants_at_size(m):
 # ------------------------------------------------------------------------------------ dense parts
 @pytest.mark.parametrize("M,N,K,splits", [(1, 1, 8, None), (5, 80, 48, (48, 16, 16)), (130, 200, 72, None),
                                           (257, 3072, 768, (1536, 1536)), (1000, 80, 1536, (48, 16, 16)),
-                                          (384, 768, 1536, None), (64, 1536, 48, None), (129, 129, 1032, (1, 128))])
+                                          (384, 768, 1536, None), (64, 1536, 48, None), (129, 129, 1032, (1, 128)),
+                                          # few rows (draft positions): the split-k kernel, one or two row blocks
+                                          (18, 3072, 768, (1536, 1536)), (12, 80, 1536, (48, 16, 16)), (32, 768, 1536, None),
+                                          (33, 100, 520, (3, 90, 7)), (64, 50, 1544, None), (3, 1000, 72, None),
+                                          (65, 96, 512, None)])
 def test_linear_against_oracle(m, M, N, K, splits):
     say(M=M, N=N, K=K, splits=splits)
     rng = np.random.default_rng(M + N + K)
