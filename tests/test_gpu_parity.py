@@ -800,7 +800,8 @@ def test_block_decode_steps_against_oracle(m, tree):
 
 
 # ------------------------------------------------------------------------------------ vocabulary ends
-@pytest.mark.parametrize("M,V,k", [(1, 5, 3), (7, 1000, 8), (32, 50280, 3), (3, 257, 1), (2, 4, 8)])
+@pytest.mark.parametrize("M,V,k", [(1, 5, 3), (7, 1000, 8), (32, 50280, 3), (3, 257, 1), (2, 4, 8), (9, 10003, 8),
+                                   (4, 20, 5)])
 def test_topk_is_exact(m, M, V, k):
     rng = np.random.default_rng(M + V + k)
     x = synth.to_io(rng.standard_normal((M, V)).astype(np.float32), synth.BF16)      # bf16: many exact ties
