@@ -217,8 +217,9 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
  * mamba_embedding_fwd: out[m,:] = table[tokens[m],:]; tokens: device int32[M]; table: (V,dm) bf16,
  *   dm a multiple of 8; M up to 2^31 - 1.  A token outside [0,V) gives a row of NaN (0xFF bytes).
  * mamba_topk_fwd: for every row of logits (M,V) bf16 the k largest entries, largest first, ties to
- *   the lower index; idx: device int32 (M,k), val: device float (M,k); 1 <= k <= 8; NaN logits
- *   never win; with fewer than k finite-or-infinite entries the tail is idx -1.  These are the
+ *   the lower index; idx: device int32 (M,k), val: device float (M,k); 1 <= k <= 8; V <= 2^25.
+ *   A NaN logit ranks as -inf (so it never wins against a number); when V < k the tail is
+ *   idx -1, val -inf.  These are the
  *   children every node of a draft tree proposes (Sec. 4.1) when the N_i candidates are taken
  *   greedily instead of sampled.
  */

@@ -362,6 +362,48 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
     const int64_t Di = p->d_inner, N = p->d_state, R = p->dt_rank;
     const mamba_dtype_t io = MAMBA_BF16;
     int rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (n_out <= 64) {
+        // A draft position has a few rows and lives on launch latency, so the chain is shortened to five
+        // launches: RMSNorm rides in in_proj, the copy of the parent's conv window in the conv step, and
+        // the dt projection in the state step.  (Buffers: x -> a, z -> b, x_c -> c, y -> d.)
+        int64_t conv_in_bytes, conv_out_bytes, ssm_in_bytes, ssm_out_bytes;
+        if (!size3(n_in, Di, p->d_conv - 1, 2, &conv_in_bytes) || !size3(n_out, Di, p->d_conv - 1, 2, &conv_out_bytes) ||
+            !size3(n_in, Di, N, 4, &ssm_in_bytes) || !size3(n_out, Di, N, 4, &ssm_out_bytes))
+            return MAMBA_ERR_BAD_SHAPE;
+        if (!aligned16(conv_src) || !aligned16(conv_dst) || !aligned16(ssm_src) || !aligned16(ssm_dst) || !aligned16(parent_idx))
+            return MAMBA_ERR_MISALIGNED;
+        if (parent_idx && (overlap(conv_dst, conv_out_bytes, conv_src, conv_in_bytes) ||
+                           overlap(ssm_dst, ssm_out_bytes, ssm_src, ssm_in_bytes)))
+            return MAMBA_ERR_ALIAS;
+        int64_t hid_bytes;
+        if (!size3(n_out, p->d_model, 1, 2, &hid_bytes)) return MAMBA_ERR_BAD_SHAPE;
+        if (hidden != hidden_out && overlap(hidden, hid_bytes, hidden_out, hid_bytes)) return MAMBA_ERR_ALIAS;
+        const void *state_bufs[4] = {conv_src, conv_dst, ssm_src, ssm_dst};
+        const int64_t state_bytes[4] = {conv_in_bytes, conv_out_bytes, ssm_in_bytes, ssm_out_bytes};
+        for (int i = 0; i < 4; ++i)
+            if (overlap(state_bufs[i], state_bytes[i], workspace, (int64_t)bb.total) ||
+                overlap(state_bufs[i], state_bytes[i], hidden, hid_bytes) ||
+                overlap(state_bufs[i], state_bytes[i], hidden_out, hid_bytes))
+                return MAMBA_ERR_ALIAS;
+        if (overlap(hidden, hid_bytes, workspace, (int64_t)bb.total) || overlap(hidden_out, hid_bytes, workspace, (int64_t)bb.total))
+            return MAMBA_ERR_ALIAS;
+        LinearArgs in{hidden, p->in_proj_w, nullptr, nullptr, {bb.a, bb.b, nullptr}, {Di, Di, 0}, n_out, p->d_model};
+        in.norm_w = p->norm_w;
+        in.eps = p->eps;
+        if (hipError_t e = launch_linear(in, stream)) return (int)e;
+        ConvArgs cv{bb.a, p->conv_w, p->conv_b, conv_src, bb.c, conv_dst, n_out, 1, Di, p->d_conv, 1, kIoBf16};
+        cv.parent = parent_idx;
+        cv.n_in = n_in;
+        if (hipError_t e = launch_conv1d(cv, stream)) return (int)e;
+        if ((rc = mamba_linear_fwd(bb.c, p->x_proj_w, nullptr, nullptr, bb.dtl, R, bb.bm, N, bb.cm, N, n_out, Di, io, hip_stream))) return rc;
+        StepArgs sa{ssm_dst, ssm_src, parent_idx, bb.c, bb.dtl, bb.bm, bb.cm, bb.b, p->A, p->Dskip, p->dt_bias, bb.d,
+                    n_out, n_in, Di, (int)N, kIoBf16, 1};
+        sa.dt_w = p->dt_proj_w;
+        sa.dt_rank = R;
+        if (hipError_t e = launch_step(sa, stream)) return (int)e;
+        return mamba_linear_fwd(bb.d, p->out_proj_w, nullptr, hidden, hidden_out, p->d_model, nullptr, 0, nullptr, 0, n_out, Di, io, hip_stream);
+    }
     if ((rc = mamba_rmsnorm_fwd(hidden, p->norm_w, bb.d, n_out, p->d_model, p->eps, io, hip_stream))) return rc;
     if ((rc = mamba_linear_fwd(bb.d, p->in_proj_w, nullptr, nullptr, bb.a, Di, bb.b, Di, nullptr, 0, n_out, p->d_model, io, hip_stream))) return rc;
     // children take their parent's conv window, then the window is shifted in place in the destination cache
@@ -398,7 +440,7 @@ int mamba_topk_fwd(const void *logits, int32_t *idx, float *val, int64_t M, int6
     if (io != MAMBA_BF16) return MAMBA_ERR_UNSUPPORTED;
     int64_t lb;
     if (!size3(M, V, 1, 2, &lb)) return MAMBA_ERR_BAD_SHAPE;
-    if (k < 1 || k > 8 || M > 0x7fffffff || V > 0x7ffffffe) return MAMBA_ERR_UNSUPPORTED;
+    if (k < 1 || k > 8 || M > 0x7fffffff || V > ((int64_t)1 << 25)) return MAMBA_ERR_UNSUPPORTED;
     if (M == 0) return MAMBA_OK;
     if (V == 0) return MAMBA_ERR_BAD_SHAPE;
     if (!logits || !idx || !val) return MAMBA_ERR_NULL_POINTER;

@@ -9,6 +9,8 @@
 // row), walks a tile of consecutive tokens and keeps the K-1 previous rows in registers, so every
 // input element is read once (plus K-1 halo rows per tile) and every wavefront access is a
 // contiguous run.  Loads of the next group of rows are issued before the current group is used.
+// In tree drafting (Sec. 4.1) a branch starts from the window of its parent: the carried rows can be
+// read through a parent index, which replaces a separate copy of the window.
 #include "device_math.h"
 #include "launch.h"
 
@@ -79,7 +81,7 @@ template <typename T, int VEC, int K, bool SILU>
 __global__ void __launch_bounds__(kBlock)
 conv1d_kernel(const T *__restrict__ x, const float *__restrict__ w, const float *__restrict__ bias,
               const T *state_in, T *__restrict__ y, T *state_out, int64_t L, int64_t D,
-              int64_t tile_len)
+              int64_t tile_len, const int32_t *__restrict__ parent, int64_t n_in)
 {
     typedef typename RowVec<T, VEC>::type row_t;
     constexpr int H = K - 1;
@@ -109,14 +111,20 @@ conv1d_kernel(const T *__restrict__ x, const float *__restrict__ w, const float 
     float win[H > 0 ? H : 1][VEC];
     float carried[VEC * (H > 0 ? H : 1)];
     if (t0 < H) {
+        // a draft branch continues from its parent's window (the copy is fused into this load)
+        const int64_t pb = parent ? (int64_t)parent[b] : b;
+        const bool p_ok = !parent || (pb >= 0 && pb < n_in);
         if (!state_in) {
 #pragma unroll
             for (int i = 0; i < VEC * H; ++i) carried[i] = 0.0f;
+        } else if (!p_ok) {
+#pragma unroll
+            for (int i = 0; i < VEC * H; ++i) carried[i] = __int_as_float(0x7fc00000);
         } else if constexpr (VEC > 1) {
-            ld_block<VEC * H>(state_in + (b * D + d0) * H, carried);
+            ld_block<VEC * H>(state_in + (pb * D + d0) * H, carried);
         } else {
 #pragma unroll
-            for (int k = 0; k < H; ++k) carried[k] = ld_io(state_in, (b * D + d0) * H + k);
+            for (int k = 0; k < H; ++k) carried[k] = ld_io(state_in, (pb * D + d0) * H + k);
         }
     }
 #pragma unroll
@@ -213,9 +221,9 @@ template <typename T, int VEC, int K> hipError_t launch_conv_k(const ConvArgs &a
     T *y = static_cast<T *>(a.y);
     T *so = static_cast<T *>(a.state_out);
     if (a.apply_silu)
-        conv1d_kernel<T, VEC, K, true><<<grid, kBlock, 0, stream>>>(x, a.w, a.bias, si, y, so, a.L, a.D, tile_len);
+        conv1d_kernel<T, VEC, K, true><<<grid, kBlock, 0, stream>>>(x, a.w, a.bias, si, y, so, a.L, a.D, tile_len, a.parent, a.n_in);
     else
-        conv1d_kernel<T, VEC, K, false><<<grid, kBlock, 0, stream>>>(x, a.w, a.bias, si, y, so, a.L, a.D, tile_len);
+        conv1d_kernel<T, VEC, K, false><<<grid, kBlock, 0, stream>>>(x, a.w, a.bias, si, y, so, a.L, a.D, tile_len, a.parent, a.n_in);
     return hipGetLastError();
 }
 

@@ -18,6 +18,10 @@ struct ConvArgs {
     void *state_out;
     int64_t batch, L, D;
     int K, apply_silu, io;
+    // tree drafting: sequence b takes the carried rows of state_in[parent[b]] (n_in rows there; an index
+    // outside [0, n_in) gives NaN); nullptr: state_in[b].  Needs state_in != state_out.
+    const int32_t *parent = nullptr;
+    int64_t n_in = 0;
 };
 hipError_t launch_conv1d(const ConvArgs &a, hipStream_t stream);
 
@@ -46,6 +50,10 @@ struct StepArgs {
     void *out;
     int64_t n_out, n_in, D;
     int N, io, dt_softplus;
+    // with dt_w (D, dt_rank) bf16 the kernel also does the dt projection: ``dt`` is then the low-rank
+    // (n_out, dt_rank) tensor and delta_raw[j,d] = sum_r dt[j,r] dt_w[d,r]  (bf16 I/O only, dt_rank % 4 == 0)
+    const void *dt_w = nullptr;
+    int64_t dt_rank = 0;
 };
 hipError_t launch_step(const StepArgs &a, hipStream_t stream);
 
@@ -70,6 +78,10 @@ struct LinearArgs {
     void *out[3];            // up to three output tensors (M, width[i]) bf16
     int64_t width[3];
     int64_t M, K;
+    // with norm_w (K) the rows of x are RMS-normalised on the way in: x[m,k] * norm_w[k] enters the
+    // product and the row factor rsqrt(mean_k x[m,k]^2 + eps) is applied to the sums (M <= 64 only)
+    const float *norm_w = nullptr;
+    float eps = 0.0f;
 };
 hipError_t launch_linear(const LinearArgs &a, hipStream_t stream);
 

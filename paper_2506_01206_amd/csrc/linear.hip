@@ -204,9 +204,12 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
 template <int NW, int MB>
 __global__ void __launch_bounds__(NW * 64)
 linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const float *__restrict__ bias,
-                     const bf16_t *residual, OutSplit out, int64_t M, int64_t N, int64_t K)
+                     const bf16_t *residual, OutSplit out, int64_t M, int64_t N, int64_t K,
+                     const float *__restrict__ norm_w, float eps)
 {
     __shared__ float part[NW][16][64];
+    __shared__ float ssq[NW][MB][64];                             // with norm_w: sum of x^2 per lane's row part
+    __shared__ float row_scale[32];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;
     const int64_t n0 = (int64_t)blockIdx.x * 32;
@@ -227,34 +230,55 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
 
-    uint4 wf[4], xf[MB][4];
-    auto fetch = [&](int64_t blk) {
+    // A wavefront's k blocks are taken G at a time: all loads of a group are issued before its first
+    // MFMA, so that a row of up to 64 * NW * G values costs one trip to memory, not one per block.
+    constexpr int G = MB == 1 ? 3 : 2;
+    float ss[MB];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int64_t c = blk * 8 + h * 4 + s;
-            const bool ok = c < kchunks;
-            wf[s] = ok ? wrow[c] : make_uint4(0, 0, 0, 0);
+    for (int b = 0; b < MB; ++b) ss[b] = 0.0f;
+    for (int64_t blk0 = wave; blk0 < kblocks; blk0 += (int64_t)NW * G) {
+        uint4 wf[G][4], xf[G][MB][4];
 #pragma unroll
-            for (int b = 0; b < MB; ++b) xf[b][s] = ok ? xrow[b][c] : make_uint4(0, 0, 0, 0);
+        for (int g = 0; g < G; ++g) {
+            const int64_t blk = blk0 + (int64_t)g * NW;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int64_t c = blk * 8 + h * 4 + s;
+                const bool ok = c < kchunks;                      // also false for blk >= kblocks
+                wf[g][s] = ok ? wrow[c] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < MB; ++b) xf[g][b][s] = ok ? xrow[b][c] : make_uint4(0, 0, 0, 0);
+            }
         }
-    };
-    int64_t blk = wave;
-    if (blk < kblocks) fetch(blk);
-    while (blk < kblocks) {
-        bf16x8 wv[4], xv[MB][4];
+        if (norm_w) {
+            // RMSNorm on the way in: the element-wise weight now, the row factor after the sums
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            wv[s] = __builtin_bit_cast(bf16x8, wf[s]);
+            for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int b = 0; b < MB; ++b) xv[b][s] = __builtin_bit_cast(bf16x8, xf[b][s]);
+                for (int s = 0; s < 4; ++s) {
+                    const int64_t c = (blk0 + (int64_t)g * NW) * 8 + h * 4 + s;
+                    if (c >= kchunks) continue;
+                    const float4 g0 = reinterpret_cast<const float4 *>(norm_w)[2 * c];
+                    const float4 g1 = reinterpret_cast<const float4 *>(norm_w)[2 * c + 1];
+#pragma unroll
+                    for (int b = 0; b < MB; ++b) {
+                        uint4 &q = xf[g][b][s];
+                        const float v0 = bf16_lo(q.x), v1 = bf16_hi(q.x), v2 = bf16_lo(q.y), v3 = bf16_hi(q.y);
+                        const float v4 = bf16_lo(q.z), v5 = bf16_hi(q.z), v6 = bf16_lo(q.w), v7 = bf16_hi(q.w);
+                        ss[b] += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3 + v4 * v4 + v5 * v5 + v6 * v6 + v7 * v7;
+                        q = make_uint4(f32x2_to_bf16x2(v0 * g0.x, v1 * g0.y), f32x2_to_bf16x2(v2 * g0.z, v3 * g0.w),
+                                       f32x2_to_bf16x2(v4 * g1.x, v5 * g1.y), f32x2_to_bf16x2(v6 * g1.z, v7 * g1.w));
+                    }
+                }
         }
-        blk += NW;
-        if (blk < kblocks) fetch(blk);                            // in flight during the MFMAs
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int b = 0; b < MB; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[b][s], wv[s], acc[b], 0, 0, 0);
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int b = 0; b < MB; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xf[g][b][s]),
+                                                                     __builtin_bit_cast(bf16x8, wf[g][s]), acc[b], 0, 0, 0);
     }
 
     // acc[b][i] is C[m = 32 b + 8 (i / 4) + 4 (lane / 32) + i % 4][n = n0 + lane % 32]
@@ -263,12 +287,23 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
         if (b > 0) __syncthreads();
 #pragma unroll
         for (int i = 0; i < 16; ++i) part[wave][i][lane] = acc[b][i];
+        if (norm_w) ssq[wave][b][lane] = ss[b];
         __syncthreads();
+        if (norm_w) {
+            if (tid < 32) {
+                float t = 0.0f;
+#pragma unroll
+                for (int q = 0; q < NW; ++q) t += ssq[q][b][tid] + ssq[q][b][tid + 32];
+                row_scale[tid] = __builtin_amdgcn_rsqf(t / (float)K + eps);
+            }
+            __syncthreads();
+        }
         for (int o = tid; o < 16 * 64; o += NW * 64) {
             const int i = o >> 6, l = o & 63;
             float v = 0.0f;
 #pragma unroll
             for (int q = 0; q < NW; ++q) v += part[q][i][l];
+            if (norm_w) v *= row_scale[8 * (i >> 2) + 4 * (l >> 5) + (i & 3)];
             const int64_t m = b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
             if (m >= M || n >= N) continue;
             if (bias) v += bias[n];
@@ -295,15 +330,17 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     const int vec = (a.width[0] % 8 == 0 && a.width[1] % 8 == 0 && a.width[2] % 8 == 0) ? 1 : 0;
     const bf16_t *x = static_cast<const bf16_t *>(a.x), *w = static_cast<const bf16_t *>(a.w);
     const bf16_t *res = static_cast<const bf16_t *>(a.residual);
-    if (a.M <= 64) {
+    // few rows: the split-k kernel, except for very wide outputs (the LM head), where the tiled kernel's
+    // shared x tile reads less
+    if (a.M <= 64 && (N < 8192 || a.norm_w)) {
         const unsigned grid = (unsigned)((N + 31) / 32);
         const bool deep = a.K > 512;                              // more wavefronts share a long k loop
         if (a.M <= 32) {
-            if (deep) linear_skinny_kernel<8, 1><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K);
-            else      linear_skinny_kernel<4, 1><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K);
+            if (deep) linear_skinny_kernel<8, 1><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps);
+            else      linear_skinny_kernel<4, 1><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps);
         } else {
-            if (deep) linear_skinny_kernel<8, 2><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K);
-            else      linear_skinny_kernel<4, 2><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K);
+            if (deep) linear_skinny_kernel<8, 2><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps);
+            else      linear_skinny_kernel<4, 2><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps);
         }
         return hipGetLastError();
     }

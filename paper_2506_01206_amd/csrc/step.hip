@@ -54,7 +54,8 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
                   const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
                   const T *__restrict__ Bm, const T *__restrict__ Cm,
                   const float *__restrict__ Dskip, const T *__restrict__ z,
-                  const float *__restrict__ dt_bias, T *__restrict__ out, int64_t n_in, int64_t D)
+                  const float *__restrict__ dt_bias, T *__restrict__ out, int64_t n_in, int64_t D,
+                  const bf16_t *__restrict__ dt_w, int64_t dt_rank)
 {
     constexpr int Q = N / 4;
     const int64_t j = blockIdx.y;
@@ -76,7 +77,23 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
         bv[i] = ld4_io<N>(Bm + j * N + 4 * q);
         cv[i] = ld4_io<N>(Cm + j * N + 4 * q);
         xv[i] = ld_io(x, j * D + d[i]);
-        dv[i] = ld_io(dt, j * D + d[i]);
+        if (sizeof(T) == 2 && dt_w) {
+            // dt projection fused in: the Q lanes of a channel share the dt_rank products (4 at a time)
+            const uint2 *wrow = reinterpret_cast<const uint2 *>(dt_w + d[i] * dt_rank);
+            const uint2 *lrow = reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(dt) + j * dt_rank);
+            float acc = 0.0f;
+#pragma unroll 4
+            for (int64_t c = q; c < dt_rank / 4; c += Q) {
+                const uint2 a2 = wrow[c], b2 = lrow[c];
+                acc = fmaf(bf16_lo(a2.x), bf16_lo(b2.x), acc);
+                acc = fmaf(bf16_hi(a2.x), bf16_hi(b2.x), acc);
+                acc = fmaf(bf16_lo(a2.y), bf16_lo(b2.y), acc);
+                acc = fmaf(bf16_hi(a2.y), bf16_hi(b2.y), acc);
+            }
+            dv[i] = bf16_to_f32(f32_to_bf16(channel_sum<Q>(acc)));     // rounded like the stored tensor it replaces
+        } else {
+            dv[i] = ld_io(dt, j * D + d[i]);
+        }
         zv[i] = HAS_Z ? ld_io(z, j * D + d[i]) : 0.0f;
         bias[i] = dt_bias ? dt_bias[d[i]] : 0.0f;
         dsk[i] = Dskip ? Dskip[d[i]] : 0.0f;
@@ -128,7 +145,8 @@ template <typename T, int N, int U> hipError_t launch_step_u(const StepArgs &a, 
     state_step_kernel<T, N, U, HZ, SP><<<grid, kBlock, 0, stream>>>(                              \
         a.h_out, a.h_in, a.parent, static_cast<const T *>(a.x), static_cast<const T *>(a.dt), a.A, \
         static_cast<const T *>(a.Bm), static_cast<const T *>(a.Cm), a.Dskip,                      \
-        static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D)
+        static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D,                \
+        static_cast<const bf16_t *>(a.dt_w), a.dt_rank)
     if (a.z) {
         if (a.dt_softplus) MAMBA_STEP(true, true);
         else MAMBA_STEP(true, false);
