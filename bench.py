@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--no-wide-step", action="store_true",
                     help="skip the separate timing of the 64-branch, D=4096 state step")
     ap.add_argument("--no-block", action="store_true", help="skip the whole-block prefill timing")
+    ap.add_argument("--no-drafter", action="store_true",
+                    help="skip the whole-drafter timing (Mamba-130M shapes, prefix encoding and draft rounds)")
     ap.add_argument("--no-tree-draft", action="store_true",
                     help="skip the sequential-versus-tree draft round timing")
     ap.add_argument("--eager-decode", action="store_true",
@@ -318,6 +320,52 @@ def main():
                         "projection_GFLOP": round(gemm_flops / 1e9, 2)}
         del hid, hout, bws
 
+    # the whole drafter at Mamba-130M shapes (Sec. 3.1: 24 blocks, d_model 768, vocabulary 50280, tied LM
+    # head): encoding a 2048-token prefix, then whole draft rounds (top-N_i -> embedding -> 24 blocks
+    # -> norm -> LM head per position), each round one captured HIP graph; the paper's comparison of
+    # sequential against tree drafting, here with every stage of the drafter included
+    drafter_detail = {}
+    if not args.no_drafter:
+        from paper_2506_01206_amd.drafter import MambaDrafter
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(130)
+        d_dm, d_D, d_N, d_K, d_R, d_nl, d_V, d_L = 768, 1536, 16, 4, 48, 24, 50280, 2048
+        rn = lambda *shape: torch.randn(*shape, device=dev, generator=gen)
+        blocks_d = []
+        for _ in range(d_nl):
+            dt0 = torch.exp(torch.rand(d_D, device=dev, generator=gen) * (np.log(0.1) - np.log(1e-3)) + np.log(1e-3))
+            blocks_d.append(m.Block(dict(
+                norm_w=1 + 0.1 * rn(d_dm), in_proj_w=(rn(2 * d_D, d_dm) / d_dm ** 0.5).to(torch.bfloat16),
+                conv_w=torch.rand(d_D, d_K, device=dev, generator=gen) - 0.5, conv_b=0.1 * rn(d_D),
+                x_proj_w=(rn(d_R + 2 * d_N, d_D) / d_D ** 0.5).to(torch.bfloat16),
+                dt_proj_w=(rn(d_D, d_R) / d_R ** 0.5).to(torch.bfloat16), dt_bias=dt0 + torch.log(-torch.expm1(-dt0)),
+                A=-(0.5 + 15.5 * torch.rand(d_D, d_N, device=dev, generator=gen)), Dskip=torch.ones(d_D, device=dev),
+                out_proj_w=(rn(d_dm, d_D) / d_D ** 0.5).to(torch.bfloat16))))
+        drafter = MambaDrafter((0.5 * rn(d_V, d_dm)).to(torch.bfloat16), blocks_d, torch.ones(d_dm, device=dev))
+        prefix = torch.randint(0, d_V, (d_L,), device=dev, generator=gen, dtype=torch.int32)
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            q0, q1 = ev(), ev()
+            q0.record()
+            for _ in range(reps):
+                fn()
+            q1.record()
+            torch.cuda.synchronize()
+            return q0.elapsed_time(q1) / reps
+        drafter_detail = {"workload": "Mamba-130M-shaped drafter, %d blocks, d_model %d, vocabulary %d, random weights"
+                                      % (d_nl, d_dm, d_V),
+                          "prefill_%d_tokens_ms" % d_L: round(timed(lambda: drafter.prefill(prefix), 5), 4)}
+        for name, tree in (("sequential_1_1_1_1_1", (1, 1, 1, 1, 1)), ("tree_3_2_2_1_1", (3, 2, 2, 1, 1)),
+                           ("tree_2_2_2_1_1_1", (2, 2, 2, 1, 1, 1))):
+            drafter.draft(tree)                                       # captures the round's graph
+            drafter_detail[name + "_round_ms"] = round(timed(lambda: drafter.draft(tree), 20), 4)
+        drafter_detail["per_position_us_sequential"] = round(drafter_detail["sequential_1_1_1_1_1_round_ms"] / 5 * 1e3, 1)
+        drafter_detail["tree_over_sequential"] = round(drafter_detail["tree_3_2_2_1_1_round_ms"] /
+                                                       drafter_detail["sequential_1_1_1_1_1_round_ms"], 3)
+        del drafter, blocks_d
+
     tokens = B * L
     sb = scan_bytes(B, L, D, N, e)
     achieved = sb / (scan_ms * 1e-3) / 1e9
@@ -346,6 +394,7 @@ def main():
         "decode_launches": nsteps * (1 + 2 * nl), "decode_mode": "eager" if args.eager_decode else "hip_graph",
         "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide,
         "tree_draft_round": tree_detail, "whole_block": block_detail,
+        "whole_drafter": drafter_detail,
     }
 
     result = {

@@ -774,7 +774,7 @@ def test_block_prefill_against_oracle(m, B, L, dm, D, N, K, R):
     assert torch.equal(h2, out)
 
 
-@pytest.mark.parametrize("tree", [(3, 2, 1), (1, 1), (4,)])
+@pytest.mark.parametrize("tree", [(3, 2, 1), (1, 1), (4,), (33, 2, 1), (66, 2)])
 def test_block_decode_steps_against_oracle(m, tree):
     """Tree drafting through whole blocks: at every draft position each branch continues from its
     parent's conv and SSM state (fork fused into the step) and produces the next hidden row."""
@@ -797,6 +797,25 @@ def test_block_decode_steps_against_oracle(m, tree):
         assert_close(to_host(g_ssm), r_ssm, tol, "block step ssm")
         assert_close(values(to_host(g_conv)), r_conv, tol, "block step conv")
         r_conv = W(synth.to_io(r_conv.astype(np.float32), synth.BF16))
+
+
+def test_block_step_bad_parent_poisons_only_that_branch(m):
+    """A parent index outside the source cache cannot be honoured: that branch's states and hidden row
+    come back NaN (never an out-of-bounds read), the other branches are untouched by it."""
+    dm, D, N, K, R = 64, 128, 16, 4, 8
+    rng = np.random.default_rng(77)
+    w, w64, blk = make_block(m, rng, dm, D, N, K, R)
+    conv = to_dev(synth.to_io(rng.standard_normal((2, D, K - 1)).astype(np.float32), synth.BF16))
+    ssm = to_dev(rng.standard_normal((2, D, N)).astype(np.float32))
+    hid = to_dev(synth.to_io(rng.standard_normal((3, dm)).astype(np.float32), synth.BF16))
+    good = m.mamba_block_step(blk, hid, conv, ssm, parent_idx=to_dev(np.array([1, 0, 1], dtype=np.int32)))
+    bad = m.mamba_block_step(blk, hid, conv, ssm, parent_idx=to_dev(np.array([1, 2, -1], dtype=np.int32)))
+    for g, b in zip(good, bad):
+        assert torch.equal(g[0], b[0])
+    out, conv_new, ssm_new = bad
+    assert torch.isnan(out[1:].float()).all() and torch.isnan(ssm_new[1:]).all()
+    # the window keeps the branch's own new column; the columns inherited from the missing parent are NaN
+    assert torch.isnan(conv_new[1:, :, :K - 2].float()).all() and torch.equal(conv_new[1:, :, K - 2], good[1][1:, :, K - 2])
 
 
 # ------------------------------------------------------------------------------------ vocabulary ends
