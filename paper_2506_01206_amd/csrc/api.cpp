@@ -364,9 +364,9 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
     int rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (n_out <= 64) {
-        // A draft position has a few rows and lives on launch latency, so the chain is shortened to five
-        // launches: RMSNorm rides in in_proj, the copy of the parent's conv window in the conv step, and
-        // the dt projection in the state step.  (Buffers: x -> a, z -> b, x_c -> c, y -> d.)
+        // A draft position has a few rows and lives on launch latency, so the chain is shortened to four
+        // launches: RMSNorm rides into in_proj and the conv step (with the copy of the parent's window)
+        // out of it, the dt projection rides in the state step.  (Buffers: z -> b, x_c -> c, y -> d.)
         int64_t conv_in_bytes, conv_out_bytes, ssm_in_bytes, ssm_out_bytes;
         if (!size3(n_in, Di, p->d_conv - 1, 2, &conv_in_bytes) || !size3(n_out, Di, p->d_conv - 1, 2, &conv_out_bytes) ||
             !size3(n_in, Di, N, 4, &ssm_in_bytes) || !size3(n_out, Di, N, 4, &ssm_out_bytes))
@@ -388,14 +388,18 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
                 return MAMBA_ERR_ALIAS;
         if (overlap(hidden, hid_bytes, workspace, (int64_t)bb.total) || overlap(hidden_out, hid_bytes, workspace, (int64_t)bb.total))
             return MAMBA_ERR_ALIAS;
-        LinearArgs in{hidden, p->in_proj_w, nullptr, nullptr, {bb.a, bb.b, nullptr}, {Di, Di, 0}, n_out, p->d_model};
+        // [x_c | z] = [silu(conv step(.)) | .] of rmsnorm(hidden) W_in^T; the conv windows move to conv_dst
+        LinearArgs in{hidden, p->in_proj_w, nullptr, nullptr, {bb.c, bb.b, nullptr}, {Di, Di, 0}, n_out, p->d_model};
         in.norm_w = p->norm_w;
         in.eps = p->eps;
+        in.conv_w = p->conv_w;
+        in.conv_b = p->conv_b;
+        in.conv_src = conv_src;
+        in.conv_dst = conv_dst;
+        in.conv_parent = parent_idx;
+        in.conv_n_in = n_in;
+        in.conv_k = p->d_conv;
         if (hipError_t e = launch_linear(in, stream)) return (int)e;
-        ConvArgs cv{bb.a, p->conv_w, p->conv_b, conv_src, bb.c, conv_dst, n_out, 1, Di, p->d_conv, 1, kIoBf16};
-        cv.parent = parent_idx;
-        cv.n_in = n_in;
-        if (hipError_t e = launch_conv1d(cv, stream)) return (int)e;
         if ((rc = mamba_linear_fwd(bb.c, p->x_proj_w, nullptr, nullptr, bb.dtl, R, bb.bm, N, bb.cm, N, n_out, Di, io, hip_stream))) return rc;
         StepArgs sa{ssm_dst, ssm_src, parent_idx, bb.c, bb.dtl, bb.bm, bb.cm, bb.b, p->A, p->Dskip, p->dt_bias, bb.d,
                     n_out, n_in, Di, (int)N, kIoBf16, 1};

@@ -82,6 +82,16 @@ struct LinearArgs {
     // product and the row factor rsqrt(mean_k x[m,k]^2 + eps) is applied to the sums (M <= 64 only)
     const float *norm_w = nullptr;
     float eps = 0.0f;
+    // with conv_w the columns of the first output tensor (the x half of in_proj, width[0] channels) go
+    // through one step of the causal depthwise conv + SiLU before they are stored (M <= 64 only): row m
+    // takes the window conv_src[parent[m]] (or conv_src[m]), and the shifted window goes to conv_dst[m].
+    // conv_src / conv_dst: (rows, width[0], conv_k - 1) bf16; may be the same buffer when parent is null.
+    const float *conv_w = nullptr, *conv_b = nullptr;
+    const void *conv_src = nullptr;
+    void *conv_dst = nullptr;
+    const int32_t *conv_parent = nullptr;
+    int64_t conv_n_in = 0;
+    int conv_k = 0;
 };
 hipError_t launch_linear(const LinearArgs &a, hipStream_t stream);
 

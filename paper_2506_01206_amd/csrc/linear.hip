@@ -29,12 +29,23 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int kStageCols = 128;                       // the output tile is staged 128 columns at a time
-constexpr int kOutRowBytes = kStageCols * 2 + 16;
+#ifndef MAMBA_LINEAR_MID
+#define MAMBA_LINEAR_MID 512
+#endif
 
 struct OutSplit {
     bf16_t *ptr[3];
     int64_t width[3];
+};
+
+// one step of the depthwise causal conv + SiLU applied to the first output tensor on its way out
+struct ConvTail {
+    const float *w, *bias;      // (channels, k), (channels) or nullptr; w == nullptr: no conv
+    const bf16_t *src;          // (rows_in, channels, k - 1) carried windows
+    bf16_t *dst;                // (M, channels, k - 1)
+    const int32_t *parent;      // row m continues from src[parent[m]]; nullptr: src[m]
+    int64_t n_in;
+    int k;
 };
 
 // column n of the virtual (M, N) output -> tensor and column inside it
@@ -55,6 +66,8 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
 {
     constexpr int MT = BM / 64, NT = BN / 64;                 // 32 x 32 MFMA tiles per wavefront along m, n
     constexpr int kBN = BN, kBK = BK;
+    constexpr int kStageCols = BN < 128 ? BN : 128;           // the output tile is staged at most 128 columns at a time
+    constexpr int kOutRowBytes = kStageCols * 2 + 16;
     constexpr int kRowBytes = BK * 2 + 16;                    // data + 16 B pad against bank conflicts
     constexpr int kOperandBytes = (BM + kBN) * kRowBytes;
     constexpr int kStageBytes = BM * kOutRowBytes;
@@ -196,90 +209,137 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
 // Few rows (M <= 64: the branches of one draft position, Sec. 4.1).  The product is then bound by
 // reading w once and by latency, so the work is cut finely: one workgroup per 32 output columns,
 // its NW wavefronts take the 64-wide k blocks of the row round robin and their partial 32 x 32 tiles
-// are added through LDS.  Operands go from global memory straight into MFMA fragments.  Inside a
-// k block the half-wavefront h owns the contiguous 64 bytes k = 32 h .. 32 h + 31 of its row and
-// feeds them to four k16 steps, 16 bytes each: both operands use the same assignment, so the sum
-// over k is complete, and every lane pair reads one whole 128-byte line of w.
+// are added through LDS.  A wavefront fetches a k block of 32 rows x 128 bytes with four 16-byte
+// loads per lane, eight lanes on one row, so that every load instruction covers whole 128-byte
+// lines; the block then goes through a 4 KiB LDS patch private to the wavefront (16-byte slots
+// xor-swizzled by the row, conflict-free both ways) and comes back as MFMA fragments: lane (r, h)
+// takes the slots 4 h .. 4 h + 3 of row r, one per k16 step.  Both operands use the same slot
+// order, so the sum over k is complete.
 // grid: ceil(N / 32)
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int NW, int MB>
 __global__ void __launch_bounds__(NW * 64)
 linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const float *__restrict__ bias,
                      const bf16_t *residual, OutSplit out, int64_t M, int64_t N, int64_t K,
-                     const float *__restrict__ norm_w, float eps)
+                     const float *__restrict__ norm_w, float eps, ConvTail conv)
 {
-    __shared__ float part[NW][16][64];
-    __shared__ float ssq[NW][MB][64];                             // with norm_w: sum of x^2 per lane's row part
-    __shared__ float row_scale[32];
+    // LDS: in the main loop two 4 KiB patches per wavefront (w block, x block); afterwards the same
+    // memory holds the partial tiles, the sums of x^2 (with norm_w) and the row factors
+    __shared__ __attribute__((aligned(16))) unsigned char lds[NW * 8192];
+    float (*part)[16][64] = reinterpret_cast<float (*)[16][64]>(lds);
+    float (*ssq)[MB][4][64] = reinterpret_cast<float (*)[MB][4][64]>(lds + NW * 4096);
+    float *row_scale = reinterpret_cast<float *>(lds + NW * 4096 + NW * MB * 1024);
+    static_assert(NW * 4096 + NW * MB * 1024 + 128 <= NW * 8192, "LDS reuse");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane & 31, h = lane >> 5;
+    const int r = lane & 31, h = lane >> 5;                       // fragment view: row, k half
+    const int lrow = lane >> 3, lch = lane & 7;                   // load view: row (+ 8 i), 16-byte slot
     const int64_t n0 = (int64_t)blockIdx.x * 32;
     const int64_t kchunks = K / 8, kblocks = (K + 63) / 64;
-    int64_t wr = n0 + r;
-    wr = wr < N ? wr : N - 1;
-    const uint4 *wrow = reinterpret_cast<const uint4 *>(w + wr * K);
-    const uint4 *xrow[MB];
+    uint4 *patch_w = reinterpret_cast<uint4 *>(lds + wave * 8192), *patch_x = patch_w + 256;
+    const int put = lrow * 8 + (lch ^ lrow);                      // + 64 i: slot of row lrow + 8 i ((lrow + 8 i) & 7 == lrow)
+    int get[4];
 #pragma unroll
-    for (int b = 0; b < MB; ++b) {
-        int64_t m = b * 32 + r;
-        m = m < M ? m : M - 1;
-        xrow[b] = reinterpret_cast<const uint4 *>(x + m * K);
+    for (int s = 0; s < 4; ++s) get[s] = r * 8 + ((4 * h + s) ^ (r & 7));
+
+    const uint4 *wptr[4];
+    const uint4 *xptr[MB][4];
+    bool xlive[MB][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int64_t wr = n0 + lrow + 8 * i;
+        wr = wr < N ? wr : N - 1;                                 // columns past N repeat the last one, never stored
+        wptr[i] = reinterpret_cast<const uint4 *>(w + wr * K);
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
+            const int64_t m = b * 32 + lrow + 8 * i;
+            xlive[b][i] = m < M;                                  // rows past M stay zero
+            xptr[b][i] = reinterpret_cast<const uint4 *>(x + (xlive[b][i] ? m : 0) * K);
+        }
     }
     f32x16 acc[MB];
 #pragma unroll
     for (int b = 0; b < MB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+    float ss[MB][4];
+#pragma unroll
+    for (int b = 0; b < MB; ++b)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ss[b][i] = 0.0f;
 
     // A wavefront's k blocks are taken G at a time: all loads of a group are issued before its first
     // MFMA, so that a row of up to 64 * NW * G values costs one trip to memory, not one per block.
     constexpr int G = MB == 1 ? 3 : 2;
-    float ss[MB];
-#pragma unroll
-    for (int b = 0; b < MB; ++b) ss[b] = 0.0f;
     for (int64_t blk0 = wave; blk0 < kblocks; blk0 += (int64_t)NW * G) {
         uint4 wf[G][4], xf[G][MB][4];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int64_t blk = blk0 + (int64_t)g * NW;
+            const int64_t c = (blk0 + (int64_t)g * NW) * 8 + lch;
+            const bool ok = c < kchunks;                          // also false for blocks past the last
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int64_t c = blk * 8 + h * 4 + s;
-                const bool ok = c < kchunks;                      // also false for blk >= kblocks
-                wf[g][s] = ok ? wrow[c] : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < 4; ++i) {
+                wf[g][i] = ok ? wptr[i][c] : make_uint4(0, 0, 0, 0);
 #pragma unroll
-                for (int b = 0; b < MB; ++b) xf[g][b][s] = ok ? xrow[b][c] : make_uint4(0, 0, 0, 0);
+                for (int b = 0; b < MB; ++b) xf[g][b][i] = (ok && xlive[b][i]) ? xptr[b][i][c] : make_uint4(0, 0, 0, 0);
             }
         }
         if (norm_w) {
             // RMSNorm on the way in: the element-wise weight now, the row factor after the sums
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+            for (int g = 0; g < G; ++g) {
+                const int64_t c = (blk0 + (int64_t)g * NW) * 8 + lch;
+                if (c >= kchunks) continue;
+                const float4 g0 = reinterpret_cast<const float4 *>(norm_w)[2 * c];
+                const float4 g1 = reinterpret_cast<const float4 *>(norm_w)[2 * c + 1];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const int64_t c = (blk0 + (int64_t)g * NW) * 8 + h * 4 + s;
-                    if (c >= kchunks) continue;
-                    const float4 g0 = reinterpret_cast<const float4 *>(norm_w)[2 * c];
-                    const float4 g1 = reinterpret_cast<const float4 *>(norm_w)[2 * c + 1];
+                for (int b = 0; b < MB; ++b)
 #pragma unroll
-                    for (int b = 0; b < MB; ++b) {
-                        uint4 &q = xf[g][b][s];
+                    for (int i = 0; i < 4; ++i) {
+                        uint4 &q = xf[g][b][i];
                         const float v0 = bf16_lo(q.x), v1 = bf16_hi(q.x), v2 = bf16_lo(q.y), v3 = bf16_hi(q.y);
                         const float v4 = bf16_lo(q.z), v5 = bf16_hi(q.z), v6 = bf16_lo(q.w), v7 = bf16_hi(q.w);
-                        ss[b] += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3 + v4 * v4 + v5 * v5 + v6 * v6 + v7 * v7;
+                        ss[b][i] += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3 + v4 * v4 + v5 * v5 + v6 * v6 + v7 * v7;
                         q = make_uint4(f32x2_to_bf16x2(v0 * g0.x, v1 * g0.y), f32x2_to_bf16x2(v2 * g0.z, v3 * g0.w),
                                        f32x2_to_bf16x2(v4 * g1.x, v5 * g1.y), f32x2_to_bf16x2(v6 * g1.z, v7 * g1.w));
                     }
-                }
+            }
         }
 #pragma unroll
-        for (int g = 0; g < G; ++g)
+        for (int g = 0; g < G; ++g) {
+            bf16x8 wv[4], xv[4];
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+            for (int i = 0; i < 4; ++i) {
+                patch_w[put + 64 * i] = wf[g][i];
+                patch_x[put + 64 * i] = xf[g][0][i];
+            }
+            wave_sync();
 #pragma unroll
-                for (int b = 0; b < MB; ++b)
-                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xf[g][b][s]),
-                                                                     __builtin_bit_cast(bf16x8, wf[g][s]), acc[b], 0, 0, 0);
+            for (int s = 0; s < 4; ++s) {
+                wv[s] = __builtin_bit_cast(bf16x8, patch_w[get[s]]);
+                xv[s] = __builtin_bit_cast(bf16x8, patch_x[get[s]]);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[s], wv[s], acc[0], 0, 0, 0);
+#pragma unroll
+            for (int b = 1; b < MB; ++b) {
+                wave_sync();                                      // the x patch has been read
+#pragma unroll
+                for (int i = 0; i < 4; ++i) patch_x[put + 64 * i] = xf[g][b][i];
+                wave_sync();
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, patch_x[get[s]]), wv[s], acc[b], 0, 0, 0);
+            }
+            wave_sync();
+        }
     }
+    __syncthreads();                                              // patches are done with: their memory is reused below
 
     // acc[b][i] is C[m = 32 b + 8 (i / 4) + 4 (lane / 32) + i % 4][n = n0 + lane % 32]
 #pragma unroll
@@ -287,13 +347,18 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
         if (b > 0) __syncthreads();
 #pragma unroll
         for (int i = 0; i < 16; ++i) part[wave][i][lane] = acc[b][i];
-        if (norm_w) ssq[wave][b][lane] = ss[b];
+        if (norm_w) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ssq[wave][b][i][lane] = ss[b][i];
+        }
         __syncthreads();
         if (norm_w) {
-            if (tid < 32) {
+            if (tid < 32) {                                       // row tid = (tid & 7) + 8 (tid >> 3): lanes 8 (tid & 7) .. + 7, i = tid >> 3
                 float t = 0.0f;
 #pragma unroll
-                for (int q = 0; q < NW; ++q) t += ssq[q][b][tid] + ssq[q][b][tid + 32];
+                for (int q = 0; q < NW; ++q)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) t += ssq[q][b][tid >> 3][8 * (tid & 7) + j];
                 row_scale[tid] = __builtin_amdgcn_rsqf(t / (float)K + eps);
             }
             __syncthreads();
@@ -312,6 +377,30 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
             const int sp = locate(out, n, &col);
             const int64_t off = m * out.width[sp] + col;
             if (residual) v += bf16_to_f32(residual[off]);
+            if (conv.w && sp == 0) {
+                // the window of this (row, channel): K - 1 carried values, then v; same order of operations
+                // as the stand-alone conv kernel
+                const int H = conv.k - 1;
+                const int64_t p = conv.parent ? (int64_t)conv.parent[m] : m;
+                const bool p_ok = !conv.parent || (p >= 0 && p < conv.n_in);
+                const bf16_t *win = conv.src + ((p_ok ? p : 0) * out.width[0] + col) * H;
+                bf16_t *nwin = conv.dst + off * H;
+                const float *wk = conv.w + col * conv.k;
+                float a = conv.bias ? conv.bias[col] : 0.0f;
+                uint16_t carried[3] = {0x7fc0, 0x7fc0, 0x7fc0};
+#pragma unroll
+                for (int k = 0; k < 3; ++k)
+                    if (k < H && p_ok) carried[k] = win[k];
+#pragma unroll
+                for (int k = 0; k < 3; ++k)
+                    if (k < H) a = fmaf(wk[k], bf16_to_f32(carried[k]), a);
+                a = fmaf(wk[H], v, a);
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+                    if (k + 1 < H) nwin[k] = carried[k + 1];
+                if (H > 0) nwin[H - 1] = (bf16_t)f32_to_bf16(v);
+                v = silu_f32(a);
+            }
             out.ptr[sp][off] = (bf16_t)f32_to_bf16(v);
         }
     }
@@ -332,15 +421,17 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     const bf16_t *res = static_cast<const bf16_t *>(a.residual);
     // few rows: the split-k kernel, except for very wide outputs (the LM head), where the tiled kernel's
     // shared x tile reads less
-    if (a.M <= 64 && (N < 8192 || a.norm_w)) {
+    if (a.M <= 64 && (N < 8192 || a.norm_w || a.conv_w)) {
         const unsigned grid = (unsigned)((N + 31) / 32);
+        const ConvTail ct{a.conv_w, a.conv_b, static_cast<const bf16_t *>(a.conv_src), static_cast<bf16_t *>(a.conv_dst),
+                          a.conv_parent, a.conv_n_in, a.conv_k};
         const bool deep = a.K > 512;                              // more wavefronts share a long k loop
         if (a.M <= 32) {
-            if (deep) linear_skinny_kernel<8, 1><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps);
-            else      linear_skinny_kernel<4, 1><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps);
+            if (deep) linear_skinny_kernel<8, 1><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
+            else      linear_skinny_kernel<4, 1><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
         } else {
-            if (deep) linear_skinny_kernel<8, 2><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps);
-            else      linear_skinny_kernel<4, 2><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps);
+            if (deep) linear_skinny_kernel<8, 2><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
+            else      linear_skinny_kernel<4, 2><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
         }
         return hipGetLastError();
     }
@@ -348,9 +439,12 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     if (tiles(128, 128) >= 1024) {
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 127) / 128));
         linear_kernel<128, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
-    } else {
+    } else if (tiles(64, 128) >= MAMBA_LINEAR_MID) {
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 63) / 64));
         linear_kernel<64, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
+    } else {
+        dim3 grid((unsigned)((N + 63) / 64), (unsigned)((a.M + 63) / 64));
+        linear_kernel<64, 64, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
     }
     return hipGetLastError();
 }
