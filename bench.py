@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--no-wide-step", action="store_true",
                     help="skip the separate timing of the 64-branch, D=4096 state step")
     ap.add_argument("--no-block", action="store_true", help="skip the whole-block prefill timing")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time conv1d, scan, fork and step on every synthetic config (cfg0..cfg4), warm and "
+                         "cold, and (unless --no-cpu-baseline) the oracle on each; adds a few minutes")
     ap.add_argument("--no-drafter", action="store_true",
                     help="skip the whole-drafter timing (Mamba-130M shapes, prefix encoding and draft rounds)")
     ap.add_argument("--no-tree-draft", action="store_true",
@@ -366,6 +369,110 @@ def main():
                                                        drafter_detail["sequential_1_1_1_1_1_round_ms"], 3)
         del drafter, blocks_d
 
+    # every synthetic config, one entry point at a time: median of many launches from HIP events on the
+    # launch stream ("warm": same buffers every launch; "cold": a graph that walks rotating state
+    # buffers of more than 512 MB, so that every launch streams its state from HBM)
+    per_config = {}
+    if args.all_configs:
+        def median_ms(fn, n_warm=20, n=100):
+            for _ in range(n_warm):
+                fn()
+            pairs = []
+            for _ in range(n):
+                q0, q1 = ev(), ev()
+                q0.record()
+                fn()
+                q1.record()
+                pairs.append((q0, q1))
+            torch.cuda.synchronize()
+            return float(np.median([a.elapsed_time(b) for a, b in pairs]))
+
+        def graph_us(fn_round, launches, reps=5):
+            fn_round()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            sd = torch.cuda.Stream()
+            sd.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(sd):
+                with torch.cuda.graph(g, stream=sd):
+                    fn_round()
+            torch.cuda.current_stream().wait_stream(sd)
+            g.replay()
+            q0, q1 = ev(), ev()
+            q0.record()
+            for _ in range(reps):
+                g.replay()
+            q1.record()
+            torch.cuda.synchronize()
+            return q0.elapsed_time(q1) * 1e3 / (reps * launches)
+
+        rate = lambda nbytes, ms: {"GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                   "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                   "frac_of_copy_kernel": round(nbytes / (ms * 1e-3) / 1e9 / copy_gbs, 4)}
+        for name in ("cfg0", "cfg1", "cfg3", "cfg4"):
+            c = synth.CONFIGS[name]
+            cB, cL, cD, cN, cK = c["batch"], c["L"], c["D"], c["N"], c["K"]
+            ce = 2 if c["io"] == synth.BF16 else 4
+            cs = synth.config_prefill(name)
+            Q = {k: to_dev(cs[k]) for k in ("x", "z", "Bm", "Cm", "dt", "A", "Dskip", "dt_bias", "conv_w", "conv_bias")}
+            del cs
+            q_xc, q_out = torch.empty_like(Q["x"]), torch.empty_like(Q["x"])
+            q_cs = torch.empty((cB, cD, cK - 1), dtype=Q["x"].dtype, device=dev)
+            q_hf = torch.empty((cB, cD, cN), dtype=torch.float32, device=dev)
+            q_ws = torch.empty(max(m.mamba_scan_workspace_bytes(cB, cL, cD, cN, 0), 16), dtype=torch.uint8, device=dev)
+            n_l = 100 if name != "cfg4" else 30
+            cms = median_ms(lambda: m.mamba_conv1d_fwd(Q["x"], Q["conv_w"], Q["conv_bias"], None, y=q_xc,
+                                                       conv_state_out=q_cs), n=n_l)
+            sms = median_ms(lambda: m.mamba_scan_fwd(q_xc, Q["dt"], Q["A"], Q["Bm"], Q["Cm"], Q["Dskip"], Q["z"],
+                                                     Q["dt_bias"], out=q_out, h_final=q_hf, workspace=q_ws), n=n_l)
+            ent = {"shape": "batch %d x L %d x D %d, N %d, K %d, %s I/O" % (cB, cL, cD, cN, cK, c["io"]),
+                   "conv1d": dict(ms=round(cms, 5), tokens_per_s=round(cB * cL / (cms * 1e-3), 1),
+                                  **rate(conv_bytes(cB, cL, cD, cK, ce), cms)),
+                   "scan": dict(ms=round(sms, 5), tokens_per_s=round(cB * cL / (sms * 1e-3), 1),
+                                TFLOPs=round(scan_flops(cB, cL, cD, cN) / (sms * 1e-3) / 1e12, 2),
+                                frac_of_fp32_vector_peak=round(scan_flops(cB, cL, cD, cN) / (sms * 1e-3) / 1e12 /
+                                                               FP32_VECTOR_PEAK_TFLOPS, 4),
+                                **rate(scan_bytes(cB, cL, cD, cN, ce), sms)),
+                   "timing": "median of %d launches (HIP events), launches below ~15 us are bound by the host" % n_l}
+            per_config[name + "_prefill"] = ent
+            del Q, q_xc, q_out, q_ws
+        for name in ("cfg2", "cfg4"):
+            c = synth.CONFIGS[name]
+            cnb, cD, cN, cK, cnl = c["branches"], c["D"], c["N"], c["K"], c.get("n_layers", 1)
+            ce = 2 if c["io"] == synth.BF16 else 4
+            rg = np.random.default_rng(synth.SEEDS[name] + 500)
+            lp = {k: to_dev(v) for k, v in synth.layer_params(rg, cD, cN, cK).items()}
+            tk = {k: to_dev(v) for k, v in synth.token_inputs(rg, (cnb,), cD, cN, c["io"]).items()}
+            par = to_dev(rg.integers(0, cnb, cnb).astype(np.int32))
+            R = int(600e6 // (cnb * cD * cN * 4)) + 1
+            hin = [torch.randn((cnb, cD, cN), device=dev) for _ in range(R)]
+            hout = [torch.empty((cnb, cD, cN), device=dev) for _ in range(R)]
+            cin = [torch.randn((cnb, cD, cK - 1), device=dev).to(tk["x"].dtype) for _ in range(R)]
+            cout = [torch.empty_like(cin[0]) for _ in range(R)]
+            so = torch.empty((cnb, cD), dtype=tk["x"].dtype, device=dev)
+            sxc = torch.empty((cnb, 1, cD), dtype=tk["x"].dtype, device=dev)
+            step_i = lambda i: m.mamba_state_step(hin[i], tk["x"], tk["dt"], lp["A"], tk["Bm"], tk["Cm"], lp["Dskip"],
+                                                  tk["z"], lp["dt_bias"], parent_idx=par, h_out=hout[i], out=so)
+            fork_i = lambda i: m.mamba_state_fork(cin[i].unsqueeze(0), hin[i].unsqueeze(0), par, conv_dst=cout[i].unsqueeze(0),
+                                                  ssm_dst=hout[i].unsqueeze(0))
+            conv_i = lambda i: m.mamba_conv1d_fwd(tk["x"].unsqueeze(1), lp["conv_w"], lp["conv_bias"],
+                                                  conv_state_in=cout[i], y=sxc, conv_state_out=cout[i])
+            sb_ = step_bytes(cnb, cD, cN, ce)
+            fb_ = cnb * 2 * (cD * cN * 4 + cD * (cK - 1) * ce)
+            cb_ = cnb * (2 * cD * (cK - 1) * ce + 2 * cD * ce)
+            ent = {"shape": "%d branches, D %d, N %d, K %d, %s I/O, one layer; %d rotating buffer sets" %
+                            (cnb, cD, cN, cK, c["io"], R)}
+            for label, fn_i, nbytes in (("state_step_fused_parent", step_i, sb_), ("state_fork_unfused", fork_i, fb_),
+                                        ("conv_step", conv_i, cb_)):
+                cold = graph_us(lambda: [fn_i(i) for i in range(R)], R)
+                warm = graph_us(lambda: [fn_i(0) for _ in range(R)], R)
+                ent[label] = {"algorithmic_bytes": nbytes, "cold_us": round(cold, 3), "warm_us": round(warm, 3),
+                              "cold": rate(nbytes, cold * 1e-3), "warm": rate(nbytes, warm * 1e-3),
+                              "branch_steps_per_s_per_layer_cold": round(cnb / (cold * 1e-6), 1)}
+            ent["timing"] = "per launch inside a replayed HIP graph of %d launches" % R
+            per_config[name + "_decode"] = ent
+            del hin, hout, cin, cout
+
     tokens = B * L
     sb = scan_bytes(B, L, D, N, e)
     achieved = sb / (scan_ms * 1e-3) / 1e9
@@ -394,7 +501,7 @@ def main():
         "decode_launches": nsteps * (1 + 2 * nl), "decode_mode": "eager" if args.eager_decode else "hip_graph",
         "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide,
         "tree_draft_round": tree_detail, "whole_block": block_detail,
-        "whole_drafter": drafter_detail,
+        "whole_drafter": drafter_detail, "per_config": per_config,
     }
 
     result = {
@@ -428,6 +535,49 @@ def main():
             "sample": "%s prefill leg only (conv1d + scan, all %d channels, %d tokens), fp64, mean of "
                       "%d runs of %.2f s wall (%.0f core-seconds in all)"
                       % (args.prefill, D, tokens, reps, sec, reps * sec * oracle.num_threads())}
+        if args.all_configs:
+            # the oracle on every config, all threads; one thread as well where that takes seconds
+            per = {}
+            for name in ("cfg0", "cfg1", "cfg3", "cfg4"):
+                c = synth.CONFIGS[name]
+                cs = synth.config_prefill(name)
+                oq = {k: W(cs[k]) for k in ("x", "z", "Bm", "Cm", "dt", "A", "Dskip", "dt_bias", "conv_w", "conv_bias")}
+                del cs
+
+                def run_oracle():
+                    q0 = time.perf_counter()
+                    rx, _ = oracle.conv1d_fwd(oq["x"], oq["conv_w"], oq["conv_bias"])
+                    q1 = time.perf_counter()
+                    oracle.scan_fwd(rx, oq["dt"], oq["A"], oq["Bm"], oq["Cm"], oq["Dskip"], oq["z"], oq["dt_bias"])
+                    return q1 - q0, time.perf_counter() - q1
+                tc, ts = run_oracle()
+                ntok = c["batch"] * c["L"]
+                name = name + "_prefill"
+                per[name] = {"threads": oracle.num_threads(), "conv1d_s": round(tc, 4), "scan_s": round(ts, 4),
+                             "scan_tokens_per_s": round(ntok / ts, 1), "prefill_tokens_per_s": round(ntok / (tc + ts), 1)}
+                if name in ("cfg0_prefill", "cfg1_prefill"):
+                    oracle.set_num_threads(1)
+                    tc1, ts1 = run_oracle()
+                    oracle.set_num_threads(per[name]["threads"])
+                    per[name]["one_thread"] = {"conv1d_s": round(tc1, 4), "scan_s": round(ts1, 4),
+                                               "scan_tokens_per_s": round(ntok / ts1, 1)}
+                del oq
+            for name in ("cfg2", "cfg4"):
+                c = synth.CONFIGS[name]
+                rg = np.random.default_rng(synth.SEEDS[name] + 500)
+                lp = {k: W(v) for k, v in synth.layer_params(rg, c["D"], c["N"], c["K"]).items()}
+                tk = {k: W(v) for k, v in synth.token_inputs(rg, (c["branches"],), c["D"], c["N"], c["io"]).items()}
+                par = rg.integers(0, c["branches"], c["branches"]).astype(np.int32)
+                h_in = rg.standard_normal((c["branches"], c["D"], c["N"]))
+                reps_o = 20
+                q0 = time.perf_counter()
+                for _ in range(reps_o):
+                    oracle.state_step(h_in, tk["x"], tk["dt"], lp["A"], tk["Bm"], tk["Cm"], lp["Dskip"], tk["z"],
+                                      lp["dt_bias"], parent=par)
+                sec_o = (time.perf_counter() - q0) / reps_o
+                per[name + "_decode"] = {"threads": oracle.num_threads(), "state_step_s": round(sec_o, 6),
+                             "branch_steps_per_s_per_layer": round(c["branches"] / sec_o, 1)}
+            result["cpu_baseline"]["per_config"] = per
     print(json.dumps(result))
 
 
