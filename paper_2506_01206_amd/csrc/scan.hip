@@ -519,13 +519,25 @@ hipError_t launch_scan_t(const ScanArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+// Channels per lane.  Two halve the instruction overhead per state update, but also the number of
+// wavefronts and double every wavefront's serial walk, so they pay only when there is work for
+// several wavefronts per SIMD even so (measured: from about 2^25 channel-tokens on).  Two channels
+// per lane need even D so that every row keeps the pair's alignment.
+int scan_channels_per_lane(int64_t batch, int64_t L, int64_t D)
+{
+#ifdef MAMBA_SCAN_FORCE_CPL1
+    return 1;
+#else
+    if (D % 2 != 0) return 1;
+    const double work = (double)batch * (double)L * (double)D;
+    return work >= 33554432.0 ? 2 : 1;
+#endif
+}
+
 template <typename T, int N>
 hipError_t launch_scan_n(const ScanArgs &a, hipStream_t stream)
 {
-    // two channels per lane need even D so that every row keeps the pair's alignment
-#ifndef MAMBA_SCAN_FORCE_CPL1
-    if (a.D % 2 == 0) return launch_scan_t<T, N, 2>(a, stream);
-#endif
+    if (scan_channels_per_lane(a.batch, a.L, a.D) == 2) return launch_scan_t<T, N, 2>(a, stream);
     return launch_scan_t<T, N, 1>(a, stream);
 }
 
@@ -558,11 +570,7 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
     if (chunk_len_req > 0) {
         cl = chunk_len_req;
     } else {
-#ifndef MAMBA_SCAN_FORCE_CPL1
-        const int64_t cpl = (D % 2 == 0) ? 2 : 1;
-#else
-        const int64_t cpl = 1;
-#endif
+        const int64_t cpl = scan_channels_per_lane(batch, L, D);
         const int64_t columns = batch * ((D + kWave * cpl - 1) / (kWave * cpl));
         const int64_t target_waves = 3072;  // 3 resident wavefronts on each of 1024 SIMDs
         if (columns >= target_waves) {
@@ -571,7 +579,8 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
             const int64_t want = (target_waves + columns - 1) / columns;
             cl = (L + want - 1) / want;
             if (cl > 256) cl = 256;  // short chunks balance better across the chip
-            if (cl < 32) cl = 32;    // and long enough to amortize the chunk prologue and carry
+            const int64_t shortest = cpl == 2 ? 32 : 16;
+            if (cl < shortest) cl = shortest;  // long enough to amortize the chunk prologue and carry
             cl = (cl + kTile - 1) / kTile * kTile;
         }
     }
