@@ -8,13 +8,14 @@
 // split over up to three contiguous output tensors (in_proj -> x | z; x_proj -> dt_low | B | C), so
 // that the consumers get the dense (tokens, features) tensors they expect without a copy.
 //
-// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a BM x BN output tile (128 x 128, or 64 x 128
-// when that is needed to give every CU a few workgroups); each wavefront a (BM/2) x (BN/2) part as
+// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a BM x BN output tile (128 x 128, or 64 x 128 or
+// 64 x 64 when that is needed to give every CU a few workgroups); each wavefront a (BM/2) x (BN/2) part as
 // MFMA tiles of v_mfma_f32_32x32x16_bf16.  K is walked in slabs of BK = 64: the x and w slabs are
 // fetched with 16-byte loads one slab ahead into registers, parked in LDS (rows padded by 16 B)
 // and read back as MFMA fragments with 16-byte LDS reads: lane l holds row l % 32,
 // k = 8 * (l / 32) .. + 7 of each k16 step.  (A 128 x 256 tile halves the LDS reads per MFMA but
-// leaves one wavefront per SIMD and measured slower: three resident workgroups hide more latency.)
+// leaves one wavefront per SIMD and measured slower: three resident workgroups hide more latency;
+// so did 256 x 128 and 128 x 128 tiles with 32-wide slabs in two LDS buffers and one barrier per slab.)
 // Rows past M or N re-read the last valid row and are never stored; a K tail is zero-filled.
 // Epilogue: the accumulators (+ bias) are rounded to bf16 into LDS, then leave as 16-byte row
 // chunks (+ residual), so that stores are coalesced; output splits that are not multiples of 8

@@ -704,7 +704,9 @@ def test_scan_invariants_at_size(m):
                                           # few rows (draft positions): the split-k kernel, one or two row blocks
                                           (18, 3072, 768, (1536, 1536)), (12, 80, 1536, (48, 16, 16)), (32, 768, 1536, None),
                                           (33, 100, 520, (3, 90, 7)), (64, 50, 1544, None), (3, 1000, 72, None),
-                                          (65, 96, 512, None)])
+                                          (65, 96, 512, None),
+                                          # more than a thousand 128 x 128 tiles (ragged edges, short and odd slab counts)
+                                          (8190, 4100, 136, (2052, 2048)), (8192, 4096, 40, None), (8300, 4000, 32, (8, 3992))])
 def test_linear_against_oracle(m, M, N, K, splits):
     say(M=M, N=N, K=K, splits=splits)
     rng = np.random.default_rng(M + N + K)
