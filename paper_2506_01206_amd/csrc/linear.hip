@@ -274,6 +274,49 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
 #pragma unroll
         for (int i = 0; i < 4; ++i) ss[b][i] = 0.0f;
 
+    // What an output element needs besides the sums: bias, residual, and for the conv tail the carried
+    // window (through the parent index), the taps and the conv bias.  With one row block these loads
+    // are issued here, ahead of the main loop, so that the epilogue does not wait for them.
+    struct Tail {
+        float bias, res, cb, wk[4];
+        uint16_t carried[3];
+    };
+    constexpr int OPT = 16 * 64 / (NW * 64);                      // outputs per thread and row block
+    auto load_tail = [&](int b, int j) {
+        Tail t;
+        t.bias = t.res = t.cb = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) t.wk[k] = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) t.carried[k] = 0x7fc0;        // NaN unless a valid parent supplies it
+        const int o = tid + j * NW * 64, i = o >> 6, l = o & 63;
+        const int64_t m = b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
+        if (m >= M || n >= N) return t;
+        if (bias) t.bias = bias[n];
+        int64_t col;
+        const int sp = locate(out, n, &col);
+        if (residual) t.res = bf16_to_f32(residual[m * out.width[sp] + col]);
+        if (conv.w && sp == 0) {
+            const int H = conv.k - 1;
+            const int64_t p = conv.parent ? (int64_t)conv.parent[m] : m;
+            const bool p_ok = !conv.parent || (p >= 0 && p < conv.n_in);
+            const bf16_t *win = conv.src + ((p_ok ? p : 0) * out.width[0] + col) * H;
+            if (conv.bias) t.cb = conv.bias[col];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (k <= H) t.wk[k] = conv.w[col * conv.k + k];
+#pragma unroll
+            for (int k = 0; k < 3; ++k)
+                if (k < H && p_ok) t.carried[k] = win[k];
+        }
+        return t;
+    };
+    Tail early[OPT];
+    if constexpr (MB == 1) {
+#pragma unroll
+        for (int j = 0; j < OPT; ++j) early[j] = load_tail(0, j);
+    }
+
     // A wavefront's k blocks are taken G at a time: all loads of a group are issued before its first
     // MFMA, so that a row of up to 64 * NW * G values costs one trip to memory, not one per block.
     constexpr int G = MB == 1 ? 3 : 2;
@@ -364,41 +407,38 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
             }
             __syncthreads();
         }
-        for (int o = tid; o < 16 * 64; o += NW * 64) {
-            const int i = o >> 6, l = o & 63;
+#pragma unroll
+        for (int j = 0; j < OPT; ++j) {
+            const int o = tid + j * NW * 64, i = o >> 6, l = o & 63;
+            const Tail t = MB == 1 ? early[j] : load_tail(b, j);
             float v = 0.0f;
 #pragma unroll
             for (int q = 0; q < NW; ++q) v += part[q][i][l];
             if (norm_w) v *= row_scale[8 * (i >> 2) + 4 * (l >> 5) + (i & 3)];
             const int64_t m = b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
             if (m >= M || n >= N) continue;
-            if (bias) v += bias[n];
-            v = bf16_to_f32(f32_to_bf16(v));                      // same two roundings as the tiled kernel
+            v = bf16_to_f32(f32_to_bf16(v + t.bias));             // same two roundings as the tiled kernel
             int64_t col;
             const int sp = locate(out, n, &col);
             const int64_t off = m * out.width[sp] + col;
-            if (residual) v += bf16_to_f32(residual[off]);
+            if (residual) v += t.res;
             if (conv.w && sp == 0) {
                 // the window of this (row, channel): K - 1 carried values, then v; same order of operations
                 // as the stand-alone conv kernel
                 const int H = conv.k - 1;
-                const int64_t p = conv.parent ? (int64_t)conv.parent[m] : m;
-                const bool p_ok = !conv.parent || (p >= 0 && p < conv.n_in);
-                const bf16_t *win = conv.src + ((p_ok ? p : 0) * out.width[0] + col) * H;
                 bf16_t *nwin = conv.dst + off * H;
-                const float *wk = conv.w + col * conv.k;
-                float a = conv.bias ? conv.bias[col] : 0.0f;
-                uint16_t carried[3] = {0x7fc0, 0x7fc0, 0x7fc0};
+                float a = t.cb;
 #pragma unroll
                 for (int k = 0; k < 3; ++k)
-                    if (k < H && p_ok) carried[k] = win[k];
+                    if (k < H) a = fmaf(t.wk[k], bf16_to_f32(t.carried[k]), a);
+                float wlast = t.wk[0];
 #pragma unroll
-                for (int k = 0; k < 3; ++k)
-                    if (k < H) a = fmaf(wk[k], bf16_to_f32(carried[k]), a);
-                a = fmaf(wk[H], v, a);
+                for (int k = 1; k < 4; ++k)
+                    if (k == H) wlast = t.wk[k];
+                a = fmaf(wlast, v, a);
 #pragma unroll
                 for (int k = 0; k < 2; ++k)
-                    if (k + 1 < H) nwin[k] = carried[k + 1];
+                    if (k + 1 < H) nwin[k] = t.carried[k + 1];
                 if (H > 0) nwin[H - 1] = (bf16_t)f32_to_bf16(v);
                 v = silu_f32(a);
             }
