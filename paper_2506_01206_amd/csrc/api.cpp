@@ -363,21 +363,18 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
     const mamba_dtype_t io = MAMBA_BF16;
     int rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (n_out <= 64) {
-        // A draft position has a few rows and lives on launch latency, so the chain is shortened to four
-        // launches: RMSNorm rides into in_proj and the conv step (with the copy of the parent's window)
-        // out of it, the dt projection rides in the state step.  (Buffers: z -> b, x_c -> c, y -> d.)
-        int64_t conv_in_bytes, conv_out_bytes, ssm_in_bytes, ssm_out_bytes;
+    if (n_out > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    {
+        int64_t conv_in_bytes, conv_out_bytes, ssm_in_bytes, ssm_out_bytes, hid_bytes;
         if (!size3(n_in, Di, p->d_conv - 1, 2, &conv_in_bytes) || !size3(n_out, Di, p->d_conv - 1, 2, &conv_out_bytes) ||
-            !size3(n_in, Di, N, 4, &ssm_in_bytes) || !size3(n_out, Di, N, 4, &ssm_out_bytes))
+            !size3(n_in, Di, N, 4, &ssm_in_bytes) || !size3(n_out, Di, N, 4, &ssm_out_bytes) ||
+            !size3(n_out, p->d_model, 1, 2, &hid_bytes))
             return MAMBA_ERR_BAD_SHAPE;
         if (!aligned16(conv_src) || !aligned16(conv_dst) || !aligned16(ssm_src) || !aligned16(ssm_dst) || !aligned16(parent_idx))
             return MAMBA_ERR_MISALIGNED;
         if (parent_idx && (overlap(conv_dst, conv_out_bytes, conv_src, conv_in_bytes) ||
                            overlap(ssm_dst, ssm_out_bytes, ssm_src, ssm_in_bytes)))
             return MAMBA_ERR_ALIAS;
-        int64_t hid_bytes;
-        if (!size3(n_out, p->d_model, 1, 2, &hid_bytes)) return MAMBA_ERR_BAD_SHAPE;
         if (hidden != hidden_out && overlap(hidden, hid_bytes, hidden_out, hid_bytes)) return MAMBA_ERR_ALIAS;
         const void *state_bufs[4] = {conv_src, conv_dst, ssm_src, ssm_dst};
         const int64_t state_bytes[4] = {conv_in_bytes, conv_out_bytes, ssm_in_bytes, ssm_out_bytes};
@@ -388,6 +385,11 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
                 return MAMBA_ERR_ALIAS;
         if (overlap(hidden, hid_bytes, workspace, (int64_t)bb.total) || overlap(hidden_out, hid_bytes, workspace, (int64_t)bb.total))
             return MAMBA_ERR_ALIAS;
+    }
+    if (n_out <= 64) {
+        // A draft position has a few rows and lives on launch latency, so the chain is shortened to four
+        // launches: RMSNorm rides into in_proj and the conv step (with the copy of the parent's window)
+        // out of it, the dt projection rides in the state step.  (Buffers: z -> b, x_c -> c, y -> d.)
         // [x_c | z] = [silu(conv step(.)) | .] of rmsnorm(hidden) W_in^T; the conv windows move to conv_dst
         LinearArgs in{hidden, p->in_proj_w, nullptr, nullptr, {bb.c, bb.b, nullptr}, {Di, Di, 0}, n_out, p->d_model};
         in.norm_w = p->norm_w;
@@ -410,11 +412,13 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
     }
     if ((rc = mamba_rmsnorm_fwd(hidden, p->norm_w, bb.d, n_out, p->d_model, p->eps, io, hip_stream))) return rc;
     if ((rc = mamba_linear_fwd(bb.d, p->in_proj_w, nullptr, nullptr, bb.a, Di, bb.b, Di, nullptr, 0, n_out, p->d_model, io, hip_stream))) return rc;
-    // children take their parent's conv window, then the window is shifted in place in the destination cache
-    if (parent_idx &&
-        (rc = mamba_state_fork(conv_dst, conv_src, nullptr, nullptr, parent_idx, 1, n_out, n_in, Di, N, p->d_conv, io, hip_stream)))
-        return rc;
-    if ((rc = mamba_conv1d_fwd(bb.a, p->conv_w, p->conv_b, conv_dst, bb.c, conv_dst, n_out, 1, Di, p->d_conv, 1, io, hip_stream))) return rc;
+    // children read their parent's conv window and leave the shifted window in the destination cache
+    {
+        ConvArgs cv{bb.a, p->conv_w, p->conv_b, conv_src, bb.c, conv_dst, n_out, 1, Di, p->d_conv, 1, kIoBf16};
+        cv.parent = parent_idx;
+        cv.n_in = n_in;
+        if (hipError_t e = launch_conv1d(cv, stream)) return (int)e;
+    }
     if ((rc = mamba_linear_fwd(bb.c, p->x_proj_w, nullptr, nullptr, bb.dtl, R, bb.bm, N, bb.cm, N, n_out, Di, io, hip_stream))) return rc;
     if ((rc = mamba_linear_fwd(bb.dtl, p->dt_proj_w, nullptr, nullptr, bb.a, Di, nullptr, 0, nullptr, 0, n_out, R, io, hip_stream))) return rc;
     if ((rc = mamba_state_step(ssm_dst, ssm_src, parent_idx, bb.c, bb.a, p->A, bb.bm, bb.cm, p->Dskip, bb.b, p->dt_bias, bb.d,
