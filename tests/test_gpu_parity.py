@@ -706,7 +706,11 @@ def test_scan_invariants_at_size(m):
                                           (33, 100, 520, (3, 90, 7)), (64, 50, 1544, None), (3, 1000, 72, None),
                                           (65, 96, 512, None),
                                           # more than a thousand 128 x 128 tiles (ragged edges, short and odd slab counts)
-                                          (8190, 4100, 136, (2052, 2048)), (8192, 4096, 40, None), (8300, 4000, 32, (8, 3992))])
+                                          (8190, 4100, 136, (2052, 2048)), (8192, 4096, 40, None), (8300, 4000, 32, (8, 3992)),
+                                          # whole slabs only (K a multiple of 64): 1, 2, 3, 5 and 7 of them, ragged edges,
+                                          # split outputs
+                                          (4096, 4096, 64, None), (4100, 4000, 128, (2000, 2000)), (4096, 4104, 192, None),
+                                          (4090, 4096, 320, (4088, 8)), (5000, 3400, 448, (1000, 1200, 1200))])
 def test_linear_against_oracle(m, M, N, K, splits):
     say(M=M, N=N, K=K, splits=splits)
     rng = np.random.default_rng(M + N + K)
