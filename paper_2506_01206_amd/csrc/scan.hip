@@ -469,6 +469,73 @@ scan_carry(const float *__restrict__ A, const float *h0, float *ws_state,
     carry_walk<true>(h, a2, st, sd, c0, c1, DN, D);
 }
 
+// The same carry for up to kFastSegs * kFastPer links with a single trip to memory: 16 segments of at
+// most 16 chunks; a lane fetches all local states and delta sums of its segment at once, folds them in
+// registers, and after the exchange walks the registers again, so the second walk loads nothing.
+// block: (64 lanes over (b,d,n), 16 segments)
+constexpr int kFastSegs = 16;
+constexpr int kFastPer = 16;
+
+__global__ void __launch_bounds__(kWave * kFastSegs)
+scan_carry_fast(const float *__restrict__ A, const float *h0, float *ws_state,
+                const float *__restrict__ ws_sumdt, int64_t batch, int64_t D, int N, int n_chunks)
+{
+    __shared__ float decay[kFastSegs][kWave], offset[kFastSegs][kWave];
+    const int lane = threadIdx.x, seg = threadIdx.y;
+    const int64_t DN = D * N;
+    const int64_t idx_raw = (int64_t)blockIdx.x * kWave + lane;
+    const bool live = idx_raw < batch * DN;
+    const int64_t idx = live ? idx_raw : batch * DN - 1;
+    const int64_t b = idx / DN;
+    const int64_t dn = idx - b * DN;
+    const int64_t d = dn / N;
+    const float a2 = A[dn] * kLog2e;
+    float *st = ws_state + b * n_chunks * DN + dn;
+    const float *sd = ws_sumdt + b * n_chunks * D + d;
+    const int per = (n_chunks - 1 + kFastSegs - 1) / kFastSegs;   // <= kFastPer, checked by the launcher
+    int c0 = 1 + seg * per, c1 = c0 + per;
+    if (c0 > n_chunks) c0 = n_chunks;
+    if (c1 > n_chunks) c1 = n_chunks;
+
+    float loc[kFastPer], e[kFastPer];
+#pragma unroll
+    for (int i = 0; i < kFastPer; ++i) {
+        const bool in = c0 + i < c1;
+        loc[i] = in ? st[(int64_t)(c0 + i) * DN] : 0.0f;
+        e[i] = in ? sd[(int64_t)(c0 + i - 1) * D] : 0.0f;        // delta sum first, decay below
+    }
+    float sum = 0.0f, h = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kFastPer; ++i) {
+        sum += e[i];
+        e[i] = exp2_hw(a2 * e[i]);                                // 1 for the unused tail (sum 0), with loc 0: no effect
+        h = fmaf(e[i], h, loc[i]);
+    }
+    decay[seg][lane] = exp2_hw(a2 * sum);
+    offset[seg][lane] = h;
+    __syncthreads();
+    h = h0 ? h0[idx] : 0.0f;
+    for (int s = 0; s < seg; ++s) h = fmaf(decay[s][lane], h, offset[s][lane]);
+    if (!live) return;
+    if (seg == 0) st[0] = h;
+#pragma unroll
+    for (int i = 0; i < kFastPer; ++i) {
+        h = fmaf(e[i], h, loc[i]);
+        if (c0 + i < c1) st[(int64_t)(c0 + i) * DN] = h;
+    }
+}
+
+// launches the carry over the chunk states
+inline void launch_carry(const ScanArgs &a, int N, int nc, float *ws_state, const float *ws_sumdt, hipStream_t stream)
+{
+    const int64_t total = a.batch * a.D * N;
+    const unsigned blocks = (unsigned)((total + kWave - 1) / kWave);
+    if (nc - 1 <= kFastSegs * kFastPer)
+        scan_carry_fast<<<blocks, dim3(kWave, kFastSegs), 0, stream>>>(a.A, a.h0, ws_state, ws_sumdt, a.batch, a.D, N, nc);
+    else
+        scan_carry<<<blocks, dim3(kWave, kCarrySegs), 0, stream>>>(a.A, a.h0, ws_state, ws_sumdt, a.batch, a.D, N, nc);
+}
+
 // copies h0 (or zeros) to h_final when L == 0
 __global__ void copy_state(const float *h0, float *h_final, int64_t n)
 {
@@ -497,9 +564,7 @@ hipError_t launch_scan_t(const ScanArgs &a, hipStream_t stream)
         else
             scan_chunk_state<T, N, CPL, false><<<g1, kWave, 0, stream>>>(
                 x, dt, a.A, Bm, a.dt_bias, ws_state, ws_sumdt, a.L, a.D, a.chunk_len, nc);
-        const int64_t total = a.batch * a.D * N;
-        scan_carry<<<(unsigned)((total + kWave - 1) / kWave), dim3(kWave, kCarrySegs), 0, stream>>>(
-            a.A, a.h0, ws_state, ws_sumdt, a.batch, a.D, N, nc);
+        launch_carry(a, N, nc, ws_state, ws_sumdt, stream);
         h_start = ws_state;
         chunked = 1;
     }
