@@ -494,3 +494,69 @@ def test_drafter_tree_reduces_to_greedy_decoding_and_to_prefill():
     lg2, _, _ = od.prefill(w, np.concatenate([prefix, [second]]).astype(np.int32))
     order = np.argsort(-lg2[0], kind="stable")[:2]
     assert list(wide[1][2:4]) == list(order)
+
+
+# ------------------------------------------------------------------------------------ Mamba-2 style core
+def _ssd_case(rng, B, L, H, P, N):
+    return dict(x=rng.standard_normal((B, L, H, P)), z=rng.standard_normal((B, L, H, P)),
+                dt=0.5 * rng.standard_normal((B, L, H)), Bm=rng.standard_normal((B, L, N)), Cm=rng.standard_normal((B, L, N)),
+                A=-rng.uniform(0.3, 4.0, H), Dskip=rng.standard_normal(H), dt_bias=rng.uniform(-3, 0, H),
+                h0=rng.standard_normal((B, H, P, N)))
+
+
+def test_ssd_oracle_is_the_selective_scan_with_one_decay_per_head():
+    """The scalar-decay layer is the selective scan of the paper's drafter with A[d, n] = A[head(d)] and
+    dt, D, dt_bias repeated over a head's channels: checked against the (separately pinned) C oracle."""
+    from oracle import ssd
+    rng = np.random.default_rng(21)
+    B, L, H, P, N = 2, 37, 3, 4, 8
+    c = _ssd_case(rng, B, L, H, P, N)
+    out, hf = ssd.ssd_scan(c["x"], c["dt"], c["A"], c["Bm"], c["Cm"], c["Dskip"], c["z"], c["dt_bias"], c["h0"])
+    rep = lambda a: np.repeat(a, P, axis=-1)
+    o1, h1 = oracle.scan_fwd(c["x"].reshape(B, L, H * P), rep(c["dt"]), np.repeat(c["A"], P)[:, None] * np.ones((1, N)),
+                             c["Bm"], c["Cm"], rep(c["Dskip"]), c["z"].reshape(B, L, H * P), rep(c["dt_bias"]),
+                             c["h0"].reshape(B, H * P, N))
+    np.testing.assert_allclose(out.reshape(B, L, H * P), o1, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(hf.reshape(B, H * P, N), h1, rtol=1e-12, atol=1e-12)
+
+
+def test_ssd_oracle_against_the_dual_matrix_form_and_closed_form():
+    """(a) The dual form: y_t = sum_{s<=t} (C_t . B_s) exp(sum_{r=s+1..t} delta_r A) delta_s x_s + decayed h0 term,
+    written out with explicit loops on a tiny case.  (b) Constant inputs: a geometric series.
+    (c) A scan equals repeated single steps, also through a parent index."""
+    from oracle import ssd
+    rng = np.random.default_rng(22)
+    B, L, H, P, N = 1, 6, 2, 3, 4
+    c = _ssd_case(rng, B, L, H, P, N)
+    out, hf = ssd.ssd_scan(c["x"], c["dt"], c["A"], c["Bm"], c["Cm"], c["Dskip"], None, c["dt_bias"], c["h0"])
+    delta = np.logaddexp(0.0, c["dt"] + c["dt_bias"])
+    for h in range(H):
+        for t in range(L):
+            for p in range(P):
+                y = c["Dskip"][h] * c["x"][0, t, h, p]
+                for s in range(t + 1):
+                    decay = np.exp(c["A"][h] * delta[0, s + 1:t + 1, h].sum())
+                    y += (c["Cm"][0, t] @ c["Bm"][0, s]) * decay * delta[0, s, h] * c["x"][0, s, h, p]
+                y += np.exp(c["A"][h] * delta[0, :t + 1, h].sum()) * (c["h0"][0, h, p] @ c["Cm"][0, t])
+                assert abs(out[0, t, h, p] - y) < 1e-11 * max(1.0, abs(y))
+    # constant inputs
+    L2, d0, xv = 50, 0.3, 1.7
+    bvec, cvec = rng.standard_normal(N), rng.standard_normal(N)
+    x = np.full((1, L2, 1, 1), xv)
+    o, hfin = ssd.ssd_scan(x, np.full((1, L2, 1), d0), np.array([-0.9]), np.tile(bvec, (1, L2, 1)), np.tile(cvec, (1, L2, 1)),
+                           dt_softplus=False)
+    abar = np.exp(-0.9 * d0)
+    for t in (0, 7, L2 - 1):
+        hn = d0 * xv * bvec * (1 - abar ** (t + 1)) / (1 - abar)
+        assert abs(o[0, t, 0, 0] - cvec @ hn) < 1e-12 * max(1.0, abs(cvec @ hn))
+    np.testing.assert_allclose(hfin[0, 0, 0], d0 * xv * bvec * (1 - abar ** L2) / (1 - abar), rtol=1e-12)
+    # steps
+    h = c["h0"]
+    for t in range(L):
+        h, o_t = ssd.ssd_step(h, c["x"][:, t], c["dt"][:, t], c["A"], c["Bm"][:, t], c["Cm"][:, t], c["Dskip"], None, c["dt_bias"])
+        np.testing.assert_allclose(o_t, out[:, t], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(h, hf, rtol=1e-12, atol=1e-12)
+    two = np.concatenate([c["h0"], 2 * c["h0"]])
+    h2, _ = ssd.ssd_step(two, np.repeat(c["x"][:, 0], 3, 0), np.repeat(c["dt"][:, 0], 3, 0), c["A"], np.repeat(c["Bm"][:, 0], 3, 0),
+                         np.repeat(c["Cm"][:, 0], 3, 0), parent=np.array([1, 0, 1]))
+    assert np.array_equal(h2[0], h2[2]) and not np.array_equal(h2[0], h2[1])
