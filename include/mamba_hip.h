@@ -267,6 +267,35 @@ int mamba_tree_plan(const int32_t *tree, int gamma, int64_t n_layers, int64_t D,
 int mamba_tree_parents(void *slab, const mamba_tree_plan_t *plan, const int32_t *tree,
                        void *hip_stream);
 
+/*
+ * Scalar-decay (Mamba-2 style) layer core.  The paper names Mamba-2 as a drafter its method carries over
+ * to (Sec. 1); the layer is the state-space-dual layer of Dao & Gu (2024).  Per head h with P channels and
+ * N states, one decay per head and step:
+ *   delta[t,h] = softplus(dt[t,h] + dt_bias[h])      (dt_softplus = 0: delta = dt + dt_bias)
+ *   H_t[h] = exp(delta[t,h] A[h]) H_{t-1}[h] + delta[t,h] x_t[h,:] (outer) B_t
+ *   y_t[h,:] = H_t[h] C_t + Dskip[h] x_t[h,:];  out = y silu(z) when z is given
+ * Layout (device pointers, 16-byte aligned): x, z, out (batch, L, H, P) and dt (batch, L, H) in the I/O
+ * dtype; Bm, Cm (batch, L, N), one group shared by all heads; A, Dskip, dt_bias float[H] (Dskip, dt_bias,
+ * z, h0, h_final nullable); states h0, h_final (batch, H, P, N) float.  P = 64, N in {64, 128}.
+ *
+ * mamba2_ssd_fwd encodes a sequence in chunks of 64 steps on the matrix cores (bf16 I/O only);
+ * workspace: device scratch of mamba2_ssd_workspace_bytes(batch, L, H, P, N) bytes (0 for an unsupported
+ * shape), caller-owned.  mamba2_state_step advances n_out draft branches by one token (x, z, out
+ * (n_out, H, P), dt (n_out, H), Bm, Cm (n_out, N); h_in (n_in, H, P, N), h_out (n_out, H, P, N)); branch j
+ * continues from h_in[parent_idx[j]] (device int32[n_out]; NULL: h_in[j], and then h_out may be h_in);
+ * an index outside [0, n_in) gives NaN for that branch.  mamba_state_fork copies such states too
+ * (pass D = H * P).  Errors as for the selective scan; batch, H, n_out <= 65535.
+ */
+size_t mamba2_ssd_workspace_bytes(int64_t batch, int64_t L, int64_t H, int64_t P, int64_t N);
+int mamba2_ssd_fwd(const void *x, const void *dt, const float *A, const void *Bm, const void *Cm,
+                   const float *Dskip, const void *z, const float *dt_bias, const float *h0, void *out,
+                   float *h_final, void *workspace, size_t workspace_bytes, int64_t batch, int64_t L,
+                   int64_t H, int64_t P, int64_t N, int dt_softplus, mamba_dtype_t io, void *hip_stream);
+int mamba2_state_step(float *h_out, const float *h_in, const int32_t *parent_idx, const void *x,
+                      const void *dt, const float *A, const void *Bm, const void *Cm, const float *Dskip,
+                      const void *z, const float *dt_bias, void *out, int64_t n_out, int64_t n_in,
+                      int64_t H, int64_t P, int64_t N, int dt_softplus, mamba_dtype_t io, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

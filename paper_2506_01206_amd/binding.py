@@ -61,6 +61,12 @@ def _declare(lib):
     lib.mamba_block_fwd.restype = _int
     lib.mamba_block_step.argtypes = [_bpp] + [_vp] * 8 + [_sz, _i64, _i64, _vp]
     lib.mamba_block_step.restype = _int
+    lib.mamba2_ssd_workspace_bytes.argtypes = [_i64] * 5
+    lib.mamba2_ssd_workspace_bytes.restype = _sz
+    lib.mamba2_ssd_fwd.argtypes = [_vp] * 12 + [_sz] + [_i64] * 5 + [_int, _int, _vp]
+    lib.mamba2_ssd_fwd.restype = _int
+    lib.mamba2_state_step.argtypes = [_vp] * 12 + [_i64] * 5 + [_int, _int, _vp]
+    lib.mamba2_state_step.restype = _int
     lib.mamba_embedding_fwd.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]
     lib.mamba_embedding_fwd.restype = _int
     lib.mamba_topk_fwd.argtypes = [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]
@@ -94,7 +100,8 @@ lib = _declare(ctypes.CDLL(LIB_PATH))
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
            "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork", "mamba_tree_plan",
            "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "mamba_block_workspace_bytes",
-           "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd")
+           "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd",
+           "mamba2_ssd_workspace_bytes", "mamba2_ssd_fwd", "mamba2_state_step")
 
 
 class MambaError(RuntimeError):
@@ -397,3 +404,51 @@ def mamba_topk_fwd(logits, k, idx=None, val=None, stream=None):
                             _ptr(val, torch.float32, (M, k), "val"), M, V, int(k), _io_code(logits), _stream(stream))
     _check("mamba_topk_fwd", st)
     return idx, val
+
+
+def mamba2_ssd_workspace_bytes(batch, L, H, P, N) -> int:
+    return int(lib.mamba2_ssd_workspace_bytes(batch, L, H, P, N))
+
+
+def mamba2_ssd_fwd(x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, h0=None, out=None, h_final=None,
+                   workspace=None, want_state=True, dt_softplus=True, stream=None):
+    """Scalar-decay layer core: x, z (B,L,H,P) bf16; dt (B,L,H); Bm, Cm (B,L,N); A, Dskip, dt_bias (H) f32;
+    h0 (B,H,P,N) f32 -> out (B,L,H,P), h_final (B,H,P,N)."""
+    B, L, H, P = x.shape
+    N = Bm.shape[-1]
+    if out is None:
+        out = torch.empty_like(x)
+    if want_state and h_final is None:
+        h_final = torch.empty((B, H, P, N), dtype=torch.float32, device=x.device)
+    need = mamba2_ssd_workspace_bytes(B, L, H, P, N)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    st = lib.mamba2_ssd_fwd(
+        _ptr(x, name="x"), _ptr(dt, x.dtype, (B, L, H), "dt"), _ptr(A, torch.float32, (H,), "A"),
+        _ptr(Bm, x.dtype, (B, L, N), "Bm"), _ptr(Cm, x.dtype, (B, L, N), "Cm"), _ptr(Dskip, torch.float32, (H,), "Dskip"),
+        _ptr(z, x.dtype, (B, L, H, P), "z"), _ptr(dt_bias, torch.float32, (H,), "dt_bias"),
+        _ptr(h0, torch.float32, (B, H, P, N), "h0"), _ptr(out, x.dtype, (B, L, H, P), "out"),
+        _ptr(h_final, torch.float32, (B, H, P, N), "h_final"), _ptr(workspace, name="workspace"),
+        workspace.numel() * workspace.element_size(), B, L, H, P, N, int(bool(dt_softplus)), _io_code(x), _stream(stream))
+    _check("mamba2_ssd_fwd", st)
+    return out, h_final
+
+
+def mamba2_state_step(h_in, x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, parent_idx=None, h_out=None, out=None,
+                      dt_softplus=True, stream=None):
+    """h_in (n_in,H,P,N) f32; x, z (n_out,H,P); dt (n_out,H); Bm, Cm (n_out,N) -> h_out (n_out,H,P,N), out (n_out,H,P)."""
+    n_in, H, P, N = h_in.shape
+    n_out = x.shape[0]
+    if h_out is None:
+        h_out = torch.empty((n_out, H, P, N), dtype=torch.float32, device=x.device)
+    if out is None:
+        out = torch.empty_like(x)
+    st = lib.mamba2_state_step(
+        _ptr(h_out, torch.float32, (n_out, H, P, N), "h_out"), _ptr(h_in, torch.float32, name="h_in"),
+        _ptr(parent_idx, torch.int32, (n_out,), "parent_idx"), _ptr(x, name="x"), _ptr(dt, x.dtype, (n_out, H), "dt"),
+        _ptr(A, torch.float32, (H,), "A"), _ptr(Bm, x.dtype, (n_out, N), "Bm"), _ptr(Cm, x.dtype, (n_out, N), "Cm"),
+        _ptr(Dskip, torch.float32, (H,), "Dskip"), _ptr(z, x.dtype, (n_out, H, P), "z"),
+        _ptr(dt_bias, torch.float32, (H,), "dt_bias"), _ptr(out, x.dtype, (n_out, H, P), "out"),
+        n_out, n_in, H, P, N, int(bool(dt_softplus)), _io_code(x), _stream(stream))
+    _check("mamba2_state_step", st)
+    return h_out, out

@@ -458,6 +458,89 @@ int mamba_topk_fwd(const void *logits, int32_t *idx, float *val, int64_t M, int6
     return (int)launch_topk(logits, idx, val, M, V, k, static_cast<hipStream_t>(hip_stream));
 }
 
+namespace {
+bool ssd_shape_ok(int64_t P, int64_t N) { return P == 64 && (N == 64 || N == 128); }
+}  // namespace
+
+size_t mamba2_ssd_workspace_bytes(int64_t batch, int64_t L, int64_t H, int64_t P, int64_t N)
+{
+    int64_t t;
+    if (batch <= 0 || L <= 0 || H <= 0 || !ssd_shape_ok(P, N)) return 0;
+    if (!size3(batch, L / 64 + 2, H, 1, &t) || !size3(t, P, N + 1, 4, &t)) return 0;
+    return ssd_workspace_bytes(batch, L, H, P, N);
+}
+
+int mamba2_ssd_fwd(const void *x, const void *dt, const float *A, const void *Bm, const void *Cm, const float *Dskip,
+                   const void *z, const float *dt_bias, const float *h0, void *out, float *h_final, void *workspace,
+                   size_t workspace_bytes, int64_t batch, int64_t L, int64_t H, int64_t P, int64_t N, int dt_softplus,
+                   mamba_dtype_t io, void *hip_stream)
+{
+    if (io != MAMBA_BF16) return MAMBA_ERR_UNSUPPORTED;
+    if (batch < 0 || L < 0 || H < 0 || P < 0 || N < 0) return MAMBA_ERR_BAD_SHAPE;
+    int64_t hp, tok_bytes, dt_bytes, bc_bytes, st_bytes, t;
+    if (!mul_ok(H, P, &hp) || !size3(batch, L, hp, 2, &tok_bytes) || !size3(batch, L, H, 2, &dt_bytes) ||
+        !size3(batch, L, N, 2, &bc_bytes) || !size3(batch, hp, N, 4, &st_bytes) ||
+        !size3(batch, L / 64 + 2, H, 1, &t) || !size3(t, P, N + 1, 4, &t))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (!ssd_shape_ok(P, N) || batch > kMaxGridYZ || H > kMaxGridYZ || L > ((int64_t)1 << 31)) return MAMBA_ERR_UNSUPPORTED;
+    if (batch == 0 || H == 0) return MAMBA_OK;
+    if (L == 0) {
+        if (h_final && h_final != h0) {
+            if (!aligned16(h_final) || !aligned16(h0)) return MAMBA_ERR_MISALIGNED;
+            return (int)launch_copy_state(h0, h_final, batch * hp * N, static_cast<hipStream_t>(hip_stream));
+        }
+        return MAMBA_OK;
+    }
+    if (!x || !dt || !A || !Bm || !Cm || !out) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(x) || !aligned16(dt) || !aligned16(A) || !aligned16(Bm) || !aligned16(Cm) || !aligned16(Dskip) ||
+        !aligned16(z) || !aligned16(dt_bias) || !aligned16(h0) || !aligned16(out) || !aligned16(h_final) || !aligned16(workspace))
+        return MAMBA_ERR_MISALIGNED;
+    const size_t need = ssd_workspace_bytes(batch, L, H, P, N);
+    if (!workspace || workspace_bytes < need) return MAMBA_ERR_WORKSPACE;
+    if (overlap(out, tok_bytes, x, tok_bytes) || overlap(out, tok_bytes, z, tok_bytes) || overlap(out, tok_bytes, dt, dt_bytes) ||
+        overlap(out, tok_bytes, Bm, bc_bytes) || overlap(out, tok_bytes, Cm, bc_bytes) || overlap(out, tok_bytes, h0, st_bytes) ||
+        overlap(out, tok_bytes, h_final, st_bytes) || overlap(out, tok_bytes, workspace, (int64_t)need) ||
+        overlap(workspace, (int64_t)need, x, tok_bytes) || overlap(workspace, (int64_t)need, z, tok_bytes) ||
+        overlap(workspace, (int64_t)need, dt, dt_bytes) || overlap(workspace, (int64_t)need, Bm, bc_bytes) ||
+        overlap(workspace, (int64_t)need, Cm, bc_bytes) || overlap(workspace, (int64_t)need, h0, st_bytes) ||
+        overlap(workspace, (int64_t)need, h_final, st_bytes) ||
+        overlap(h_final, st_bytes, x, tok_bytes) || overlap(h_final, st_bytes, z, tok_bytes))
+        return MAMBA_ERR_ALIAS;
+    SsdArgs a{x, dt, Bm, Cm, z, A, Dskip, dt_bias, h0, out, h_final, static_cast<float *>(workspace), batch, L, H, (int)P, (int)N,
+              dt_softplus};
+    return (int)launch_ssd(a, static_cast<hipStream_t>(hip_stream));
+}
+
+int mamba2_state_step(float *h_out, const float *h_in, const int32_t *parent_idx, const void *x, const void *dt,
+                      const float *A, const void *Bm, const void *Cm, const float *Dskip, const void *z,
+                      const float *dt_bias, void *out, int64_t n_out, int64_t n_in, int64_t H, int64_t P, int64_t N,
+                      int dt_softplus, mamba_dtype_t io, void *hip_stream)
+{
+    const int e = io_size(io);
+    if (e == 0) return MAMBA_ERR_UNSUPPORTED;
+    if (n_out < 0 || n_in < 0 || H < 0 || P < 0 || N < 0) return MAMBA_ERR_BAD_SHAPE;
+    int64_t hp, out_bytes, hin_bytes, hout_bytes;
+    if (!mul_ok(H, P, &hp) || !size3(n_out, hp, 1, e, &out_bytes) || !size3(n_in, hp, N, 4, &hin_bytes) ||
+        !size3(n_out, hp, N, 4, &hout_bytes))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (!parent_idx && n_in != n_out) return MAMBA_ERR_BAD_SHAPE;
+    if (n_out > 0 && n_in == 0) return MAMBA_ERR_BAD_SHAPE;
+    if (!ssd_shape_ok(P, N) || n_out > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    if (n_out == 0 || H == 0) return MAMBA_OK;
+    if (!h_out || !h_in || !x || !dt || !A || !Bm || !Cm || !out) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(h_out) || !aligned16(h_in) || !aligned16(parent_idx) || !aligned16(x) || !aligned16(dt) || !aligned16(A) ||
+        !aligned16(Bm) || !aligned16(Cm) || !aligned16(Dskip) || !aligned16(z) || !aligned16(dt_bias) || !aligned16(out))
+        return MAMBA_ERR_MISALIGNED;
+    if (!(h_out == h_in && !parent_idx) && overlap(h_out, hout_bytes, h_in, hin_bytes)) return MAMBA_ERR_ALIAS;
+    if (overlap(out, out_bytes, x, out_bytes) || overlap(out, out_bytes, z, out_bytes) || overlap(out, out_bytes, h_in, hin_bytes) ||
+        overlap(out, out_bytes, h_out, hout_bytes) || overlap(h_out, hout_bytes, x, out_bytes) ||
+        overlap(h_out, hout_bytes, z, out_bytes))
+        return MAMBA_ERR_ALIAS;
+    SsdStepArgs a{h_out, h_in, parent_idx, x, dt, Bm, Cm, z, A, Dskip, dt_bias, out, n_out, n_in, H, (int)P, (int)N, (int)io,
+                  dt_softplus};
+    return (int)launch_ssd_step(a, static_cast<hipStream_t>(hip_stream));
+}
+
 int mamba_tree_plan(const int32_t *tree, int gamma, int64_t n_layers, int64_t D, int64_t N, int K,
                     mamba_dtype_t conv_dtype, mamba_tree_plan_t *plan)
 {

@@ -40,6 +40,38 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
                int64_t *chunk_len, int64_t *n_chunks);
 size_t scan_workspace_bytes(int64_t batch, int64_t D, int64_t N, int64_t n_chunks);
 hipError_t launch_scan(const ScanArgs &a, hipStream_t stream);
+// Carry over chunk states, in place: slot 0 <- h0 (or 0); slot c <- exp(A * sumdt[c-1]) * slot[c-1] + slot[c].
+// ws_state: (batch, n_slots, D, N) fp32, slot c holding the local end state of chunk c - 1 on entry;
+// ws_sumdt: (batch, n_slots, D) fp32, entry c the sum of deltas of chunk c; A: (D, N).
+hipError_t launch_chunk_carry(const float *A, const float *h0, float *ws_state, const float *ws_sumdt, int64_t batch,
+                              int64_t D, int N, int n_slots, hipStream_t stream);
+hipError_t launch_copy_state(const float *src /* nullptr: zeros */, float *dst, int64_t n, hipStream_t stream);
+
+// Scalar-decay (Mamba-2 style) layer core.  x, z, out: (batch, L, H, P); dt: (batch, L, H); Bm, Cm: (batch, L, N);
+// A, Dskip, dt_bias: (H); h0, h_final: (batch, H, P, N) fp32.  P = 64, N in {64, 128}; bf16 I/O for the scan.
+struct SsdArgs {
+    const void *x, *dt, *Bm, *Cm, *z;
+    const float *A, *Dskip, *dt_bias, *h0;
+    void *out;
+    float *h_final;
+    float *ws;
+    int64_t batch, L, H;
+    int P, N, dt_softplus;
+};
+size_t ssd_workspace_bytes(int64_t batch, int64_t L, int64_t H, int64_t P, int64_t N);
+hipError_t launch_ssd(const SsdArgs &a, hipStream_t stream);
+
+struct SsdStepArgs {
+    float *h_out;
+    const float *h_in;
+    const int32_t *parent;
+    const void *x, *dt, *Bm, *Cm, *z;
+    const float *A, *Dskip, *dt_bias;
+    void *out;
+    int64_t n_out, n_in, H;
+    int P, N, io, dt_softplus;
+};
+hipError_t launch_ssd_step(const SsdStepArgs &a, hipStream_t stream);
 
 struct StepArgs {
     float *h_out;

@@ -528,12 +528,7 @@ scan_carry_fast(const float *__restrict__ A, const float *h0, float *ws_state,
 // launches the carry over the chunk states
 inline void launch_carry(const ScanArgs &a, int N, int nc, float *ws_state, const float *ws_sumdt, hipStream_t stream)
 {
-    const int64_t total = a.batch * a.D * N;
-    const unsigned blocks = (unsigned)((total + kWave - 1) / kWave);
-    if (nc - 1 <= kFastSegs * kFastPer)
-        scan_carry_fast<<<blocks, dim3(kWave, kFastSegs), 0, stream>>>(a.A, a.h0, ws_state, ws_sumdt, a.batch, a.D, N, nc);
-    else
-        scan_carry<<<blocks, dim3(kWave, kCarrySegs), 0, stream>>>(a.A, a.h0, ws_state, ws_sumdt, a.batch, a.D, N, nc);
+    (void)launch_chunk_carry(a.A, a.h0, ws_state, ws_sumdt, a.batch, a.D, N, nc, stream);
 }
 
 // copies h0 (or zeros) to h_final when L == 0
@@ -618,6 +613,24 @@ template <typename T> hipError_t launch_scan_io(const ScanArgs &a, hipStream_t s
 }
 
 }  // namespace
+
+hipError_t launch_chunk_carry(const float *A, const float *h0, float *ws_state, const float *ws_sumdt, int64_t batch,
+                              int64_t D, int N, int n_slots, hipStream_t stream)
+{
+    const int64_t total = batch * D * N;
+    const unsigned blocks = (unsigned)((total + kWave - 1) / kWave);
+    if (n_slots - 1 <= kFastSegs * kFastPer)
+        scan_carry_fast<<<blocks, dim3(kWave, kFastSegs), 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
+    else
+        scan_carry<<<blocks, dim3(kWave, kCarrySegs), 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_state(const float *src, float *dst, int64_t n, hipStream_t stream)
+{
+    copy_state<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(src, dst, n);
+    return hipGetLastError();
+}
 
 // Chunking policy.  A wavefront column covers 64 * CPL channels of one batch row; the chip has
 // 256 CUs x 4 SIMDs.  Sequences are cut only as far as needed to put about two wavefronts on

@@ -31,7 +31,7 @@ def P(i):
 def test_library_exports_every_declared_symbol(b):
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(mamba_[a-z0-9_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(mamba2?_[a-z0-9_]+)\s*\(", text))
     assert declared == set(b.EXPORTS), declared ^ set(b.EXPORTS)
     raw = ctypes.CDLL(b.LIB_PATH)
     for name in declared:

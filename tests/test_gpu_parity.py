@@ -907,3 +907,73 @@ def test_drafter_tree_tokens_match_the_oracle(m):
     for gt, rt in zip(g_tok2, r_tok2):
         assert np.array_equal(to_host(gt), rt)
     assert_close(values(to_host(g_last2)), r_logits2[-1], tol, "second prefix, last logits")
+
+
+# ------------------------------------------------------------------------------------ Mamba-2 style core
+def ssd_case(rng, B, L, H, P, N, io):
+    c = dict(x=rng.standard_normal((B, L, H, P)), z=rng.standard_normal((B, L, H, P)), dt=0.5 * rng.standard_normal((B, L, H)),
+             Bm=rng.standard_normal((B, L, N)), Cm=rng.standard_normal((B, L, N)))
+    c = {k: synth.to_io(v.astype(np.float32), io) for k, v in c.items()}
+    c.update(A=(-rng.uniform(0.05, 1.5, H)).astype(np.float32), Dskip=rng.standard_normal(H).astype(np.float32),
+             dt_bias=rng.uniform(-4.0, -1.0, H).astype(np.float32), h0=rng.standard_normal((B, H, P, N)).astype(np.float32))
+    return c
+
+
+@pytest.mark.parametrize("B,L,H,N", [(1, 64, 2, 64), (2, 200, 3, 128), (1, 1, 1, 128), (1, 63, 2, 64), (1, 65, 2, 128),
+                                     (1, 1000, 24, 128)])
+def test_ssd_scan_against_oracle(m, B, L, H, N):
+    """Chunked scalar-decay scan on the matrix cores against the plain float64 recurrence: outputs and final
+    state, with and without gate / skip / initial state, and in two pieces with the state carried."""
+    from oracle import ssd
+    say(B=B, L=L, H=H, N=N)
+    P = 64
+    rng = np.random.default_rng(B * 7 + L + H + N)
+    c = ssd_case(rng, B, L, H, P, N, synth.BF16)
+    w = {k: W(v) for k, v in c.items()}
+    g = {k: to_dev(v) for k, v in c.items()}
+    tol = TOL[synth.BF16]
+    out, hf = m.mamba2_ssd_fwd(g["x"], g["dt"], g["A"], g["Bm"], g["Cm"], g["Dskip"], g["z"], g["dt_bias"], g["h0"])
+    ro, rh = ssd.ssd_scan(w["x"], w["dt"], w["A"], w["Bm"], w["Cm"], w["Dskip"], w["z"], w["dt_bias"], w["h0"])
+    assert_close(values(to_host(out)), ro, tol, "ssd out")
+    assert_close(to_host(hf), rh, tol, "ssd final state")
+    out2, hf2 = m.mamba2_ssd_fwd(g["x"], g["dt"], g["A"], g["Bm"], g["Cm"])
+    ro2, rh2 = ssd.ssd_scan(w["x"], w["dt"], w["A"], w["Bm"], w["Cm"])
+    assert_close(values(to_host(out2)), ro2, tol, "ssd out, bare")
+    assert_close(to_host(hf2), rh2, tol, "ssd final state, bare")
+    if L > 2:
+        cut = L // 3
+        sl = lambda t, a, b: t[:, a:b].clone()
+        o1, h1 = m.mamba2_ssd_fwd(sl(g["x"], 0, cut), sl(g["dt"], 0, cut), g["A"], sl(g["Bm"], 0, cut), sl(g["Cm"], 0, cut),
+                                  g["Dskip"], sl(g["z"], 0, cut), g["dt_bias"], g["h0"])
+        o2, h2 = m.mamba2_ssd_fwd(sl(g["x"], cut, L), sl(g["dt"], cut, L), g["A"], sl(g["Bm"], cut, L), sl(g["Cm"], cut, L),
+                                  g["Dskip"], sl(g["z"], cut, L), g["dt_bias"], h1)
+        assert_close(values(to_host(torch.cat([o1, o2], 1))), ro, tol, "ssd pieces out")
+        assert_close(to_host(h2), rh, tol, "ssd pieces state")
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("n_out,n_in,H,N", [(5, 3, 2, 64), (12, 6, 24, 128), (1, 1, 1, 128)])
+def test_ssd_state_step_against_oracle(m, io, n_out, n_in, H, N):
+    from oracle import ssd
+    P = 64
+    rng = np.random.default_rng(n_out + n_in + H + N)
+    c = ssd_case(rng, n_out, 1, H, P, N, io)
+    tok = {k: c[k][:, 0] for k in ("x", "z", "dt", "Bm", "Cm")}
+    h_in = rng.standard_normal((n_in, H, P, N)).astype(np.float32)
+    parent = rng.integers(0, n_in, n_out).astype(np.int32)
+    g = {k: to_dev(np.ascontiguousarray(v)) for k, v in tok.items()}
+    w = {k: W(np.ascontiguousarray(v)) for k, v in tok.items()}
+    ho, out = m.mamba2_state_step(to_dev(h_in), g["x"], g["dt"], to_dev(c["A"]), g["Bm"], g["Cm"], to_dev(c["Dskip"]), g["z"],
+                                  to_dev(c["dt_bias"]), parent_idx=to_dev(parent))
+    rh, ro = ssd.ssd_step(h_in, w["x"], w["dt"], W(c["A"]), w["Bm"], w["Cm"], W(c["Dskip"]), w["z"], W(c["dt_bias"]), parent=parent)
+    assert_close(values(to_host(out)), ro, TOL[io], "ssd step out")
+    assert_close(to_host(ho), rh, TOL[synth.F32] if io == synth.F32 else 1e-5, "ssd step state")
+    if n_in == n_out:
+        hbuf = to_dev(h_in)
+        m.mamba2_state_step(hbuf, g["x"], g["dt"], to_dev(c["A"]), g["Bm"], g["Cm"], h_out=hbuf)            # in place
+        rh2, _ = ssd.ssd_step(h_in, w["x"], w["dt"], W(c["A"]), w["Bm"], w["Cm"])
+        assert_close(to_host(hbuf), rh2, 1e-5, "ssd step in place")
+    bad = parent.copy()
+    bad[0] = n_in
+    ho2, out2 = m.mamba2_state_step(to_dev(h_in), g["x"], g["dt"], to_dev(c["A"]), g["Bm"], g["Cm"], parent_idx=to_dev(bad))
+    assert torch.isnan(ho2[0]).all() and torch.isnan(out2[0].float()).all() and not torch.isnan(ho2[1:]).any()
