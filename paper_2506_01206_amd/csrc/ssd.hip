@@ -7,15 +7,18 @@
 //
 // One decay per head and step makes the layer a sum of dense contractions over chunks of 64 steps,
 // so unlike the selective scan this one runs on the matrix cores (v_mfma_f32_32x32x16_bf16).  With
-// s_t the running sum of delta A inside a chunk (s_t <= 0):
-//   pass 1  S[p,n]  = sum_s exp(s_end - s_s) delta_s x_s[p] B_s[n]            local end state of the chunk
-//   carry   H_in[c+1] = exp(s_end) H_in[c] + S_c                              same kernel as the selective scan
-//   pass 2  G[t,s]  = C_t . B_s;  M[t,s] = G[t,s] exp(s_t - s_s) delta_s for s <= t, else 0
-//           y_t[p]  = sum_s M[t,s] x_s[p] + exp(s_t) (C_t . H_in[p,:]) + D x_t[p]
-// A workgroup of four wavefronts owns one (batch row, head, chunk).  Operands whose contraction index
-// is the slow one in memory (x and B over s) are transposed through LDS on the way in; C, B and the
-// incoming state are read from global memory directly in MFMA fragment order (lane l: row l % 32,
-// eight consecutive k starting at 8 (l / 32)).  Products run in bf16 with float32 accumulation; of
+// s_t the running sum of delta A inside a chunk (s_t <= 0) and H the state at the start of the chunk:
+//   outputs G[t,s]  = C_t . B_s;  M[t,s] = G[t,s] exp(s_t - s_s) delta_s for s <= t, else 0
+//           y_t[p]  = sum_s M[t,s] x_s[p] + exp(s_t) (C_t . H[p,:]) + D x_t[p]
+//   state   H      <- exp(s_end) H + S,   S[p,n] = sum_s exp(s_end - s_s) delta_s x_s[p] B_s[n]
+// A workgroup of four wavefronts walks the chunks of one segment of a (batch row, head) in order and
+// keeps H (P x N float32) in MFMA accumulators, so chunk states never travel through memory; the
+// sequence is cut into segments only to fill the chip, and as in the selective scan a first pass
+// gives every segment's end state from zero, the carry kernel stitches them, and a second pass
+// walks the segments again from their true incoming state and writes the outputs.  Tiles enter
+// LDS once per chunk (those whose contraction index is the slow one in memory, x and B over s,
+// transposed) and are read as MFMA fragments (lane l: row l % 32, eight consecutive k from
+// 8 (l / 32)).  Products run in bf16 with float32 accumulation; of
 // every product one factor is an input as it stands (x, B, C) and the other (M, the weighted x of pass 1,
 // the incoming state) is carried as two bf16 terms, the rounded value and the remainder, i.e. with about
 // 16 significant bits: single rounding showed wherever large terms cancel (errors of 2^-9 of the terms,
@@ -32,224 +35,269 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kLc = 64;       // chunk length
 constexpr int kP = 64;        // head dimension
 constexpr int kThreads = 256;
-constexpr int kRowU16 = kLc + 8;   // LDS row of 64 bf16 + 16 bytes of padding
 
-// delta, inclusive running sum of delta * A over the chunk (wavefront 0, one lane per step)
-__device__ __forceinline__ void chunk_decay(const bf16_t *dt, const float *dt_bias, float A_h, int64_t tok0, int64_t L,
-                                            int64_t H, int64_t h, int64_t row0, int softplus, float *delta_out,
-                                            float *cum_out)
+constexpr int kRowS = kLc + 8;    // LDS row of 64 bf16 (steps or channels) + 16 bytes of padding
+
+__device__ __forceinline__ bf16x8 frag(const uint16_t *base, int row_stride, int row, int k0)
 {
-    const int t = threadIdx.x;                                   // < 64
-    const int64_t tok = tok0 + t;
-    float delta = 0.0f;
-    if (tok < L) {
-        const float v = bf16_to_f32(dt[(row0 + tok) * H + h]) + (dt_bias ? dt_bias[h] : 0.0f);
-        delta = softplus ? softplus_f32(v) : v;
-    }
-    float s = delta * A_h;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const float o = __shfl_up(s, off, 64);
-        if (t >= off) s += o;
-    }
-    delta_out[t] = delta;
-    cum_out[t] = s;
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + row * row_stride + k0));
 }
 
-// x tile (64 steps x 64 channels of one head), scaled per step when scale is given, to LDS as [channel][step] bf16;
-// with xt_rem the scaled value is kept as two bf16 terms (rounded value and remainder)
-__device__ __forceinline__ void stage_x_transposed(const bf16_t *x, int64_t row0, int64_t tok0, int64_t L, int64_t H,
-                                                   int64_t h, const float *scale, uint16_t (*xt)[kRowU16],
-                                                   uint16_t (*xt_rem)[kRowU16] = nullptr)
+// Tiles that are written transposed (a lane holds 8 consecutive rows of one column, lanes 8 rows apart)
+// get 16 more bytes of padding after every 8 rows: with a plain row stride of 144 bytes rows 8 apart fall
+// into the same LDS bank and the 2-byte writes of a wavefront serialize 16 ways.
+__device__ __forceinline__ int trow(int row) { return row * kRowS + (row >> 3) * 8; }
+constexpr int tsize(int rows) { return rows * kRowS + (rows / 8) * 8; }
+__device__ __forceinline__ bf16x8 tfrag(const uint16_t *base, int row, int k0)
 {
-    for (int ch = threadIdx.x; ch < kLc * (kP / 8); ch += kThreads) {
-        const int s = ch / (kP / 8), p0 = (ch % (kP / 8)) * 8;
-        const int64_t tok = tok0 + s;
-        uint4 r = make_uint4(0, 0, 0, 0);
-        if (tok < L) r = *reinterpret_cast<const uint4 *>(x + ((row0 + tok) * H + h) * kP + p0);
-        const float w = scale ? scale[s] : 1.0f;                 // times 1: the bits of x unchanged
-        const float v[8] = {bf16_lo(r.x) * w, bf16_hi(r.x) * w, bf16_lo(r.y) * w, bf16_hi(r.y) * w,
-                            bf16_lo(r.z) * w, bf16_hi(r.z) * w, bf16_lo(r.w) * w, bf16_hi(r.w) * w};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t top = f32_to_bf16(v[i]);
-            xt[p0 + i][s] = (uint16_t)top;
-            if (xt_rem) xt_rem[p0 + i][s] = (uint16_t)f32_to_bf16(v[i] - bf16_to_f32(top));   // what the rounding dropped
-        }
-    }
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + trow(row) + k0));
 }
 
-__device__ __forceinline__ bf16x8 lds_frag(const uint16_t (*m)[kRowU16], int row, int k0)
+// value -> rounded bf16 and the bf16 of what the rounding dropped
+__device__ __forceinline__ void split2(float v, uint16_t *top, uint16_t *rem)
 {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&m[row][k0]));
+    const uint32_t t = f32_to_bf16(v);
+    *top = (uint16_t)t;
+    *rem = (uint16_t)f32_to_bf16(v - bf16_to_f32(t));
 }
 
 // ---------------------------------------------------------------------------------------------------
-// pass 1.  grid: (n_chunks, H, batch).  Writes slot chunk + 1 of ws_state ((batch, n_chunks + 1, H * P, N)),
-// entry chunk of ws_sumdt ((batch, n_chunks + 1, H * P), the sum of deltas repeated over the head's channels)
-// and, from the first workgroups, the decay matrix the carry kernel expects (A[h] repeated, (H * P, N)).
-template <int N>
+// A workgroup walks the chunks of one segment of one (batch row, head) in order, the head's state
+// (P x N float32) living in MFMA accumulators: per chunk acc <- exp(s_end) acc + S.
+//   PASS2 = false: from a zero state; leaves the segment's end state in slot seg + 1 of ws_state
+//       ((batch, n_seg + 1, H * P, N)) and the segment's sum of deltas in ws_sumdt; the carry kernel
+//       of the selective scan then turns the slots into the states at the segment starts;
+//   PASS2 = true: from the true incoming state (slot seg), with outputs.
+// The raw tiles of the next chunk (x, B, C, z, dt) are fetched into registers while the current one
+// is multiplied.  grid: (n_seg, H, batch), 4 wavefronts.
+template <int N, bool PASS2, bool HAS_Z>
 __global__ void __launch_bounds__(kThreads)
-ssd_chunk_state(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dt, const float *__restrict__ A,
-                const bf16_t *__restrict__ Bm, const float *__restrict__ dt_bias, float *__restrict__ ws_state,
-                float *__restrict__ ws_sumdt, float *__restrict__ a_rows, int64_t L, int64_t H, int n_chunks, int softplus)
+ssd_segment(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dt, const float *__restrict__ A,
+            const bf16_t *__restrict__ Bm, const bf16_t *__restrict__ Cm, const float *__restrict__ Dskip,
+            const bf16_t *__restrict__ z, const float *__restrict__ dt_bias, float *__restrict__ ws_state,
+            float *__restrict__ ws_sumdt, float *__restrict__ a_rows, bf16_t *__restrict__ out, float *h_final,
+            int64_t L, int64_t H, int chunks_per_seg, int n_seg, int n_chunks, int softplus)
 {
-    __shared__ float delta[kLc], cum[kLc], weight[kLc];
-    __shared__ __attribute__((aligned(16))) uint16_t xt[kP][kRowU16], xt_rem[kP][kRowU16];
-    __shared__ __attribute__((aligned(16))) uint16_t bt[N][kRowU16];
+    constexpr int kRowN = N + 8;                              // LDS row of N bf16 + padding
+    constexpr int NB = N / 32;                                // 16-byte chunks of a B / C tile per thread
+    constexpr int PPW = (2 * (N / 32)) / 4;                   // state tiles (32 x 32) per wavefront: 2 p tiles x N / 32 n tiles
+    __shared__ float delta[kLc], cum[kLc];
+    __shared__ __attribute__((aligned(16))) uint16_t bt[tsize(N)];                       // B as [n][s]
+    __shared__ __attribute__((aligned(16))) uint16_t xw_hi[tsize(kP)], xw_lo[tsize(kP)]; // weight_s x_s[p] as [p][s]
+    __shared__ __attribute__((aligned(16))) uint16_t xt[PASS2 ? tsize(kP) : 8];          // x as [p][s]
+    __shared__ __attribute__((aligned(16))) uint16_t zt[PASS2 ? kLc * kRowS : 8];         // z as [t][p]
+    __shared__ __attribute__((aligned(16))) uint16_t c_rows[PASS2 ? kLc * kRowN : 8];     // C as [t][n]
+    __shared__ __attribute__((aligned(16))) uint16_t b_rows[PASS2 ? kLc * kRowN : 8];     // B as [s][n]
+    __shared__ __attribute__((aligned(16))) uint16_t mm_hi[PASS2 ? kLc * kRowS : 8], mm_lo[PASS2 ? kLc * kRowS : 8];
+    __shared__ __attribute__((aligned(16))) uint16_t h_hi[PASS2 ? kP * kRowN : 8], h_lo[PASS2 ? kP * kRowN : 8];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int chunk = blockIdx.x;
+    const int seg = blockIdx.x;
     const int64_t h = blockIdx.y, b = blockIdx.z;
-    const int64_t row0 = b * L, tok0 = (int64_t)chunk * kLc, D = H * kP;
-    const float A_h = A[h];
-
-    if (wave == 0) chunk_decay(dt, dt_bias, A_h, tok0, L, H, h, row0, softplus, delta, cum);
-    __syncthreads();
-    if (tid < kLc) weight[tid] = exp2_hw((cum[kLc - 1] - cum[tid]) * kLog2e) * delta[tid];
-    if (tid < kP) {
-        // the sum of deltas: the carry kernel forms the chunk's decay as exp(A * sum)
-        float sum = 0.0f;
-        for (int t = 0; t < kLc; ++t) sum += delta[t];
-        ws_sumdt[((int64_t)b * (n_chunks + 1) + chunk) * D + h * kP + tid] = sum;
-    }
-    if (chunk == 0 && b == 0)
-        for (int i = tid; i < kP * N; i += kThreads) a_rows[h * kP * N + i] = A_h;
-    __syncthreads();
-    stage_x_transposed(x, row0, tok0, L, H, h, weight, xt, xt_rem);
-    for (int ch = tid; ch < kLc * (N / 8); ch += kThreads) {     // B tile to LDS as [state][step]
-        const int s = ch / (N / 8), n0 = (ch % (N / 8)) * 8;
-        const int64_t tok = tok0 + s;
-        uint4 r = make_uint4(0, 0, 0, 0);
-        if (tok < L) r = *reinterpret_cast<const uint4 *>(Bm + (row0 + tok) * N + n0);
-        const uint32_t q[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            bt[n0 + 2 * i][s] = (uint16_t)(q[i] & 0xffffu);
-            bt[n0 + 2 * i + 1][s] = (uint16_t)(q[i] >> 16);
-        }
-    }
-    __syncthreads();
-
-    // S[p][n] = sum_s xt[p][s] bt[n][s]: 2 tiles along p, N / 32 along n, dealt to the four wavefronts
+    const int64_t row0 = b * L, D = H * kP;
+    const float A_h = A[h], bias_h = dt_bias ? dt_bias[h] : 0.0f;
     const int r = lane & 31, hk = (lane >> 5) * 8;
-    float *dst = ws_state + (((int64_t)b * (n_chunks + 1) + chunk + 1) * D + h * kP) * N;
-    for (int pair = wave; pair < 2 * (N / 32); pair += 4) {
-        const int pt = pair & 1, ntile = pair >> 1;
-        f32x16 acc;
+    const int tt = wave >> 1, half = wave & 1;                // output block of this wavefront in pass 2
+    const int c_first = seg * chunks_per_seg;
+    const int c_last = min(c_first + chunks_per_seg, n_chunks);
+
+    // raw tiles of one chunk, as this thread's 16-byte pieces
+    struct Raw {
+        uint4 x[2], z[2], bq[NB], cq[NB];
+        float dt;
+    };
+    auto fetch = [&](int chunk) {
+        Raw q;
+        const int64_t tok0 = (int64_t)chunk * kLc;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-#pragma unroll
-        for (int ks = 0; ks < kLc / 16; ++ks) {
-            const bf16x8 bf = lds_frag(bt, ntile * 32 + r, ks * 16 + hk);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(xt, pt * 32 + r, ks * 16 + hk), bf, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(xt_rem, pt * 32 + r, ks * 16 + hk), bf, acc, 0, 0, 0);
+        for (int i = 0; i < 2; ++i) {
+            const int ch = tid + i * kThreads, s = ch >> 3, p0 = (ch & 7) * 8;
+            const bool ok = tok0 + s < L;
+            const int64_t o = ((row0 + tok0 + s) * H + h) * kP + p0;
+            q.x[i] = ok ? *reinterpret_cast<const uint4 *>(x + o) : make_uint4(0, 0, 0, 0);
+            q.z[i] = (PASS2 && HAS_Z && ok) ? *reinterpret_cast<const uint4 *>(z + o) : make_uint4(0, 0, 0, 0);
         }
-        // acc[i] is S[p = 32 pt + 8 (i / 4) + 4 (lane / 32) + i % 4][n = 32 ntile + lane % 32]
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int ch = tid + i * kThreads, s = ch / (N / 8), n0 = (ch % (N / 8)) * 8;
+            const bool ok = tok0 + s < L;
+            const int64_t o = (row0 + tok0 + s) * N + n0;
+            q.bq[i] = ok ? *reinterpret_cast<const uint4 *>(Bm + o) : make_uint4(0, 0, 0, 0);
+            q.cq[i] = (PASS2 && ok) ? *reinterpret_cast<const uint4 *>(Cm + o) : make_uint4(0, 0, 0, 0);
+        }
+        q.dt = 0.0f;
+        if (tid < kLc && tok0 + tid < L) q.dt = bf16_to_f32(dt[(row0 + tok0 + tid) * H + h]);
+        return q;
+    };
+
+    // the head's state: tile j of this wavefront is (p tile pt, n tile nt); acc[j][i] is
+    // H[p = 32 pt + 8 (i / 4) + 4 (lane / 32) + i % 4][n = 32 nt + lane % 32]
+    f32x16 acc[PPW];
+    float *slot_in = ws_state + (((int64_t)b * (n_seg + 1) + seg) * D + h * kP) * N;
+#pragma unroll
+    for (int j = 0; j < PPW; ++j) {
+        const int pair = wave * PPW + j, pt = pair & 1, nt = pair >> 1;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int p = pt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-            dst[(int64_t)p * N + ntile * 32 + r] = acc[i];
+            acc[j][i] = PASS2 ? slot_in[(int64_t)p * N + nt * 32 + r] : 0.0f;
         }
     }
-}
+    float seg_sum = 0.0f;
+    if (!PASS2 && seg == 0 && b == 0)
+        for (int i = tid; i < kP * N; i += kThreads) a_rows[h * kP * N + i] = A_h;   // decay matrix for the carry kernel
 
-// ---------------------------------------------------------------------------------------------------
-// pass 2.  grid: (n_chunks, H, batch).  Wavefront w owns the 32 x 32 block (t tile w / 2, p tile w % 2) of
-// the chunk's outputs and the block (t tile w / 2, s tile w % 2) of G.
-template <int N, bool HAS_Z>
-__global__ void __launch_bounds__(kThreads)
-ssd_chunk_out(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dt, const float *__restrict__ A,
-              const bf16_t *__restrict__ Bm, const bf16_t *__restrict__ Cm, const float *__restrict__ Dskip,
-              const bf16_t *__restrict__ z, const float *__restrict__ dt_bias, const float *__restrict__ ws_state,
-              bf16_t *__restrict__ out, int64_t L, int64_t H, int n_chunks, int softplus)
-{
-    __shared__ float delta[kLc], cum[kLc];
-    __shared__ __attribute__((aligned(16))) uint16_t xt[kP][kRowU16];     // x_s[p] as [p][s]
-    __shared__ __attribute__((aligned(16))) uint16_t mm[kLc][kRowU16], mm_rem[kLc][kRowU16];   // M[t][s], two bf16 terms
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int chunk = blockIdx.x;
-    const int64_t h = blockIdx.y, b = blockIdx.z;
-    const int64_t row0 = b * L, tok0 = (int64_t)chunk * kLc, D = H * kP;
-    const int tt = wave >> 1, half = wave & 1;
-    const int r = lane & 31, hk = (lane >> 5) * 8;
-
-    if (wave == 0) chunk_decay(dt, dt_bias, A[h], tok0, L, H, h, row0, softplus, delta, cum);
-    __syncthreads();
-    stage_x_transposed(x, row0, tok0, L, H, h, nullptr, xt);
-
-    // C fragments of this wavefront's t tile (kept for G and for the incoming-state term); rows past L
-    // repeat the last token and are never stored
-    int64_t tok_c = tok0 + tt * 32 + r;
-    tok_c = tok_c < L ? tok_c : L - 1;
-    const uint4 *crow = reinterpret_cast<const uint4 *>(Cm + (row0 + tok_c) * N);
-    bf16x8 cf[N / 16];
+    Raw raw = fetch(c_first);
+    for (int chunk = c_first; chunk < c_last; ++chunk) {
+        const int64_t tok0 = (int64_t)chunk * kLc;
+        // delta and the inclusive running sum of delta * A over the chunk (wavefront 0, one lane per step)
+        if (wave == 0) {
+            const float dl = (tok0 + lane < L) ? (softplus ? softplus_f32(raw.dt + bias_h) : raw.dt + bias_h) : 0.0f;
+            float sc = dl * A_h;
 #pragma unroll
-    for (int ks = 0; ks < N / 16; ++ks) cf[ks] = __builtin_bit_cast(bf16x8, crow[ks * 2 + (lane >> 5)]);
-
-    // G block (t tile tt, s tile half); above the diagonal it is masked out entirely
-    f32x16 g;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) g[i] = 0.0f;
-    if (half <= tt) {
-        int64_t tok_b = tok0 + half * 32 + r;
-        tok_b = tok_b < L ? tok_b : L - 1;
-        const uint4 *brow = reinterpret_cast<const uint4 *>(Bm + (row0 + tok_b) * N);
-#pragma unroll
-        for (int ks = 0; ks < N / 16; ++ks)
-            g = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[ks], __builtin_bit_cast(bf16x8, brow[ks * 2 + (lane >> 5)]), g, 0, 0, 0);
-    }
-    // M = G * exp(s_t - s_s) * delta_s for s <= t (steps past L have delta = 0 and x = 0, so they add nothing)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int t = tt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3), s = half * 32 + r;
-        const float v = (s <= t) ? g[i] * exp2_hw((cum[t] - cum[s]) * kLog2e) * delta[s] : 0.0f;
-        const uint32_t top = f32_to_bf16(v);
-        mm[t][s] = (uint16_t)top;
-        mm_rem[t][s] = (uint16_t)f32_to_bf16(v - bf16_to_f32(top));
-    }
-    __syncthreads();
-
-    // output block (t tile tt, p tile half)
-    f32x16 inter, intra;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) inter[i] = intra[i] = 0.0f;
-    {
-        // incoming state of the chunk, rows p of this p tile, as two bf16 terms (value and rounding
-        // remainder): this is the one sum where single rounding shows, a long contraction with a state
-        // that can be large and cancel
-        const float *hrow = ws_state + (((int64_t)b * (n_chunks + 1) + chunk) * D + h * kP + half * 32 + r) * N;
-#pragma unroll
-        for (int ks = 0; ks < N / 16; ++ks) {
-            const float4 lo4 = *reinterpret_cast<const float4 *>(hrow + ks * 16 + hk);
-            const float4 hi4 = *reinterpret_cast<const float4 *>(hrow + ks * 16 + hk + 4);
-            const float v[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
-            uint32_t top[4], rem[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                top[i] = f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
-                rem[i] = f32x2_to_bf16x2(v[2 * i] - bf16_lo(top[i]), v[2 * i + 1] - bf16_hi(top[i]));
+            for (int off = 1; off < 64; off <<= 1) {
+                const float o = __shfl_up(sc, off, 64);
+                if (lane >= off) sc += o;
             }
-            inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[ks], __builtin_bit_cast(bf16x8, make_uint4(top[0], top[1], top[2], top[3])), inter, 0, 0, 0);
-            inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[ks], __builtin_bit_cast(bf16x8, make_uint4(rem[0], rem[1], rem[2], rem[3])), inter, 0, 0, 0);
+            delta[lane] = dl;
+            cum[lane] = sc;
+            seg_sum += dl;
+        }
+        // raw B (and C, x, z in pass 2) into LDS
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int ch = tid + i * kThreads, s = ch / (N / 8), n0 = (ch % (N / 8)) * 8;
+            const uint32_t w[4] = {raw.bq[i].x, raw.bq[i].y, raw.bq[i].z, raw.bq[i].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                bt[trow(n0 + 2 * k) + s] = (uint16_t)(w[k] & 0xffffu);
+                bt[trow(n0 + 2 * k + 1) + s] = (uint16_t)(w[k] >> 16);
+            }
+            if constexpr (PASS2) {
+                *reinterpret_cast<uint4 *>(&b_rows[s * kRowN + n0]) = raw.bq[i];
+                *reinterpret_cast<uint4 *>(&c_rows[s * kRowN + n0]) = raw.cq[i];
+            }
+        }
+        if constexpr (PASS2) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int ch = tid + i * kThreads, s = ch >> 3, p0 = (ch & 7) * 8;
+                const uint32_t w[4] = {raw.x[i].x, raw.x[i].y, raw.x[i].z, raw.x[i].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    xt[trow(p0 + 2 * k) + s] = (uint16_t)(w[k] & 0xffffu);
+                    xt[trow(p0 + 2 * k + 1) + s] = (uint16_t)(w[k] >> 16);
+                }
+                *reinterpret_cast<uint4 *>(&zt[s * kRowS + p0]) = raw.z[i];
+            }
+            // the state at the start of the chunk, as two bf16 terms, for the incoming-state product
+#pragma unroll
+            for (int j = 0; j < PPW; ++j) {
+                const int pair = wave * PPW + j, pt = pair & 1, nt = pair >> 1;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int p = pt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                    split2(acc[j][i], &h_hi[p * kRowN + nt * 32 + r], &h_lo[p * kRowN + nt * 32 + r]);
+                }
+            }
+        }
+        __syncthreads();                                          // delta, cum and the raw tiles are in LDS
+        // weighted x for the state update, two bf16 terms: weight_s = exp(s_end - s_s) delta_s
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int ch = tid + i * kThreads, s = ch >> 3, p0 = (ch & 7) * 8;
+            const float w = exp2_hw((cum[kLc - 1] - cum[s]) * kLog2e) * delta[s];
+            const uint4 q = raw.x[i];
+            const float v[8] = {bf16_lo(q.x) * w, bf16_hi(q.x) * w, bf16_lo(q.y) * w, bf16_hi(q.y) * w,
+                                bf16_lo(q.z) * w, bf16_hi(q.z) * w, bf16_lo(q.w) * w, bf16_hi(q.w) * w};
+#pragma unroll
+            for (int k = 0; k < 8; ++k) split2(v[k], &xw_hi[trow(p0 + k) + s], &xw_lo[trow(p0 + k) + s]);
+        }
+        if (chunk + 1 < c_last) raw = fetch(chunk + 1);           // in flight during the products below
+
+        f32x16 gacc;
+        if constexpr (PASS2) {
+            // G block (t tile tt, s tile half); above the diagonal it is masked out entirely
+#pragma unroll
+            for (int i = 0; i < 16; ++i) gacc[i] = 0.0f;
+            if (half <= tt) {
+#pragma unroll
+                for (int ks = 0; ks < N / 16; ++ks)
+                    gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk),
+                                                                   frag(b_rows, kRowN, half * 32 + r, ks * 16 + hk), gacc, 0, 0, 0);
+            }
+            // M = G * exp(s_t - s_s) * delta_s for s <= t (steps past L have delta = 0)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int t = tt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3), s = half * 32 + r;
+                const float v = (s <= t) ? gacc[i] * exp2_hw((cum[t] - cum[s]) * kLog2e) * delta[s] : 0.0f;
+                split2(v, &mm_hi[t * kRowS + s], &mm_lo[t * kRowS + s]);
+            }
+        }
+        __syncthreads();                                          // M and the weighted x are in LDS
+
+        if constexpr (PASS2) {
+            f32x16 inter, intra;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) inter[i] = intra[i] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < N / 16; ++ks) {
+                const bf16x8 cf = frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk);
+                inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf, frag(h_hi, kRowN, half * 32 + r, ks * 16 + hk), inter, 0, 0, 0);
+                inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf, frag(h_lo, kRowN, half * 32 + r, ks * 16 + hk), inter, 0, 0, 0);
+            }
+#pragma unroll
+            for (int ks = 0; ks < kLc / 16; ++ks)
+                if (ks < 2 * (tt + 1)) {                          // M is zero right of the diagonal block
+                    const bf16x8 xf = tfrag(xt, half * 32 + r, ks * 16 + hk);
+                    intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(mm_hi, kRowS, tt * 32 + r, ks * 16 + hk), xf, intra, 0, 0, 0);
+                    intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(mm_lo, kRowS, tt * 32 + r, ks * 16 + hk), xf, intra, 0, 0, 0);
+                }
+            const float dsk = Dskip ? Dskip[h] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int t = tt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3), p = half * 32 + r;
+                if (tok0 + t >= L) continue;
+                float y = intra[i] + exp2_hw(cum[t] * kLog2e) * inter[i] + dsk * bf16_to_f32(xt[trow(p) + t]);
+                if constexpr (HAS_Z) y *= silu_f32(bf16_to_f32(zt[t * kRowS + p]));
+                out[((row0 + tok0 + t) * H + h) * kP + p] = (bf16_t)f32_to_bf16(y);
+            }
+        }
+        // state: acc <- exp(s_end) acc + sum_s xw[p][s] bt[n][s]
+        const float dec = exp2_hw(cum[kLc - 1] * kLog2e);
+#pragma unroll
+        for (int j = 0; j < PPW; ++j) {
+            const int pair = wave * PPW + j, pt = pair & 1, nt = pair >> 1;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[j][i] *= dec;
+#pragma unroll
+            for (int ks = 0; ks < kLc / 16; ++ks) {
+                const bf16x8 bf = tfrag(bt, nt * 32 + r, ks * 16 + hk);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tfrag(xw_hi, pt * 32 + r, ks * 16 + hk), bf, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tfrag(xw_lo, pt * 32 + r, ks * 16 + hk), bf, acc[j], 0, 0, 0);
+            }
+        }
+        __syncthreads();                                          // the chunk's LDS tiles are free again
+    }
+
+    // end of the segment: pass 1 leaves the local end state and the sum of deltas, pass 2 the final state
+    float *dst = nullptr;
+    if (!PASS2) dst = ws_state + (((int64_t)b * (n_seg + 1) + seg + 1) * D + h * kP) * N;
+    else if (h_final && seg == n_seg - 1) dst = h_final + (b * D + h * kP) * N;
+    if (dst) {
+#pragma unroll
+        for (int j = 0; j < PPW; ++j) {
+            const int pair = wave * PPW + j, pt = pair & 1, nt = pair >> 1;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int p = pt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                dst[(int64_t)p * N + nt * 32 + r] = acc[j][i];
+            }
         }
     }
+    if (!PASS2 && wave == 0) {
 #pragma unroll
-    for (int ks = 0; ks < kLc / 16; ++ks)
-        if (ks < 2 * (tt + 1)) {                                 // M is zero right of the diagonal block
-            const bf16x8 xf = lds_frag(xt, half * 32 + r, ks * 16 + hk);
-            intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(mm, tt * 32 + r, ks * 16 + hk), xf, intra, 0, 0, 0);
-            intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(mm_rem, tt * 32 + r, ks * 16 + hk), xf, intra, 0, 0, 0);
-        }
-    const float dsk = Dskip ? Dskip[h] : 0.0f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int t = tt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-        const int64_t tok = tok0 + t;
-        if (tok >= L) continue;
-        const int64_t o = ((row0 + tok) * H + h) * kP + half * 32 + r;
-        float y = intra[i] + exp2_hw(cum[t] * kLog2e) * inter[i] + dsk * bf16_to_f32(x[o]);
-        if constexpr (HAS_Z) y *= silu_f32(bf16_to_f32(z[o]));
-        out[o] = (bf16_t)f32_to_bf16(y);
+        for (int off = 32; off > 0; off >>= 1) seg_sum += __shfl_xor(seg_sum, off, 64);
+        ws_sumdt[((int64_t)b * (n_seg + 1) + seg) * D + h * kP + lane] = seg_sum;   // kP == 64 lanes
     }
 }
 
@@ -311,48 +359,64 @@ ssd_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ par
 
 int64_t chunks_of(int64_t L) { return (L + kLc - 1) / kLc; }
 
+// Segments: about one workgroup per CU (a workgroup holds most of a CU's LDS), never more than chunks.
+void ssd_plan(int64_t batch, int64_t L, int64_t H, int *chunks_per_seg, int *n_seg)
+{
+    const int64_t nc = chunks_of(L);
+    int64_t want = 256 / (batch * H > 0 ? batch * H : 1);
+    if (want < 1) want = 1;
+    if (want > nc) want = nc;
+    const int64_t cps = (nc + want - 1) / want;
+    *chunks_per_seg = (int)cps;
+    *n_seg = (int)((nc + cps - 1) / cps);
+}
+
 }  // namespace
 
 size_t ssd_workspace_bytes(int64_t batch, int64_t L, int64_t H, int64_t P, int64_t N)
 {
-    const int64_t slots = chunks_of(L) + 1, D = H * P;
+    int cps, n_seg;
+    ssd_plan(batch, L, H, &cps, &n_seg);
+    const int64_t slots = n_seg + 1, D = H * P;
     return (size_t)(batch * slots * D * (N + 1) + D * N) * sizeof(float);
 }
 
 hipError_t launch_ssd(const SsdArgs &a, hipStream_t stream)
 {
+    int cps, n_seg;
+    ssd_plan(a.batch, a.L, a.H, &cps, &n_seg);
     const int nc = (int)chunks_of(a.L);
     const int64_t D = a.H * a.P;
     float *ws_state = a.ws;
-    float *ws_sumdt = ws_state + (size_t)a.batch * (nc + 1) * D * a.N;
-    float *a_rows = ws_sumdt + (size_t)a.batch * (nc + 1) * D;
+    float *ws_sumdt = ws_state + (size_t)a.batch * (n_seg + 1) * D * a.N;
+    float *a_rows = ws_sumdt + (size_t)a.batch * (n_seg + 1) * D;
     const bf16_t *x = static_cast<const bf16_t *>(a.x), *dt = static_cast<const bf16_t *>(a.dt);
     const bf16_t *Bm = static_cast<const bf16_t *>(a.Bm), *Cm = static_cast<const bf16_t *>(a.Cm);
     const bf16_t *z = static_cast<const bf16_t *>(a.z);
     bf16_t *out = static_cast<bf16_t *>(a.out);
-    dim3 grid((unsigned)nc, (unsigned)a.H, (unsigned)a.batch);
-    if (a.N == 64)
-        ssd_chunk_state<64><<<grid, kThreads, 0, stream>>>(x, dt, a.A, Bm, a.dt_bias, ws_state, ws_sumdt, a_rows, a.L, a.H, nc, a.dt_softplus);
-    else
-        ssd_chunk_state<128><<<grid, kThreads, 0, stream>>>(x, dt, a.A, Bm, a.dt_bias, ws_state, ws_sumdt, a_rows, a.L, a.H, nc, a.dt_softplus);
-    if (hipError_t e = launch_chunk_carry(a_rows, a.h0, ws_state, ws_sumdt, a.batch, D, a.N, nc + 1, stream)) return e;
-#define MAMBA_SSD_OUT(NN, HZ)                                                                                    \
-    ssd_chunk_out<NN, HZ><<<grid, kThreads, 0, stream>>>(x, dt, a.A, Bm, Cm, a.Dskip, z, a.dt_bias, ws_state, out, \
-                                                        a.L, a.H, nc, a.dt_softplus)
-    if (a.N == 64) {
-        if (z) MAMBA_SSD_OUT(64, true);
-        else MAMBA_SSD_OUT(64, false);
+    dim3 grid((unsigned)n_seg, (unsigned)a.H, (unsigned)a.batch);
+#define MAMBA_SSD(NN, P2, HZ)                                                                                     \
+    ssd_segment<NN, P2, HZ><<<grid, kThreads, 0, stream>>>(x, dt, a.A, Bm, Cm, a.Dskip, z, a.dt_bias, ws_state,    \
+                                                          ws_sumdt, a_rows, out, a.h_final, a.L, a.H, cps, n_seg, \
+                                                          nc, a.dt_softplus)
+    if (n_seg > 1) {
+        if (a.N == 64) MAMBA_SSD(64, false, false);
+        else MAMBA_SSD(128, false, false);
+        if (hipError_t e = launch_chunk_carry(a_rows, a.h0, ws_state, ws_sumdt, a.batch, D, a.N, n_seg + 1, stream)) return e;
     } else {
-        if (z) MAMBA_SSD_OUT(128, true);
-        else MAMBA_SSD_OUT(128, false);
-    }
-#undef MAMBA_SSD_OUT
-    if (a.h_final) {
-        // the carry left the state after the last chunk in the last slot of every batch row
+        // a single segment starts from h0 itself: slot 0 <- h0 (or zeros)
         for (int64_t b = 0; b < a.batch; ++b)
-            if (hipError_t e = launch_copy_state(ws_state + ((size_t)b * (nc + 1) + nc) * D * a.N, a.h_final + b * D * a.N, D * a.N, stream))
+            if (hipError_t e = launch_copy_state(a.h0 ? a.h0 + b * D * a.N : nullptr, ws_state + (size_t)b * 2 * D * a.N, D * a.N, stream))
                 return e;
     }
+    if (a.N == 64) {
+        if (z) MAMBA_SSD(64, true, true);
+        else MAMBA_SSD(64, true, false);
+    } else {
+        if (z) MAMBA_SSD(128, true, true);
+        else MAMBA_SSD(128, true, false);
+    }
+#undef MAMBA_SSD
     return hipGetLastError();
 }
 
