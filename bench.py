@@ -71,6 +71,7 @@ def main():
     ap.add_argument("--all-configs", action="store_true",
                     help="also time conv1d, scan, fork and step on every synthetic config (cfg0..cfg4), warm and "
                          "cold, and (unless --no-cpu-baseline) the oracle on each; adds a few minutes")
+    ap.add_argument("--no-mamba2", action="store_true", help="skip the scalar-decay (Mamba-2 style) core timing")
     ap.add_argument("--no-drafter", action="store_true",
                     help="skip the whole-drafter timing (Mamba-130M shapes, prefix encoding and draft rounds)")
     ap.add_argument("--no-tree-draft", action="store_true",
@@ -473,6 +474,73 @@ def main():
             per_config[name + "_decode"] = ent
             del hin, hout, cin, cout
 
+    # the scalar-decay (Mamba-2 style) core at Mamba2-130M-like shapes: 24 heads x 64 channels, 128 states
+    ssd_detail = {}
+    if not args.no_mamba2:
+        sH, sP, sN = 24, 64, 128
+        gen2 = torch.Generator(device=dev)
+        gen2.manual_seed(222)
+        rn2 = lambda *shape: torch.randn(*shape, device=dev, generator=gen2)
+        sA = -(0.05 + 1.45 * torch.rand(sH, device=dev, generator=gen2))
+        sD, sb_ = torch.ones(sH, device=dev), torch.full((sH,), -2.5, device=dev)
+        ssd_detail = {"workload": "%d heads x %d channels, %d states, one group, bf16 I/O" % (sH, sP, sN)}
+        for sL in (2048, 32768):
+            sx, sz = rn2(1, sL, sH, sP).to(torch.bfloat16), rn2(1, sL, sH, sP).to(torch.bfloat16)
+            sdt = (0.5 * rn2(1, sL, sH)).to(torch.bfloat16)
+            sB, sC = rn2(1, sL, sN).to(torch.bfloat16), rn2(1, sL, sN).to(torch.bfloat16)
+            so, sh = torch.empty_like(sx), torch.empty((1, sH, sP, sN), device=dev)
+            sws = torch.empty(m.mamba2_ssd_workspace_bytes(1, sL, sH, sP, sN), dtype=torch.uint8, device=dev)
+            run_ssd = lambda: m.mamba2_ssd_fwd(sx, sdt, sA, sB, sC, sD, sz, sb_, None, out=so, h_final=sh, workspace=sws)
+            for _ in range(3):
+                run_ssd()
+            q0, q1 = ev(), ev()
+            q0.record()
+            for _ in range(10):
+                run_ssd()
+            q1.record()
+            torch.cuda.synchronize()
+            s_ms = q0.elapsed_time(q1) / 10
+            s_bytes = sL * (3 * sH * sP + 2 * sN + sH) * 2
+            ssd_detail["scan_L%d" % sL] = {"ms": round(s_ms, 4), "tokens_per_s": round(sL / (s_ms * 1e-3), 1),
+                                           "algorithmic_GBps": round(s_bytes / (s_ms * 1e-3) / 1e9, 1)}
+            del sx, sz, sdt, sB, sC, so, sws
+        snb = 64
+        Rs = 12
+        shin = [rn2(snb, sH, sP, sN) for _ in range(Rs)]
+        shout = [torch.empty_like(shin[0]) for _ in range(Rs)]
+        tx, tz = rn2(snb, sH, sP).to(torch.bfloat16), rn2(snb, sH, sP).to(torch.bfloat16)
+        tdt, tB, tC = rn2(snb, sH).to(torch.bfloat16), rn2(snb, sN).to(torch.bfloat16), rn2(snb, sN).to(torch.bfloat16)
+        tpar = torch.randint(0, snb, (snb,), device=dev, dtype=torch.int32, generator=gen2)
+        tout = torch.empty_like(tx)
+
+        def ssd_round():
+            for i in range(Rs):
+                m.mamba2_state_step(shin[i], tx, tdt, sA, tB, tC, sD, tz, sb_, parent_idx=tpar, h_out=shout[i], out=tout)
+        ssd_round()
+        torch.cuda.synchronize()
+        sg = torch.cuda.CUDAGraph()
+        side3 = torch.cuda.Stream()
+        side3.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side3):
+            with torch.cuda.graph(sg, stream=side3):
+                ssd_round()
+        torch.cuda.current_stream().wait_stream(side3)
+        sg.replay()
+        q0, q1 = ev(), ev()
+        q0.record()
+        for _ in range(5):
+            sg.replay()
+        q1.record()
+        torch.cuda.synchronize()
+        s_us = q0.elapsed_time(q1) * 1e3 / (5 * Rs)
+        st_bytes = snb * (2 * sH * sP * sN * 4 + (3 * sH * sP + 2 * sN + sH) * 2)
+        ssd_detail["state_step_%d_branches" % snb] = {
+            "us_per_launch": round(s_us, 3), "algorithmic_bytes_per_launch": st_bytes,
+            "GBps": round(st_bytes / s_us / 1e3, 1), "frac_of_hbm_peak": round(st_bytes / s_us / 1e3 / HBM_PEAK_GBS, 4),
+            "frac_of_copy_kernel": round(st_bytes / s_us / 1e3 / copy_gbs, 4),
+            "timing": "per launch in a replayed HIP graph over %d rotating state sets (%.0f MB)" % (Rs, Rs * 2 * snb * sH * sP * sN * 4 / 1e6)}
+        del shin, shout
+
     tokens = B * L
     sb = scan_bytes(B, L, D, N, e)
     achieved = sb / (scan_ms * 1e-3) / 1e9
@@ -501,7 +569,7 @@ def main():
         "decode_launches": nsteps * (1 + 2 * nl), "decode_mode": "eager" if args.eager_decode else "hip_graph",
         "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide,
         "tree_draft_round": tree_detail, "whole_block": block_detail,
-        "whole_drafter": drafter_detail, "per_config": per_config,
+        "whole_drafter": drafter_detail, "mamba2_core": ssd_detail, "per_config": per_config,
     }
 
     result = {

@@ -250,3 +250,41 @@ def test_tree_plan_validation(b):
     assert b.lib.mamba_tree_parents(P(0), ctypes.byref(plan), other, None) == S["BAD_SHAPE"]
     assert b.lib.mamba_tree_parents(None, ctypes.byref(plan), other, None) == S["NULL_POINTER"]
     assert b.lib.mamba_tree_parents(P(0) + 4, ctypes.byref(plan), other, None) == S["MISALIGNED"]
+
+
+def ssd(b, x=P(0), dt=P(1), A=P(2), Bm=P(3), Cm=P(4), Dskip=P(5), z=P(6), bias=P(7), h0=P(8), out=P(9), hf=P(10),
+        ws=P(11), ws_bytes=1 << 39, batch=1, L=4096, H=24, Pd=64, N=128, sp=1, io=1):
+    return b.lib.mamba2_ssd_fwd(x, dt, A, Bm, Cm, Dskip, z, bias, h0, out, hf, ws, ws_bytes, batch, L, H, Pd, N, sp, io, None)
+
+
+def test_ssd_validation(b):
+    """Every rejection of the scalar-decay scan and step happens on the host, before any launch."""
+    S = b.STATUS
+    assert ssd(b, x=None) == S["NULL_POINTER"] and ssd(b, Cm=None) == S["NULL_POINTER"] and ssd(b, out=None) == S["NULL_POINTER"]
+    assert ssd(b, L=-1) == S["BAD_SHAPE"] and ssd(b, H=-3) == S["BAD_SHAPE"]
+    assert ssd(b, L=1 << 40, H=1 << 30) == S["BAD_SHAPE"]                      # size overflow
+    assert ssd(b, Pd=32) == S["UNSUPPORTED"] and ssd(b, N=16) == S["UNSUPPORTED"] and ssd(b, N=256) == S["UNSUPPORTED"]
+    assert ssd(b, io=0) == S["UNSUPPORTED"]                                    # float32 I/O: the products run in bf16
+    assert ssd(b, batch=70000, L=8, H=1) == S["UNSUPPORTED"]
+    assert ssd(b, x=P(0) + 2) == S["MISALIGNED"] and ssd(b, ws=P(11) + 8) == S["MISALIGNED"]
+    assert ssd(b, ws=None) == S["WORKSPACE"] and ssd(b, ws_bytes=1000) == S["WORKSPACE"]
+    assert ssd(b, out=P(0)) == S["ALIAS"] and ssd(b, out=P(6)) == S["ALIAS"] and ssd(b, ws=P(9)) == S["ALIAS"]
+    assert ssd(b, batch=0) == 0 and ssd(b, H=0) == 0
+    need = b.lib.mamba2_ssd_workspace_bytes(1, 4096, 24, 64, 128)
+    assert need > 0 and ssd(b, ws_bytes=need - 1) == S["WORKSPACE"]
+    assert b.lib.mamba2_ssd_workspace_bytes(1, 4096, 24, 32, 128) == 0 and b.lib.mamba2_ssd_workspace_bytes(0, 64, 1, 64, 64) == 0
+    # the workspace holds one state per segment, not per chunk: it stays small for long sequences
+    assert b.lib.mamba2_ssd_workspace_bytes(1, 1 << 20, 24, 64, 128) < 64 << 20
+
+    def step(h_out=P(0), h_in=P(1), par=P(2), x=P(3), dt=P(4), A=P(5), Bm=P(6), Cm=P(7), Dskip=P(8), z=P(9), bias=P(10),
+             out=P(11), n_out=8, n_in=4, H=24, Pd=64, N=128, sp=1, io=1):
+        return b.lib.mamba2_state_step(h_out, h_in, par, x, dt, A, Bm, Cm, Dskip, z, bias, out, n_out, n_in, H, Pd, N, sp, io, None)
+    assert step(h_in=None) == S["NULL_POINTER"] and step(out=None) == S["NULL_POINTER"]
+    assert step(n_out=-1) == S["BAD_SHAPE"] and step(par=None) == S["BAD_SHAPE"]              # no parents: n_in must equal n_out
+    assert step(n_in=0) == S["BAD_SHAPE"]
+    assert step(N=32) == S["UNSUPPORTED"] and step(Pd=128) == S["UNSUPPORTED"] and step(io=5) == S["UNSUPPORTED"]
+    assert step(n_out=70000) == S["UNSUPPORTED"]
+    assert step(par=P(2) + 4) == S["MISALIGNED"]
+    assert step(h_out=P(1)) == S["ALIAS"]                                                     # in place only without parents
+    assert step(out=P(3)) == S["ALIAS"]
+    assert step(n_out=0) == 0
