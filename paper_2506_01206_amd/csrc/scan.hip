@@ -525,6 +525,37 @@ scan_carry_fast(const float *__restrict__ A, const float *h0, float *ws_state,
     }
 }
 
+// Few slots (the segment states of the scalar-decay scan, or a short selective scan): one lane per (b, d, n)
+// walks them all; every load is issued before the first is used.  grid: ceil(batch * D * N / 256)
+constexpr int kSerialSlots = 32;
+
+__global__ void __launch_bounds__(256)
+scan_carry_serial(const float *__restrict__ A, const float *h0, float *ws_state, const float *__restrict__ ws_sumdt,
+                  int64_t batch, int64_t D, int N, int n_chunks)
+{
+    const int64_t DN = D * N;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= batch * DN) return;
+    const int64_t b = idx / DN, dn = idx - b * DN, d = dn / N;
+    const float a2 = A[dn] * kLog2e;
+    float *st = ws_state + b * n_chunks * DN + dn;
+    const float *sd = ws_sumdt + b * n_chunks * D + d;
+    float loc[kSerialSlots], sm[kSerialSlots];
+#pragma unroll
+    for (int c = 1; c < kSerialSlots; ++c) {
+        const bool in = c < n_chunks;
+        loc[c] = in ? st[(int64_t)c * DN] : 0.0f;
+        sm[c] = in ? sd[(int64_t)(c - 1) * D] : 0.0f;
+    }
+    float h = h0 ? h0[idx] : 0.0f;
+    st[0] = h;
+#pragma unroll
+    for (int c = 1; c < kSerialSlots; ++c) {
+        h = fmaf(exp2_hw(a2 * sm[c]), h, loc[c]);
+        if (c < n_chunks) st[(int64_t)c * DN] = h;
+    }
+}
+
 // launches the carry over the chunk states
 inline void launch_carry(const ScanArgs &a, int N, int nc, float *ws_state, const float *ws_sumdt, hipStream_t stream)
 {
@@ -619,7 +650,9 @@ hipError_t launch_chunk_carry(const float *A, const float *h0, float *ws_state, 
 {
     const int64_t total = batch * D * N;
     const unsigned blocks = (unsigned)((total + kWave - 1) / kWave);
-    if (n_slots - 1 <= kFastSegs * kFastPer)
+    if (n_slots <= kSerialSlots)
+        scan_carry_serial<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
+    else if (n_slots - 1 <= kFastSegs * kFastPer)
         scan_carry_fast<<<blocks, dim3(kWave, kFastSegs), 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
     else
         scan_carry<<<blocks, dim3(kWave, kCarrySegs), 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
