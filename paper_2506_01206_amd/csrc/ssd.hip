@@ -53,248 +53,350 @@ __device__ __forceinline__ bf16x8 tfrag(const uint16_t *base, int row, int k0)
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + trow(row) + k0));
 }
 
-// value -> rounded bf16 and the bf16 of what the rounding dropped
-__device__ __forceinline__ void split2(float v, uint16_t *top, uint16_t *rem)
+// Workgroup barrier that orders LDS traffic only: the tiles exchanged between wavefronts live in LDS, and a
+// barrier that also ordered global memory would wait for every output store and every prefetch in flight.
+__device__ __forceinline__ void lds_barrier()
 {
-    const uint32_t t = f32_to_bf16(v);
-    *top = (uint16_t)t;
-    *rem = (uint16_t)f32_to_bf16(v - bf16_to_f32(t));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// four values -> their bf16 roundings and the bf16 of what the roundings dropped, packed in order
+__device__ __forceinline__ void split4(const float *v, uint2 *top, uint2 *rem)
+{
+    const uint32_t t01 = f32x2_to_bf16x2(v[0], v[1]), t23 = f32x2_to_bf16x2(v[2], v[3]);
+    *top = make_uint2(t01, t23);
+    *rem = make_uint2(f32x2_to_bf16x2(v[0] - bf16_lo(t01), v[1] - bf16_hi(t01)),
+                      f32x2_to_bf16x2(v[2] - bf16_lo(t23), v[3] - bf16_hi(t23)));
+}
+
+// element k (0 .. 7) of a 16-byte piece of bf16, as float / the 16-bit halves of two pieces side by side
+__device__ __forceinline__ uint32_t piece_word(const uint4 &q, int k2) { return k2 == 0 ? q.x : k2 == 1 ? q.y : k2 == 2 ? q.z : q.w; }
+__device__ __forceinline__ float piece_el(const uint4 &q, int k)
+{
+    const uint32_t w = piece_word(q, k >> 1);
+    return (k & 1) ? bf16_hi(w) : bf16_lo(w);
+}
+__device__ __forceinline__ uint32_t pair_el(const uint4 &a, const uint4 &b, int k)   // element k of a (low half), of b (high half)
+{
+    const uint32_t wa = piece_word(a, k >> 1), wb = piece_word(b, k >> 1);
+    return (k & 1) ? ((wa >> 16) | (wb & 0xffff0000u)) : ((wa & 0xffffu) | (wb << 16));
 }
 
 // ---------------------------------------------------------------------------------------------------
 // A workgroup walks the chunks of one segment of one (batch row, head) in order, the head's state
-// (P x N float32) living in MFMA accumulators: per chunk acc <- exp(s_end) acc + S.
+// living transposed (N x P float32) in MFMA accumulators: per chunk acc <- exp(s_end) acc + S.
 //   PASS2 = false: from a zero state; leaves the segment's end state in slot seg + 1 of ws_state
 //       ((batch, n_seg + 1, H * P, N)) and the segment's sum of deltas in ws_sumdt; the carry kernel
 //       of the selective scan then turns the slots into the states at the segment starts;
 //   PASS2 = true: from the true incoming state (slot seg), with outputs.
-// The raw tiles of the next chunk (x, B, C, z, dt) are fetched into registers while the current one
-// is multiplied.  grid: (n_seg, H, batch), 4 wavefronts.
+// Two roles.  The four "state" wavefronts hold the accumulators and do all the fetching: per chunk they
+// park B transposed and the weighted x (two bf16 terms) in LDS and multiply them into the state; in pass 2
+// they also lay out B, C and z row-major, x transposed and the state at the chunk start (two bf16 terms)
+// for the output products.  Pass 2 adds four "output" wavefronts, one 32 x 32 block of the chunk's 64 x 64
+// outputs each, computed transposed so that a lane owns one step and four adjacent channels at a time:
+// they form G^T and M (D goes onto M's diagonal, which adds D x_t to the outputs), and after the barrier
+// multiply M with x and C with the incoming state, gate and write out.  With one wavefront of each role
+// on every SIMD the conversions of one overlap the products of the other.  Everything a thread moves into LDS transposed is a run of 2 or 4
+// steps of one row (its pieces are adjacent steps), so the writes are 4 or 8 bytes wide.  The raw tiles
+// of the next chunk are fetched (unconditionally: steps past L re-read step L - 1 and are zeroed at use)
+// as soon as the registers of the current one have gone to LDS; delta and its running sum are formed one
+// chunk ahead into the other half of a double buffer.
+// grid: (n_seg, H, batch); 256 threads in pass 1, 512 in pass 2.
 template <int N, bool PASS2, bool HAS_Z>
-__global__ void __launch_bounds__(kThreads)
-ssd_segment(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dt, const float *__restrict__ A,
-            const bf16_t *__restrict__ Bm, const bf16_t *__restrict__ Cm, const float *__restrict__ Dskip,
-            const bf16_t *__restrict__ z, const float *__restrict__ dt_bias, float *__restrict__ ws_state,
-            float *__restrict__ ws_sumdt, float *__restrict__ a_rows, bf16_t *__restrict__ out, float *h_final,
-            int64_t L, int64_t H, int chunks_per_seg, int n_seg, int n_chunks, int softplus)
+__global__ void __launch_bounds__(PASS2 ? 2 * kThreads : kThreads) __attribute__((amdgpu_waves_per_eu(2)))
+ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, const bf16_t *Bm, const bf16_t *Cm,
+            const float *__restrict__ Dskip, const bf16_t *z, const float *__restrict__ dt_bias, float *ws_state,
+            float *ws_sumdt, float *a_rows, bf16_t *out, float *h_final, int64_t L, int64_t H, int chunks_per_seg,
+            int n_seg, int n_chunks, int softplus)
 {
+    // (x, dt, B, C, z are deliberately not declared restrict: as possibly aliased by the stores to out they
+    // stay where they are written, a chunk ahead of their use, instead of being sunk to it by the compiler)
     constexpr int kRowN = N + 8;                              // LDS row of N bf16 + padding
-    constexpr int NB = N / 32;                                // 16-byte chunks of a B / C tile per thread
-    constexpr int PPW = (2 * (N / 32)) / 4;                   // state tiles (32 x 32) per wavefront: 2 p tiles x N / 32 n tiles
-    __shared__ float delta[kLc], cum[kLc];
+    constexpr int NB = N / 32;                                // 16-byte pieces of a B / C tile per state thread
+    constexpr int PPR = N / 8;                                // pieces per B / C row
+    constexpr int PPW = N / 64;                               // state tiles (32 x 32) per state wavefront: N / 32 n tiles x 2 p tiles
+    __shared__ __attribute__((aligned(16))) float delta[2][kLc], cum[2][kLc];
     __shared__ __attribute__((aligned(16))) uint16_t bt[tsize(N)];                       // B as [n][s]
     __shared__ __attribute__((aligned(16))) uint16_t xw_hi[tsize(kP)], xw_lo[tsize(kP)]; // weight_s x_s[p] as [p][s]
     __shared__ __attribute__((aligned(16))) uint16_t xt[PASS2 ? tsize(kP) : 8];          // x as [p][s]
-    __shared__ __attribute__((aligned(16))) uint16_t zt[PASS2 ? kLc * kRowS : 8];         // z as [t][p]
+    __shared__ __attribute__((aligned(16))) uint16_t zt[(PASS2 && HAS_Z) ? kLc * kRowS : 8];   // z as [t][p]
     __shared__ __attribute__((aligned(16))) uint16_t c_rows[PASS2 ? kLc * kRowN : 8];     // C as [t][n]
     __shared__ __attribute__((aligned(16))) uint16_t b_rows[PASS2 ? kLc * kRowN : 8];     // B as [s][n]
-    __shared__ __attribute__((aligned(16))) uint16_t mm_hi[PASS2 ? kLc * kRowS : 8], mm_lo[PASS2 ? kLc * kRowS : 8];
-    __shared__ __attribute__((aligned(16))) uint16_t h_hi[PASS2 ? kP * kRowN : 8], h_lo[PASS2 ? kP * kRowN : 8];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ __attribute__((aligned(16))) uint16_t mm_hi[PASS2 ? kLc * kRowS : 8], mm_lo[PASS2 ? kLc * kRowS : 8];   // M as [t][s]
+    __shared__ __attribute__((aligned(16))) uint16_t h_hi[PASS2 ? kP * kRowN : 8], h_lo[PASS2 ? kP * kRowN : 8];       // state as [p][n]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool role_y = PASS2 && wave < 4;                    // output role: wavefronts 0 .. 3 of pass 2
+    const int yt = tid & (kThreads - 1);                      // thread index inside a role
+    const int sw = wave & 3;                                  // wavefront index inside a role
+    const bool scan_wave = !role_y && sw == 0;                // keeps delta and its running sum
     const int seg = blockIdx.x;
     const int64_t h = blockIdx.y, b = blockIdx.z;
     const int64_t row0 = b * L, D = H * kP;
     const float A_h = A[h], bias_h = dt_bias ? dt_bias[h] : 0.0f;
-    const int r = lane & 31, hk = (lane >> 5) * 8;
-    const int tt = wave >> 1, half = wave & 1;                // output block of this wavefront in pass 2
+    const float dsk = Dskip ? Dskip[h] : 0.0f;
+    const int r = lane & 31, up = lane >> 5, hk = up * 8;
+    const int tt = sw >> 1, half = sw & 1;                    // output role: block (channel tile half, step tile tt)
     const int c_first = seg * chunks_per_seg;
     const int c_last = min(c_first + chunks_per_seg, n_chunks);
 
-    // raw tiles of one chunk, as this thread's 16-byte pieces
-    struct Raw {
-        uint4 x[2], z[2], bq[NB], cq[NB];
-        float dt;
+    // State role: this thread's 16-byte pieces of a chunk's raw tiles: NB adjacent steps sb0 .. of B and of
+    // C (states nb0 .. + 7), two adjacent steps sx0, sx0 + 1 of x and of z (channels px0 .. + 7).
+    const int sb0 = NB * (yt / PPR), nb0 = (yt % PPR) * 8;
+    const int sx0 = 2 * (yt >> 3), px0 = (yt & 7) * 8;
+    uint4 Pb[NB], Pc[NB], Pz0 = make_uint4(0, 0, 0, 0), Pz1 = Pz0, Px[2][2];                        // x is kept a phase longer: two sets, used in turn
+    auto tok_of = [&](int chunk, int s) {                         // row of step s of a chunk, clamped to the segment and to L
+        const int64_t tok = (int64_t)min(chunk, c_last - 1) * kLc + s;
+        return row0 + (tok < L ? tok : L - 1);
     };
-    auto fetch = [&](int chunk) {
-        Raw q;
-        const int64_t tok0 = (int64_t)chunk * kLc;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int ch = tid + i * kThreads, s = ch >> 3, p0 = (ch & 7) * 8;
-            const bool ok = tok0 + s < L;
-            const int64_t o = ((row0 + tok0 + s) * H + h) * kP + p0;
-            q.x[i] = ok ? *reinterpret_cast<const uint4 *>(x + o) : make_uint4(0, 0, 0, 0);
-            q.z[i] = (PASS2 && HAS_Z && ok) ? *reinterpret_cast<const uint4 *>(z + o) : make_uint4(0, 0, 0, 0);
-        }
+    auto fetch = [&](int chunk, uint4 (&X)[2]) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int ch = tid + i * kThreads, s = ch / (N / 8), n0 = (ch % (N / 8)) * 8;
-            const bool ok = tok0 + s < L;
-            const int64_t o = (row0 + tok0 + s) * N + n0;
-            q.bq[i] = ok ? *reinterpret_cast<const uint4 *>(Bm + o) : make_uint4(0, 0, 0, 0);
-            q.cq[i] = (PASS2 && ok) ? *reinterpret_cast<const uint4 *>(Cm + o) : make_uint4(0, 0, 0, 0);
+            const int64_t o = tok_of(chunk, sb0 + i) * N + nb0;
+            Pb[i] = *reinterpret_cast<const uint4 *>(Bm + o);
+            if constexpr (PASS2) Pc[i] = *reinterpret_cast<const uint4 *>(Cm + o);
         }
-        q.dt = 0.0f;
-        if (tid < kLc && tok0 + tid < L) q.dt = bf16_to_f32(dt[(row0 + tok0 + tid) * H + h]);
-        return q;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int64_t o = (tok_of(chunk, sx0 + i) * H + h) * kP + px0;
+            X[i] = *reinterpret_cast<const uint4 *>(x + o);
+            if constexpr (PASS2 && HAS_Z) (i == 0 ? Pz0 : Pz1) = *reinterpret_cast<const uint4 *>(z + o);
+        }
+    };
+    auto fetch_dt = [&](int chunk) {                              // one lane per step, raw bits (converted where used)
+        return dt[tok_of(chunk, lane) * H + h];
+    };
+    // delta and the inclusive running sum of delta * A over a chunk (steps past L: delta = 0), one lane per
+    // step: sums inside rows of 16 lanes by shifted adds, then the totals of the rows before
+    float seg_sum = 0.0f;
+    auto prefix = [&](int chunk, bf16_t dt_raw, int buf) {
+        const float dtv = bf16_to_f32(dt_raw);
+        const float dl = ((int64_t)chunk * kLc + lane < L) ? (softplus ? softplus_f32(dtv + bias_h) : dtv + bias_h) : 0.0f;
+        float sc = dl * A_h;
+        sc += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sc), 0x111, 0xf, 0xf, false));
+        sc += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sc), 0x112, 0xf, 0xf, false));
+        sc += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sc), 0x114, 0xf, 0xf, false));
+        sc += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sc), 0x118, 0xf, 0xf, false));
+        const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc), 15));
+        const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc), 31));
+        const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc), 47));
+        const int row = lane >> 4;
+        sc += row == 0 ? 0.0f : row == 1 ? r0 : row == 2 ? r0 + r1 : (r0 + r1) + r2;
+        delta[buf][lane] = dl;
+        cum[buf][lane] = sc;
+        seg_sum += dl;
     };
 
-    // the head's state: tile j of this wavefront is (p tile pt, n tile nt); acc[j][i] is
-    // H[p = 32 pt + 8 (i / 4) + 4 (lane / 32) + i % 4][n = 32 nt + lane % 32]
+    // State role: the head's state, transposed: tile j of a state wavefront is (n tile nt, p tile pt);
+    // acc[j][4 g + q] is H[p = 32 pt + lane % 32][n = 32 nt + 8 g + 4 (lane / 32) + q].
     f32x16 acc[PPW];
     float *slot_in = ws_state + (((int64_t)b * (n_seg + 1) + seg) * D + h * kP) * N;
 #pragma unroll
-    for (int j = 0; j < PPW; ++j) {
-        const int pair = wave * PPW + j, pt = pair & 1, nt = pair >> 1;
+    for (int j = 0; j < PPW; ++j)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int p = pt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-            acc[j][i] = PASS2 ? slot_in[(int64_t)p * N + nt * 32 + r] : 0.0f;
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.0f;
+    if (PASS2 && !role_y) {
+#pragma unroll
+        for (int j = 0; j < PPW; ++j) {
+            const int id = sw * PPW + j, pt = id & 1, nt = id >> 1;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 v = *reinterpret_cast<const float4 *>(slot_in + (int64_t)(pt * 32 + r) * N + nt * 32 + 8 * g + 4 * up);
+                acc[j][4 * g] = v.x, acc[j][4 * g + 1] = v.y, acc[j][4 * g + 2] = v.z, acc[j][4 * g + 3] = v.w;
+            }
         }
     }
-    float seg_sum = 0.0f;
     if (!PASS2 && seg == 0 && b == 0)
         for (int i = tid; i < kP * N; i += kThreads) a_rows[h * kP * N + i] = A_h;   // decay matrix for the carry kernel
 
-    Raw raw = fetch(c_first);
-    for (int chunk = c_first; chunk < c_last; ++chunk) {
-        const int64_t tok0 = (int64_t)chunk * kLc;
-        // delta and the inclusive running sum of delta * A over the chunk (wavefront 0, one lane per step)
-        if (wave == 0) {
-            const float dl = (tok0 + lane < L) ? (softplus ? softplus_f32(raw.dt + bias_h) : raw.dt + bias_h) : 0.0f;
-            float sc = dl * A_h;
+    bf16_t dt_next = 0, dt_after = 0;                             // dt of the next chunk and of the one after
+    if (!role_y) {
+        fetch(c_first, Px[0]);
+        dt_next = fetch_dt(c_first + 1);
+        dt_after = fetch_dt(c_first + 2);
+        if (scan_wave) prefix(c_first, fetch_dt(c_first), 0);
+    }
+    lds_barrier();                                                // delta, cum of the first chunk
+
+    // Each role runs its own loop over the chunks, with the same three barriers per chunk (two in pass 1):
+    //   A  state role: raw tiles into LDS, then the next chunk's fetch          | barrier (pass 2 only)
+    //   B  output role: G^T and M;  state role: weighted x                      | barrier
+    //   C  output role: products, gate, store;  state role: state update, the next chunk's delta sums | barrier
+    // (a wavefront never changes role, so both sides meet at every barrier; with the loops apart the
+    // compiler counts each role's loads in flight exactly)
+    if (role_y) {
+        if constexpr (PASS2) {
+            const int t = tt * 32 + r;
+            for (int chunk = c_first; chunk < c_last; ++chunk) {
+                const int64_t tok0 = (int64_t)chunk * kLc;
+                const int buf = (chunk - c_first) & 1;
+                lds_barrier();                                        // the raw tiles are in LDS
+                if (half <= tt) {                                     // the block above the diagonal is masked out entirely
+                    f32x16 gacc;
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const float o = __shfl_up(sc, off, 64);
-                if (lane >= off) sc += o;
+                    for (int i = 0; i < 16; ++i) gacc[i] = 0.0f;
+#pragma unroll
+                    for (int ks = 0; ks < N / 16; ++ks)
+                        gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(b_rows, kRowN, half * 32 + r, ks * 16 + hk),
+                                                                       frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk), gacc, 0, 0, 0);
+                    // gacc[4 g + q] = C_t . B_s, t = 32 tt + lane % 32, s = 32 half + 8 g + 4 (lane / 32) + q
+                    // M = G * exp(s_t - s_s) * delta_s for s <= t (steps past L have delta = 0), + D on the diagonal
+                    const float ct = cum[buf][t];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int s0 = half * 32 + 8 * g + 4 * up;
+                        const float4 cs = *reinterpret_cast<const float4 *>(&cum[buf][s0]);
+                        const float4 ds = *reinterpret_cast<const float4 *>(&delta[buf][s0]);
+                        const float c4[4] = {cs.x, cs.y, cs.z, cs.w}, d4[4] = {ds.x, ds.y, ds.z, ds.w};
+                        float v[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            v[q] = (s0 + q <= t) ? gacc[4 * g + q] * exp2_hw((ct - c4[q]) * kLog2e) * d4[q] : 0.0f;
+                            if (s0 + q == t) v[q] += dsk;
+                        }
+                        split4(v, reinterpret_cast<uint2 *>(&mm_hi[t * kRowS + s0]), reinterpret_cast<uint2 *>(&mm_lo[t * kRowS + s0]));
+                    }
+                }
+                lds_barrier();                                        // M and the weighted x are in LDS
+                f32x16 inter, intra;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) inter[i] = intra[i] = 0.0f;
+#pragma unroll
+                for (int ks = 0; ks < N / 16; ++ks) {                 // C with the incoming state
+                    const bf16x8 cf = frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk);
+                    inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h_hi, kRowN, half * 32 + r, ks * 16 + hk), cf, inter, 0, 0, 0);
+                    inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h_lo, kRowN, half * 32 + r, ks * 16 + hk), cf, inter, 0, 0, 0);
+                }
+#pragma unroll
+                for (int ks = 0; ks < kLc / 16; ++ks)                 // M (with D) with x
+                    if (ks < 2 * (tt + 1)) {                          // M is zero right of the diagonal block
+                        const bf16x8 xf = tfrag(xt, half * 32 + r, ks * 16 + hk);
+                        intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, frag(mm_hi, kRowS, tt * 32 + r, ks * 16 + hk), intra, 0, 0, 0);
+                        intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, frag(mm_lo, kRowS, tt * 32 + r, ks * 16 + hk), intra, 0, 0, 0);
+                    }
+                // inter / intra [4 g + q]: step t = 32 tt + lane % 32, channel p = 32 half + 8 g + 4 (lane / 32) + q
+                if (tok0 + t < L) {
+                    const float e = exp2_hw(cum[buf][t] * kLog2e);
+                    bf16_t *orow = out + ((row0 + tok0 + t) * H + h) * kP + half * 32 + 4 * up;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        float y[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) y[q] = intra[4 * g + q] + e * inter[4 * g + q];
+                        if constexpr (HAS_Z) {
+                            const uint2 zq = *reinterpret_cast<const uint2 *>(&zt[t * kRowS + half * 32 + 8 * g + 4 * up]);
+                            y[0] *= silu_f32(bf16_lo(zq.x)), y[1] *= silu_f32(bf16_hi(zq.x));
+                            y[2] *= silu_f32(bf16_lo(zq.y)), y[3] *= silu_f32(bf16_hi(zq.y));
+                        }
+                        *reinterpret_cast<uint2 *>(orow + 8 * g) = make_uint2(f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3]));
+                    }
+                }
+                lds_barrier();                                        // the chunk's LDS tiles are free again
             }
-            delta[lane] = dl;
-            cum[lane] = sc;
-            seg_sum += dl;
         }
-        // raw B (and C, x, z in pass 2) into LDS
+    } else {
+        // one chunk; X holds its x pieces, Xn takes those of the next chunk
+        auto walk = [&](int chunk, uint4 (&X)[2], uint4 (&Xn)[2]) {
+            const int64_t tok0 = (int64_t)chunk * kLc;
+            const int buf = (chunk - c_first) & 1;
+            if (tok0 + kLc > L) {                                 // only the last chunk of a row: zero the steps past L
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int ch = tid + i * kThreads, s = ch / (N / 8), n0 = (ch % (N / 8)) * 8;
-            const uint32_t w[4] = {raw.bq[i].x, raw.bq[i].y, raw.bq[i].z, raw.bq[i].w};
+                for (int i = 0; i < NB; ++i)
+                    if (tok0 + sb0 + i >= L) {
+                        Pb[i] = make_uint4(0, 0, 0, 0);
+                        if constexpr (PASS2) Pc[i] = make_uint4(0, 0, 0, 0);
+                    }
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                bt[trow(n0 + 2 * k) + s] = (uint16_t)(w[k] & 0xffffu);
-                bt[trow(n0 + 2 * k + 1) + s] = (uint16_t)(w[k] >> 16);
+                for (int i = 0; i < 2; ++i)
+                    if (tok0 + sx0 + i >= L) X[i] = make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if constexpr (NB == 4)
+                    *reinterpret_cast<uint2 *>(&bt[trow(nb0 + k) + sb0]) = make_uint2(pair_el(Pb[0], Pb[1], k), pair_el(Pb[2], Pb[3], k));
+                else
+                    *reinterpret_cast<uint32_t *>(&bt[trow(nb0 + k) + sb0]) = pair_el(Pb[0], Pb[1], k);
             }
             if constexpr (PASS2) {
-                *reinterpret_cast<uint4 *>(&b_rows[s * kRowN + n0]) = raw.bq[i];
-                *reinterpret_cast<uint4 *>(&c_rows[s * kRowN + n0]) = raw.cq[i];
-            }
-        }
-        if constexpr (PASS2) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int ch = tid + i * kThreads, s = ch >> 3, p0 = (ch & 7) * 8;
-                const uint32_t w[4] = {raw.x[i].x, raw.x[i].y, raw.x[i].z, raw.x[i].w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    xt[trow(p0 + 2 * k) + s] = (uint16_t)(w[k] & 0xffffu);
-                    xt[trow(p0 + 2 * k + 1) + s] = (uint16_t)(w[k] >> 16);
+                for (int i = 0; i < NB; ++i) {
+                    *reinterpret_cast<uint4 *>(&b_rows[(sb0 + i) * kRowN + nb0]) = Pb[i];
+                    *reinterpret_cast<uint4 *>(&c_rows[(sb0 + i) * kRowN + nb0]) = Pc[i];
                 }
-                *reinterpret_cast<uint4 *>(&zt[s * kRowS + p0]) = raw.z[i];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) *reinterpret_cast<uint32_t *>(&xt[trow(px0 + k) + sx0]) = pair_el(X[0], X[1], k);
+                if constexpr (HAS_Z) {
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4 *>(&zt[(sx0 + i) * kRowS + px0]) = i == 0 ? Pz0 : Pz1;
+                }
+                // the state at the start of the chunk, as two bf16 terms, for the incoming-state product
+#pragma unroll
+                for (int j = 0; j < PPW; ++j) {
+                    const int id = sw * PPW + j, pt = id & 1, nt = id >> 1;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const float v[4] = {acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
+                        const int o = (pt * 32 + r) * kRowN + nt * 32 + 8 * g + 4 * up;
+                        split4(v, reinterpret_cast<uint2 *>(&h_hi[o]), reinterpret_cast<uint2 *>(&h_lo[o]));
+                    }
+                }
             }
-            // the state at the start of the chunk, as two bf16 terms, for the incoming-state product
+            fetch(chunk + 1, Xn);
+            if constexpr (PASS2) lds_barrier();                   // the raw tiles are in LDS
+            // weighted x for the state update, two bf16 terms: weight_s = exp(s_end - s_s) delta_s
+            const float cend = cum[buf][kLc - 1];
+            const float w0 = exp2_hw((cend - cum[buf][sx0]) * kLog2e) * delta[buf][sx0];
+            const float w1 = exp2_hw((cend - cum[buf][sx0 + 1]) * kLog2e) * delta[buf][sx0 + 1];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float v0 = piece_el(X[0], k) * w0, v1 = piece_el(X[1], k) * w1;
+                const uint32_t top = f32x2_to_bf16x2(v0, v1);
+                *reinterpret_cast<uint32_t *>(&xw_hi[trow(px0 + k) + sx0]) = top;
+                *reinterpret_cast<uint32_t *>(&xw_lo[trow(px0 + k) + sx0]) = f32x2_to_bf16x2(v0 - bf16_lo(top), v1 - bf16_hi(top));
+            }
+            lds_barrier();                                        // M, the weighted x (and in pass 1 B) are in LDS
+            if (scan_wave && chunk + 1 < c_last) prefix(chunk + 1, dt_next, buf ^ 1);
+            dt_next = dt_after;
+            dt_after = fetch_dt(chunk + 3);
+            // state: acc <- exp(s_end) acc + sum_s bt[n][s] xw[p][s]
+            const float dec = exp2_hw(cend * kLog2e);
 #pragma unroll
             for (int j = 0; j < PPW; ++j) {
-                const int pair = wave * PPW + j, pt = pair & 1, nt = pair >> 1;
+                const int id = sw * PPW + j, pt = id & 1, nt = id >> 1;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int p = pt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                    split2(acc[j][i], &h_hi[p * kRowN + nt * 32 + r], &h_lo[p * kRowN + nt * 32 + r]);
+                for (int i = 0; i < 16; ++i) acc[j][i] *= dec;
+#pragma unroll
+                for (int ks = 0; ks < kLc / 16; ++ks) {
+                    const bf16x8 bf = tfrag(bt, nt * 32 + r, ks * 16 + hk);
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, tfrag(xw_hi, pt * 32 + r, ks * 16 + hk), acc[j], 0, 0, 0);
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, tfrag(xw_lo, pt * 32 + r, ks * 16 + hk), acc[j], 0, 0, 0);
                 }
             }
+            lds_barrier();                                        // the chunk's LDS tiles are free again
+        };
+        for (int chunk = c_first; chunk < c_last; chunk += 2) {
+            walk(chunk, Px[0], Px[1]);
+            if (chunk + 1 < c_last) walk(chunk + 1, Px[1], Px[0]);
         }
-        __syncthreads();                                          // delta, cum and the raw tiles are in LDS
-        // weighted x for the state update, two bf16 terms: weight_s = exp(s_end - s_s) delta_s
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int ch = tid + i * kThreads, s = ch >> 3, p0 = (ch & 7) * 8;
-            const float w = exp2_hw((cum[kLc - 1] - cum[s]) * kLog2e) * delta[s];
-            const uint4 q = raw.x[i];
-            const float v[8] = {bf16_lo(q.x) * w, bf16_hi(q.x) * w, bf16_lo(q.y) * w, bf16_hi(q.y) * w,
-                                bf16_lo(q.z) * w, bf16_hi(q.z) * w, bf16_lo(q.w) * w, bf16_hi(q.w) * w};
-#pragma unroll
-            for (int k = 0; k < 8; ++k) split2(v[k], &xw_hi[trow(p0 + k) + s], &xw_lo[trow(p0 + k) + s]);
-        }
-        if (chunk + 1 < c_last) raw = fetch(chunk + 1);           // in flight during the products below
-
-        f32x16 gacc;
-        if constexpr (PASS2) {
-            // G block (t tile tt, s tile half); above the diagonal it is masked out entirely
-#pragma unroll
-            for (int i = 0; i < 16; ++i) gacc[i] = 0.0f;
-            if (half <= tt) {
-#pragma unroll
-                for (int ks = 0; ks < N / 16; ++ks)
-                    gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk),
-                                                                   frag(b_rows, kRowN, half * 32 + r, ks * 16 + hk), gacc, 0, 0, 0);
-            }
-            // M = G * exp(s_t - s_s) * delta_s for s <= t (steps past L have delta = 0)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int t = tt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3), s = half * 32 + r;
-                const float v = (s <= t) ? gacc[i] * exp2_hw((cum[t] - cum[s]) * kLog2e) * delta[s] : 0.0f;
-                split2(v, &mm_hi[t * kRowS + s], &mm_lo[t * kRowS + s]);
-            }
-        }
-        __syncthreads();                                          // M and the weighted x are in LDS
-
-        if constexpr (PASS2) {
-            f32x16 inter, intra;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) inter[i] = intra[i] = 0.0f;
-#pragma unroll
-            for (int ks = 0; ks < N / 16; ++ks) {
-                const bf16x8 cf = frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk);
-                inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf, frag(h_hi, kRowN, half * 32 + r, ks * 16 + hk), inter, 0, 0, 0);
-                inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf, frag(h_lo, kRowN, half * 32 + r, ks * 16 + hk), inter, 0, 0, 0);
-            }
-#pragma unroll
-            for (int ks = 0; ks < kLc / 16; ++ks)
-                if (ks < 2 * (tt + 1)) {                          // M is zero right of the diagonal block
-                    const bf16x8 xf = tfrag(xt, half * 32 + r, ks * 16 + hk);
-                    intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(mm_hi, kRowS, tt * 32 + r, ks * 16 + hk), xf, intra, 0, 0, 0);
-                    intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(mm_lo, kRowS, tt * 32 + r, ks * 16 + hk), xf, intra, 0, 0, 0);
-                }
-            const float dsk = Dskip ? Dskip[h] : 0.0f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int t = tt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3), p = half * 32 + r;
-                if (tok0 + t >= L) continue;
-                float y = intra[i] + exp2_hw(cum[t] * kLog2e) * inter[i] + dsk * bf16_to_f32(xt[trow(p) + t]);
-                if constexpr (HAS_Z) y *= silu_f32(bf16_to_f32(zt[t * kRowS + p]));
-                out[((row0 + tok0 + t) * H + h) * kP + p] = (bf16_t)f32_to_bf16(y);
-            }
-        }
-        // state: acc <- exp(s_end) acc + sum_s xw[p][s] bt[n][s]
-        const float dec = exp2_hw(cum[kLc - 1] * kLog2e);
-#pragma unroll
-        for (int j = 0; j < PPW; ++j) {
-            const int pair = wave * PPW + j, pt = pair & 1, nt = pair >> 1;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[j][i] *= dec;
-#pragma unroll
-            for (int ks = 0; ks < kLc / 16; ++ks) {
-                const bf16x8 bf = tfrag(bt, nt * 32 + r, ks * 16 + hk);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tfrag(xw_hi, pt * 32 + r, ks * 16 + hk), bf, acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tfrag(xw_lo, pt * 32 + r, ks * 16 + hk), bf, acc[j], 0, 0, 0);
-            }
-        }
-        __syncthreads();                                          // the chunk's LDS tiles are free again
     }
 
     // end of the segment: pass 1 leaves the local end state and the sum of deltas, pass 2 the final state
     float *dst = nullptr;
     if (!PASS2) dst = ws_state + (((int64_t)b * (n_seg + 1) + seg + 1) * D + h * kP) * N;
     else if (h_final && seg == n_seg - 1) dst = h_final + (b * D + h * kP) * N;
-    if (dst) {
+    if (dst && !role_y) {
 #pragma unroll
         for (int j = 0; j < PPW; ++j) {
-            const int pair = wave * PPW + j, pt = pair & 1, nt = pair >> 1;
+            const int id = sw * PPW + j, pt = id & 1, nt = id >> 1;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int p = pt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                dst[(int64_t)p * N + nt * 32 + r] = acc[j][i];
-            }
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4 *>(dst + (int64_t)(pt * 32 + r) * N + nt * 32 + 8 * g + 4 * up) =
+                    make_float4(acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]);
         }
     }
-    if (!PASS2 && wave == 0) {
+    if (!PASS2 && scan_wave) {
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) seg_sum += __shfl_xor(seg_sum, off, 64);
         ws_sumdt[((int64_t)b * (n_seg + 1) + seg) * D + h * kP + lane] = seg_sum;   // kP == 64 lanes
@@ -396,9 +498,8 @@ hipError_t launch_ssd(const SsdArgs &a, hipStream_t stream)
     bf16_t *out = static_cast<bf16_t *>(a.out);
     dim3 grid((unsigned)n_seg, (unsigned)a.H, (unsigned)a.batch);
 #define MAMBA_SSD(NN, P2, HZ)                                                                                     \
-    ssd_segment<NN, P2, HZ><<<grid, kThreads, 0, stream>>>(x, dt, a.A, Bm, Cm, a.Dskip, z, a.dt_bias, ws_state,    \
-                                                          ws_sumdt, a_rows, out, a.h_final, a.L, a.H, cps, n_seg, \
-                                                          nc, a.dt_softplus)
+    ssd_segment<NN, P2, HZ><<<grid, (P2) ? 2 * kThreads : kThreads, 0, stream>>>(x, dt, a.A, Bm, Cm, a.Dskip, z,   \
+        a.dt_bias, ws_state, ws_sumdt, a_rows, out, a.h_final, a.L, a.H, cps, n_seg, nc, a.dt_softplus)
     if (n_seg > 1) {
         if (a.N == 64) MAMBA_SSD(64, false, false);
         else MAMBA_SSD(128, false, false);
