@@ -62,6 +62,18 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+#ifdef MAMBA_SSD_TIMING
+// tuning builds only: shader clock at the phase boundaries of one chunk of one workgroup, per wavefront
+__device__ long long g_ssd_clock[8][8];
+#define SSD_STAMP(i)                                                                                       \
+    do {                                                                                                   \
+        if (blockIdx.x == 3 && blockIdx.y == 1 && chunk == c_first + 6 && lane == 0)                       \
+            g_ssd_clock[wave][i] = (long long)__builtin_amdgcn_s_memtime();                                \
+    } while (0)
+#else
+#define SSD_STAMP(i)
+#endif
+
 // four values -> their bf16 roundings and the bf16 of what the roundings dropped, packed in order
 __device__ __forceinline__ void split4(const float *v, uint2 *top, uint2 *rem)
 {
@@ -88,16 +100,17 @@ __device__ __forceinline__ uint32_t pair_el(const uint4 &a, const uint4 &b, int 
 // A workgroup walks the chunks of one segment of one (batch row, head) in order, the head's state
 // living transposed (N x P float32) in MFMA accumulators: per chunk acc <- exp(s_end) acc + S.
 //   PASS2 = false: from a zero state; leaves the segment's end state in slot seg + 1 of ws_state
-//       ((batch, n_seg + 1, H * P, N)) and the segment's sum of deltas in ws_sumdt; the carry kernel
+//       ((batch, n_slots, H * P, N)) and the segment's sum of deltas in ws_sumdt; the carry kernel
 //       of the selective scan then turns the slots into the states at the segment starts;
-//   PASS2 = true: from the true incoming state (slot seg), with outputs.
-// Two roles.  The four "state" wavefronts hold the accumulators and do all the fetching: per chunk they
-// park B transposed and the weighted x (two bf16 terms) in LDS and multiply them into the state; in pass 2
-// they also lay out B, C and z row-major, x transposed and the state at the chunk start (two bf16 terms)
-// for the output products.  Pass 2 adds four "output" wavefronts, one 32 x 32 block of the chunk's 64 x 64
+//   PASS2 = true: from the true incoming state (slot seg * slot_step: pass 1 may cut the sequence
+//       slot_step times finer than pass 2, its workgroups being small enough to share a CU), with outputs.
+// Two roles.  The four "state" wavefronts hold the accumulators: per chunk they park B transposed and the
+// weighted x (two bf16 terms) in LDS and multiply them into the state; in pass 2 they also lay out B
+// row-major, x transposed and the state at the chunk start (two bf16 terms) for the output products.  Pass 2 adds four "output" wavefronts, one 32 x 32 block of the chunk's 64 x 64
 // outputs each, computed transposed so that a lane owns one step and four adjacent channels at a time:
-// they form G^T and M (D goes onto M's diagonal, which adds D x_t to the outputs), and after the barrier
-// multiply M with x and C with the incoming state, gate and write out.  With one wavefront of each role
+// they lay out C and z, form G^T and M (D goes onto M's diagonal, which adds D x_t to the outputs), after
+// the barrier multiply M with x and C with the incoming state, and gate and store during the next chunk's
+// first phase, when the state role is busy filling LDS.  With one wavefront of each role
 // on every SIMD the conversions of one overlap the products of the other.  Everything a thread moves into LDS transposed is a run of 2 or 4
 // steps of one row (its pieces are adjacent steps), so the writes are 4 or 8 bytes wide.  The raw tiles
 // of the next chunk are fetched (unconditionally: steps past L re-read step L - 1 and are zeroed at use)
@@ -109,7 +122,7 @@ __global__ void __launch_bounds__(PASS2 ? 2 * kThreads : kThreads) __attribute__
 ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, const bf16_t *Bm, const bf16_t *Cm,
             const float *__restrict__ Dskip, const bf16_t *z, const float *__restrict__ dt_bias, float *ws_state,
             float *ws_sumdt, float *a_rows, bf16_t *out, float *h_final, int64_t L, int64_t H, int chunks_per_seg,
-            int n_seg, int n_chunks, int softplus)
+            int n_seg, int n_slots, int slot_step, int n_chunks, int softplus)
 {
     // (x, dt, B, C, z are deliberately not declared restrict: as possibly aliased by the stores to out they
     // stay where they are written, a chunk ahead of their use, instead of being sunk to it by the compiler)
@@ -117,7 +130,8 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
     constexpr int NB = N / 32;                                // 16-byte pieces of a B / C tile per state thread
     constexpr int PPR = N / 8;                                // pieces per B / C row
     constexpr int PPW = N / 64;                               // state tiles (32 x 32) per state wavefront: N / 32 n tiles x 2 p tiles
-    __shared__ __attribute__((aligned(16))) float delta[2][kLc], cum[2][kLc];
+    __shared__ float4 delta4[2][kLc / 4], cum4[2][kLc / 4];      // delta and its running sum times A, per step; two chunks
+    float (*delta)[kLc] = reinterpret_cast<float (*)[kLc]>(delta4), (*cum)[kLc] = reinterpret_cast<float (*)[kLc]>(cum4);
     __shared__ __attribute__((aligned(16))) uint16_t bt[tsize(N)];                       // B as [n][s]
     __shared__ __attribute__((aligned(16))) uint16_t xw_hi[tsize(kP)], xw_lo[tsize(kP)]; // weight_s x_s[p] as [p][s]
     __shared__ __attribute__((aligned(16))) uint16_t xt[PASS2 ? tsize(kP) : 8];          // x as [p][s]
@@ -146,27 +160,72 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
     // C (states nb0 .. + 7), two adjacent steps sx0, sx0 + 1 of x and of z (channels px0 .. + 7).
     const int sb0 = NB * (yt / PPR), nb0 = (yt % PPR) * 8;
     const int sx0 = 2 * (yt >> 3), px0 = (yt & 7) * 8;
-    uint4 Pb[NB], Pc[NB], Pz0 = make_uint4(0, 0, 0, 0), Pz1 = Pz0, Px[2][2];                        // x is kept a phase longer: two sets, used in turn
-    auto tok_of = [&](int chunk, int s) {                         // row of step s of a chunk, clamped to the segment and to L
-        const int64_t tok = (int64_t)min(chunk, c_last - 1) * kLc + s;
-        return row0 + (tok < L ? tok : L - 1);
+    // B and x are needed twice, a phase before their chunk starts (transposed B and weighted x for the state
+    // update) and in its first phase (row-major B, transposed x): two register sets used in turn, each
+    // refilled for the chunk after the next as soon as its chunk has gone to LDS.  C and z (output role, which
+    // uses the same piece-to-thread map): one set, fetched a chunk ahead.
+    struct Early {
+        uint4 b[NB], x[2];
     };
-    auto fetch = [&](int chunk, uint4 (&X)[2]) {
+    Early E2[2];
+    uint4 Pc[NB], Pz0 = make_uint4(0, 0, 0, 0), Pz1 = Pz0;
+    // Every fetch is unconditional: chunks past the segment re-read its last chunk, steps past L the row of
+    // step L - 1 (zeroed where used).  Addresses: a per-thread base plus (step inside the batch row) x (row size).
+    const uint32_t last_tok = (uint32_t)(L - 1);
+    auto tok_of = [&](int chunk, int s) { return min((uint32_t)min(chunk, c_last - 1) * kLc + s, last_tok); };
+    const bf16_t *b_base = Bm + row0 * N + nb0, *c_base = Cm + row0 * N + nb0;
+    const bf16_t *x_base = x + (row0 * H + h) * kP + px0;
+    const bf16_t *z_base = (PASS2 && HAS_Z) ? z + (row0 * H + h) * kP + px0 : x_base;
+    const uint32_t xz_row = (uint32_t)(H * kP);
+    auto fetch_early = [&](int chunk, Early &e) {                 // state role: B and x
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int64_t o = tok_of(chunk, sb0 + i) * N + nb0;
-            Pb[i] = *reinterpret_cast<const uint4 *>(Bm + o);
-            if constexpr (PASS2) Pc[i] = *reinterpret_cast<const uint4 *>(Cm + o);
+        for (int i = 0; i < NB; ++i) e.b[i] = *reinterpret_cast<const uint4 *>(b_base + (uint64_t)tok_of(chunk, sb0 + i) * (uint32_t)N);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) e.x[i] = *reinterpret_cast<const uint4 *>(x_base + (uint64_t)tok_of(chunk, sx0 + i) * xz_row);
+    };
+    auto fetch_late = [&](int chunk) {                            // output role: C and z
+#pragma unroll
+        for (int i = 0; i < NB; ++i) Pc[i] = *reinterpret_cast<const uint4 *>(c_base + (uint64_t)tok_of(chunk, sb0 + i) * (uint32_t)N);
+        if constexpr (HAS_Z) {
+            Pz0 = *reinterpret_cast<const uint4 *>(z_base + (uint64_t)tok_of(chunk, sx0) * xz_row);
+            Pz1 = *reinterpret_cast<const uint4 *>(z_base + (uint64_t)tok_of(chunk, sx0 + 1) * xz_row);
         }
+    };
+    // steps past L (only in the last chunk of a row) count as zeros
+    auto mask_early = [&](int chunk, Early &e) {
+        const int64_t tok0 = (int64_t)chunk * kLc;
+        if (tok0 + kLc > L) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int64_t o = (tok_of(chunk, sx0 + i) * H + h) * kP + px0;
-            X[i] = *reinterpret_cast<const uint4 *>(x + o);
-            if constexpr (PASS2 && HAS_Z) (i == 0 ? Pz0 : Pz1) = *reinterpret_cast<const uint4 *>(z + o);
+            for (int i = 0; i < NB; ++i)
+                if (tok0 + sb0 + i >= L) e.b[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                if (tok0 + sx0 + i >= L) e.x[i] = make_uint4(0, 0, 0, 0);
+        }
+    };
+    // B transposed and the weighted x (two bf16 terms: weight_s = exp(s_end - s_s) delta_s) of a chunk into
+    // LDS, for its state update; buf: where the chunk's delta and running sums are
+    auto park_state_operands = [&](const Early &e, int buf) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if constexpr (NB == 4)
+                *reinterpret_cast<uint2 *>(&bt[trow(nb0 + k) + sb0]) = make_uint2(pair_el(e.b[0], e.b[1], k), pair_el(e.b[2], e.b[3], k));
+            else
+                *reinterpret_cast<uint32_t *>(&bt[trow(nb0 + k) + sb0]) = pair_el(e.b[0], e.b[1], k);
+        }
+        const float cend = cum[buf][kLc - 1];
+        const float w0 = exp2_hw((cend - cum[buf][sx0]) * kLog2e) * delta[buf][sx0];
+        const float w1 = exp2_hw((cend - cum[buf][sx0 + 1]) * kLog2e) * delta[buf][sx0 + 1];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float v0 = piece_el(e.x[0], k) * w0, v1 = piece_el(e.x[1], k) * w1;
+            const uint32_t top = f32x2_to_bf16x2(v0, v1);
+            *reinterpret_cast<uint32_t *>(&xw_hi[trow(px0 + k) + sx0]) = top;
+            *reinterpret_cast<uint32_t *>(&xw_lo[trow(px0 + k) + sx0]) = f32x2_to_bf16x2(v0 - bf16_lo(top), v1 - bf16_hi(top));
         }
     };
     auto fetch_dt = [&](int chunk) {                              // one lane per step, raw bits (converted where used)
-        return dt[tok_of(chunk, lane) * H + h];
+        return dt[(row0 + tok_of(chunk, lane)) * H + h];
     };
     // delta and the inclusive running sum of delta * A over a chunk (steps past L: delta = 0), one lane per
     // step: sums inside rows of 16 lanes by shifted adds, then the totals of the rows before
@@ -192,7 +251,7 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
     // State role: the head's state, transposed: tile j of a state wavefront is (n tile nt, p tile pt);
     // acc[j][4 g + q] is H[p = 32 pt + lane % 32][n = 32 nt + 8 g + 4 (lane / 32) + q].
     f32x16 acc[PPW];
-    float *slot_in = ws_state + (((int64_t)b * (n_seg + 1) + seg) * D + h * kP) * N;
+    float *slot_in = ws_state + (((int64_t)b * n_slots + (int64_t)seg * slot_step) * D + h * kP) * N;
 #pragma unroll
     for (int j = 0; j < PPW; ++j)
 #pragma unroll
@@ -212,28 +271,83 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
         for (int i = tid; i < kP * N; i += kThreads) a_rows[h * kP * N + i] = A_h;   // decay matrix for the carry kernel
 
     bf16_t dt_next = 0, dt_after = 0;                             // dt of the next chunk and of the one after
-    if (!role_y) {
-        fetch(c_first, Px[0]);
+    if (role_y) {
+        if constexpr (PASS2) fetch_late(c_first);
+    } else {
+        fetch_early(c_first, E2[0]);
+        fetch_early(c_first + 1, E2[1]);
         dt_next = fetch_dt(c_first + 1);
         dt_after = fetch_dt(c_first + 2);
         if (scan_wave) prefix(c_first, fetch_dt(c_first), 0);
     }
     lds_barrier();                                                // delta, cum of the first chunk
+    if (!role_y) {
+        mask_early(c_first, E2[0]);
+        park_state_operands(E2[0], 0);
+    }
+    if constexpr (!PASS2) lds_barrier();                          // (pass 2 has a barrier ahead of the first state update anyway)
 
     // Each role runs its own loop over the chunks, with the same three barriers per chunk (two in pass 1):
-    //   A  state role: raw tiles into LDS, then the next chunk's fetch          | barrier (pass 2 only)
-    //   B  output role: G^T and M;  state role: weighted x                      | barrier
-    //   C  output role: products, gate, store;  state role: state update, the next chunk's delta sums | barrier
+    //   A  state role: row-major B, transposed x and the state at the chunk start into LDS; fetches.
+    //      output role: gate and store the outputs of the chunk before; C and z into LDS; fetches. | barrier (pass 2)
+    //   B  state role: state update; delta sums of the next chunk.  output role: G^T and M.   | barrier
+    //   C  state role: transposed B and weighted x of the next chunk into LDS.
+    //      output role: the two output products.                                              | barrier
     // (a wavefront never changes role, so both sides meet at every barrier; with the loops apart the
     // compiler counts each role's loads in flight exactly)
     if (role_y) {
         if constexpr (PASS2) {
             const int t = tt * 32 + r;
+            f32x16 inter, intra;                                      // outputs of the chunk before, not yet gated
+            uint2 zq[4];
+            float e_t = 0.0f;
+            int64_t tok_prev = -1;                                    // its token (none yet)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) inter[i] = intra[i] = 0.0f;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) zq[g] = make_uint2(0, 0);
+            auto epilogue = [&]() {
+                if (tok_prev < 0 || tok_prev >= L) return;
+                bf16_t *orow = out + ((row0 + tok_prev) * H + h) * kP + half * 32 + 4 * up;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float y[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) y[q] = intra[4 * g + q] + e_t * inter[4 * g + q];
+                    if constexpr (HAS_Z) {
+                        y[0] *= silu_f32(bf16_lo(zq[g].x)), y[1] *= silu_f32(bf16_hi(zq[g].x));
+                        y[2] *= silu_f32(bf16_lo(zq[g].y)), y[3] *= silu_f32(bf16_hi(zq[g].y));
+                    }
+                    *reinterpret_cast<uint2 *>(orow + 8 * g) = make_uint2(f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3]));
+                }
+            };
             for (int chunk = c_first; chunk < c_last; ++chunk) {
-                const int64_t tok0 = (int64_t)chunk * kLc;
                 const int buf = (chunk - c_first) & 1;
+                SSD_STAMP(0);
+                epilogue();
+                if ((int64_t)chunk * kLc + kLc > L) {                 // only the last chunk of a row: zero C past L
+#pragma unroll
+                    for (int i = 0; i < NB; ++i)
+                        if ((int64_t)chunk * kLc + sb0 + i >= L) Pc[i] = make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4 *>(&c_rows[(sb0 + i) * kRowN + nb0]) = Pc[i];
+                if constexpr (HAS_Z) {
+                    *reinterpret_cast<uint4 *>(&zt[sx0 * kRowS + px0]) = Pz0;
+                    *reinterpret_cast<uint4 *>(&zt[(sx0 + 1) * kRowS + px0]) = Pz1;
+                }
+                fetch_late(chunk + 1);
+                SSD_STAMP(1);
                 lds_barrier();                                        // the raw tiles are in LDS
+                SSD_STAMP(2);
                 if (half <= tt) {                                     // the block above the diagonal is masked out entirely
+                    float4 cs[4], ds[4];                              // running sums and deltas of the lane's 16 steps s
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        cs[g] = cum4[buf][half * 8 + 2 * g + up];
+                        ds[g] = delta4[buf][half * 8 + 2 * g + up];
+                    }
+                    const float ct = cum[buf][t];
                     f32x16 gacc;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) gacc[i] = 0.0f;
@@ -243,13 +357,10 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                                                                        frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk), gacc, 0, 0, 0);
                     // gacc[4 g + q] = C_t . B_s, t = 32 tt + lane % 32, s = 32 half + 8 g + 4 (lane / 32) + q
                     // M = G * exp(s_t - s_s) * delta_s for s <= t (steps past L have delta = 0), + D on the diagonal
-                    const float ct = cum[buf][t];
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int s0 = half * 32 + 8 * g + 4 * up;
-                        const float4 cs = *reinterpret_cast<const float4 *>(&cum[buf][s0]);
-                        const float4 ds = *reinterpret_cast<const float4 *>(&delta[buf][s0]);
-                        const float c4[4] = {cs.x, cs.y, cs.z, cs.w}, d4[4] = {ds.x, ds.y, ds.z, ds.w};
+                        const float c4[4] = {cs[g].x, cs[g].y, cs[g].z, cs[g].w}, d4[4] = {ds[g].x, ds[g].y, ds[g].z, ds[g].w};
                         float v[4];
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
@@ -259,8 +370,9 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                         split4(v, reinterpret_cast<uint2 *>(&mm_hi[t * kRowS + s0]), reinterpret_cast<uint2 *>(&mm_lo[t * kRowS + s0]));
                     }
                 }
-                lds_barrier();                                        // M and the weighted x are in LDS
-                f32x16 inter, intra;
+                SSD_STAMP(3);
+                lds_barrier();                                        // M is in LDS
+                SSD_STAMP(4);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) inter[i] = intra[i] = 0.0f;
 #pragma unroll
@@ -276,61 +388,30 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                         intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, frag(mm_hi, kRowS, tt * 32 + r, ks * 16 + hk), intra, 0, 0, 0);
                         intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, frag(mm_lo, kRowS, tt * 32 + r, ks * 16 + hk), intra, 0, 0, 0);
                     }
-                // inter / intra [4 g + q]: step t = 32 tt + lane % 32, channel p = 32 half + 8 g + 4 (lane / 32) + q
-                if (tok0 + t < L) {
-                    const float e = exp2_hw(cum[buf][t] * kLog2e);
-                    bf16_t *orow = out + ((row0 + tok0 + t) * H + h) * kP + half * 32 + 4 * up;
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        float y[4];
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) y[q] = intra[4 * g + q] + e * inter[4 * g + q];
-                        if constexpr (HAS_Z) {
-                            const uint2 zq = *reinterpret_cast<const uint2 *>(&zt[t * kRowS + half * 32 + 8 * g + 4 * up]);
-                            y[0] *= silu_f32(bf16_lo(zq.x)), y[1] *= silu_f32(bf16_hi(zq.x));
-                            y[2] *= silu_f32(bf16_lo(zq.y)), y[3] *= silu_f32(bf16_hi(zq.y));
-                        }
-                        *reinterpret_cast<uint2 *>(orow + 8 * g) = make_uint2(f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3]));
-                    }
-                }
-                lds_barrier();                                        // the chunk's LDS tiles are free again
-            }
-        }
-    } else {
-        // one chunk; X holds its x pieces, Xn takes those of the next chunk
-        auto walk = [&](int chunk, uint4 (&X)[2], uint4 (&Xn)[2]) {
-            const int64_t tok0 = (int64_t)chunk * kLc;
-            const int buf = (chunk - c_first) & 1;
-            if (tok0 + kLc > L) {                                 // only the last chunk of a row: zero the steps past L
-#pragma unroll
-                for (int i = 0; i < NB; ++i)
-                    if (tok0 + sb0 + i >= L) {
-                        Pb[i] = make_uint4(0, 0, 0, 0);
-                        if constexpr (PASS2) Pc[i] = make_uint4(0, 0, 0, 0);
-                    }
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    if (tok0 + sx0 + i >= L) X[i] = make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if constexpr (NB == 4)
-                    *reinterpret_cast<uint2 *>(&bt[trow(nb0 + k) + sb0]) = make_uint2(pair_el(Pb[0], Pb[1], k), pair_el(Pb[2], Pb[3], k));
-                else
-                    *reinterpret_cast<uint32_t *>(&bt[trow(nb0 + k) + sb0]) = pair_el(Pb[0], Pb[1], k);
-            }
-            if constexpr (PASS2) {
-#pragma unroll
-                for (int i = 0; i < NB; ++i) {
-                    *reinterpret_cast<uint4 *>(&b_rows[(sb0 + i) * kRowN + nb0]) = Pb[i];
-                    *reinterpret_cast<uint4 *>(&c_rows[(sb0 + i) * kRowN + nb0]) = Pc[i];
-                }
-#pragma unroll
-                for (int k = 0; k < 8; ++k) *reinterpret_cast<uint32_t *>(&xt[trow(px0 + k) + sx0]) = pair_el(X[0], X[1], k);
+                // inter / intra [4 g + q]: step t = 32 tt + lane % 32, channel p = 32 half + 8 g + 4 (lane / 32) + q;
+                // what the gate needs leaves LDS now, the arithmetic waits for the next chunk's first phase
+                e_t = exp2_hw(cum[buf][t] * kLog2e);
                 if constexpr (HAS_Z) {
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4 *>(&zt[(sx0 + i) * kRowS + px0]) = i == 0 ? Pz0 : Pz1;
+                    for (int g = 0; g < 4; ++g) zq[g] = *reinterpret_cast<const uint2 *>(&zt[t * kRowS + half * 32 + 8 * g + 4 * up]);
                 }
+                tok_prev = (int64_t)chunk * kLc + t;
+                SSD_STAMP(5);
+                lds_barrier();                                        // the chunk's LDS tiles are free again
+                SSD_STAMP(6);
+            }
+            epilogue();
+        }
+    } else {
+        // one chunk; cur holds its B and x pieces (and takes those of the chunk after the next), nxt the next chunk's
+        auto walk = [&](int chunk, Early &cur, Early &nxt) {
+            const int buf = (chunk - c_first) & 1;
+            if constexpr (PASS2) SSD_STAMP(0);
+            if constexpr (PASS2) {
+#pragma unroll
+                for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4 *>(&b_rows[(sb0 + i) * kRowN + nb0]) = cur.b[i];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) *reinterpret_cast<uint32_t *>(&xt[trow(px0 + k) + sx0]) = pair_el(cur.x[0], cur.x[1], k);
                 // the state at the start of the chunk, as two bf16 terms, for the incoming-state product
 #pragma unroll
                 for (int j = 0; j < PPW; ++j) {
@@ -343,25 +424,15 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                     }
                 }
             }
-            fetch(chunk + 1, Xn);
+            fetch_early(chunk + 2, cur);
+            if constexpr (PASS2) SSD_STAMP(1);
             if constexpr (PASS2) lds_barrier();                   // the raw tiles are in LDS
-            // weighted x for the state update, two bf16 terms: weight_s = exp(s_end - s_s) delta_s
-            const float cend = cum[buf][kLc - 1];
-            const float w0 = exp2_hw((cend - cum[buf][sx0]) * kLog2e) * delta[buf][sx0];
-            const float w1 = exp2_hw((cend - cum[buf][sx0 + 1]) * kLog2e) * delta[buf][sx0 + 1];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const float v0 = piece_el(X[0], k) * w0, v1 = piece_el(X[1], k) * w1;
-                const uint32_t top = f32x2_to_bf16x2(v0, v1);
-                *reinterpret_cast<uint32_t *>(&xw_hi[trow(px0 + k) + sx0]) = top;
-                *reinterpret_cast<uint32_t *>(&xw_lo[trow(px0 + k) + sx0]) = f32x2_to_bf16x2(v0 - bf16_lo(top), v1 - bf16_hi(top));
-            }
-            lds_barrier();                                        // M, the weighted x (and in pass 1 B) are in LDS
+            if constexpr (PASS2) SSD_STAMP(2);
             if (scan_wave && chunk + 1 < c_last) prefix(chunk + 1, dt_next, buf ^ 1);
             dt_next = dt_after;
             dt_after = fetch_dt(chunk + 3);
             // state: acc <- exp(s_end) acc + sum_s bt[n][s] xw[p][s]
-            const float dec = exp2_hw(cend * kLog2e);
+            const float dec = exp2_hw(cum[buf][kLc - 1] * kLog2e);
 #pragma unroll
             for (int j = 0; j < PPW; ++j) {
                 const int id = sw * PPW + j, pt = id & 1, nt = id >> 1;
@@ -374,17 +445,26 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                     acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, tfrag(xw_lo, pt * 32 + r, ks * 16 + hk), acc[j], 0, 0, 0);
                 }
             }
+            if constexpr (PASS2) SSD_STAMP(3);
+            lds_barrier();                                        // the state operands are used up; the next delta sums are in LDS
+            if constexpr (PASS2) SSD_STAMP(4);
+            if (chunk + 1 < c_last) {
+                mask_early(chunk + 1, nxt);
+                park_state_operands(nxt, buf ^ 1);
+            }
+            if constexpr (PASS2) SSD_STAMP(5);
             lds_barrier();                                        // the chunk's LDS tiles are free again
+            if constexpr (PASS2) SSD_STAMP(6);
         };
         for (int chunk = c_first; chunk < c_last; chunk += 2) {
-            walk(chunk, Px[0], Px[1]);
-            if (chunk + 1 < c_last) walk(chunk + 1, Px[1], Px[0]);
+            walk(chunk, E2[0], E2[1]);
+            if (chunk + 1 < c_last) walk(chunk + 1, E2[1], E2[0]);
         }
     }
 
     // end of the segment: pass 1 leaves the local end state and the sum of deltas, pass 2 the final state
     float *dst = nullptr;
-    if (!PASS2) dst = ws_state + (((int64_t)b * (n_seg + 1) + seg + 1) * D + h * kP) * N;
+    if (!PASS2) dst = ws_state + (((int64_t)b * n_slots + seg + 1) * D + h * kP) * N;
     else if (h_final && seg == n_seg - 1) dst = h_final + (b * D + h * kP) * N;
     if (dst && !role_y) {
 #pragma unroll
@@ -399,7 +479,7 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
     if (!PASS2 && scan_wave) {
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) seg_sum += __shfl_xor(seg_sum, off, 64);
-        ws_sumdt[((int64_t)b * (n_seg + 1) + seg) * D + h * kP + lane] = seg_sum;   // kP == 64 lanes
+        ws_sumdt[((int64_t)b * n_slots + seg) * D + h * kP + lane] = seg_sum;   // kP == 64 lanes
     }
 }
 
@@ -461,53 +541,64 @@ ssd_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ par
 
 int64_t chunks_of(int64_t L) { return (L + kLc - 1) / kLc; }
 
-// Segments: about one workgroup per CU (a workgroup holds most of a CU's LDS), never more than chunks.
-void ssd_plan(int64_t batch, int64_t L, int64_t H, int *chunks_per_seg, int *n_seg)
+// Segments.  Pass 2: about one workgroup per CU (a workgroup holds most of a CU's LDS), never more than
+// chunks.  Pass 1 cuts every such segment in two when its length is even: its workgroups are small, and two
+// on a CU hide each other's waits.  chunks1 / n_seg1 describe pass 1 (and the state slots: n_seg1 + 1),
+// chunks2 / n_seg2 pass 2.
+struct SsdPlan {
+    int chunks1, n_seg1, chunks2, n_seg2;
+};
+SsdPlan ssd_plan(int64_t batch, int64_t L, int64_t H)
 {
     const int64_t nc = chunks_of(L);
     int64_t want = 256 / (batch * H > 0 ? batch * H : 1);
     if (want < 1) want = 1;
     if (want > nc) want = nc;
-    const int64_t cps = (nc + want - 1) / want;
-    *chunks_per_seg = (int)cps;
-    *n_seg = (int)((nc + cps - 1) / cps);
+    int64_t cps = (nc + want - 1) / want;
+    if (cps > 1 && cps % 2) ++cps;
+    SsdPlan p;
+    p.chunks2 = (int)cps;
+    p.n_seg2 = (int)((nc + cps - 1) / cps);
+    p.chunks1 = cps % 2 ? (int)cps : (int)(cps / 2);
+    p.n_seg1 = (int)((nc + p.chunks1 - 1) / p.chunks1);
+    return p;
 }
 
 }  // namespace
 
 size_t ssd_workspace_bytes(int64_t batch, int64_t L, int64_t H, int64_t P, int64_t N)
 {
-    int cps, n_seg;
-    ssd_plan(batch, L, H, &cps, &n_seg);
-    const int64_t slots = n_seg + 1, D = H * P;
+    const SsdPlan p = ssd_plan(batch, L, H);
+    const int64_t slots = p.n_seg1 + 1, D = H * P;
     return (size_t)(batch * slots * D * (N + 1) + D * N) * sizeof(float);
 }
 
 hipError_t launch_ssd(const SsdArgs &a, hipStream_t stream)
 {
-    int cps, n_seg;
-    ssd_plan(a.batch, a.L, a.H, &cps, &n_seg);
+    const SsdPlan p = ssd_plan(a.batch, a.L, a.H);
     const int nc = (int)chunks_of(a.L);
+    const int n_slots = p.n_seg1 + 1, slot_step = p.chunks2 / p.chunks1;
     const int64_t D = a.H * a.P;
     float *ws_state = a.ws;
-    float *ws_sumdt = ws_state + (size_t)a.batch * (n_seg + 1) * D * a.N;
-    float *a_rows = ws_sumdt + (size_t)a.batch * (n_seg + 1) * D;
+    float *ws_sumdt = ws_state + (size_t)a.batch * n_slots * D * a.N;
+    float *a_rows = ws_sumdt + (size_t)a.batch * n_slots * D;
     const bf16_t *x = static_cast<const bf16_t *>(a.x), *dt = static_cast<const bf16_t *>(a.dt);
     const bf16_t *Bm = static_cast<const bf16_t *>(a.Bm), *Cm = static_cast<const bf16_t *>(a.Cm);
     const bf16_t *z = static_cast<const bf16_t *>(a.z);
     bf16_t *out = static_cast<bf16_t *>(a.out);
-    dim3 grid((unsigned)n_seg, (unsigned)a.H, (unsigned)a.batch);
-#define MAMBA_SSD(NN, P2, HZ)                                                                                     \
-    ssd_segment<NN, P2, HZ><<<grid, (P2) ? 2 * kThreads : kThreads, 0, stream>>>(x, dt, a.A, Bm, Cm, a.Dskip, z,   \
-        a.dt_bias, ws_state, ws_sumdt, a_rows, out, a.h_final, a.L, a.H, cps, n_seg, nc, a.dt_softplus)
-    if (n_seg > 1) {
+#define MAMBA_SSD(NN, P2, HZ)                                                                                       \
+    ssd_segment<NN, P2, HZ><<<dim3((unsigned)((P2) ? p.n_seg2 : p.n_seg1), (unsigned)a.H, (unsigned)a.batch),        \
+                              (P2) ? 2 * kThreads : kThreads, 0, stream>>>(                                         \
+        x, dt, a.A, Bm, Cm, a.Dskip, z, a.dt_bias, ws_state, ws_sumdt, a_rows, out, a.h_final, a.L, a.H,             \
+        (P2) ? p.chunks2 : p.chunks1, (P2) ? p.n_seg2 : p.n_seg1, n_slots, slot_step, nc, a.dt_softplus)
+    if (p.n_seg1 > 1) {
         if (a.N == 64) MAMBA_SSD(64, false, false);
         else MAMBA_SSD(128, false, false);
-        if (hipError_t e = launch_chunk_carry(a_rows, a.h0, ws_state, ws_sumdt, a.batch, D, a.N, n_seg + 1, stream)) return e;
+        if (hipError_t e = launch_chunk_carry(a_rows, a.h0, ws_state, ws_sumdt, a.batch, D, a.N, n_slots, stream)) return e;
     } else {
         // a single segment starts from h0 itself: slot 0 <- h0 (or zeros)
         for (int64_t b = 0; b < a.batch; ++b)
-            if (hipError_t e = launch_copy_state(a.h0 ? a.h0 + b * D * a.N : nullptr, ws_state + (size_t)b * 2 * D * a.N, D * a.N, stream))
+            if (hipError_t e = launch_copy_state(a.h0 ? a.h0 + b * D * a.N : nullptr, ws_state + (size_t)b * n_slots * D * a.N, D * a.N, stream))
                 return e;
     }
     if (a.N == 64) {
@@ -541,3 +632,10 @@ hipError_t launch_ssd_step(const SsdStepArgs &a, hipStream_t stream)
 }
 
 }  // namespace mamba
+
+#ifdef MAMBA_SSD_TIMING
+extern "C" int mamba2_debug_clock(long long *host)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mamba::g_ssd_clock), sizeof(long long) * 64);
+}
+#endif
