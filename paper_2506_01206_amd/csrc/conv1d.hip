@@ -209,7 +209,9 @@ template <typename T, int VEC, int K> hipError_t launch_conv_k(const ConvArgs &a
     const unsigned gx = (unsigned)((vecs + kBlock - 1) / kBlock);
     // Time tiles: enough workgroups to fill the chip, long enough to amortize the K-1 halo rows.
     // An in-place state update keeps one tile so that a thread reads the state before it writes it.
+    // Short inputs get shorter tiles (down to one group of rows) until there are about two wavefronts per SIMD.
     int64_t tile_len = MAMBA_CONV_TILE;
+    while (tile_len > kRows && (int64_t)gx * ((a.L + tile_len - 1) / tile_len) * a.batch < 2048) tile_len /= 2;
     if (a.state_out && a.state_in == a.state_out) tile_len = a.L;
     if ((a.L + tile_len - 1) / tile_len > 65535) tile_len = (a.L + 65534) / 65535;
     if (tile_len < 1) tile_len = 1;

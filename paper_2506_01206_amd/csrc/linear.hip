@@ -33,6 +33,9 @@ constexpr int kThreads = 256;
 #ifndef MAMBA_LINEAR_MID
 #define MAMBA_LINEAR_MID 512
 #endif
+#ifndef MAMBA_LINEAR_DEEP
+#define MAMBA_LINEAR_DEEP 513
+#endif
 
 struct OutSplit {
     bf16_t *ptr[3];
@@ -215,8 +218,10 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
 // lines; the block then goes through a 4 KiB LDS patch private to the wavefront (16-byte slots
 // xor-swizzled by the row, conflict-free both ways) and comes back as MFMA fragments: lane (r, h)
 // takes the slots 4 h .. 4 h + 3 of row r, one per k16 step.  Both operands use the same slot
-// order, so the sum over k is complete.
-// grid: ceil(N / 32)
+// order, so the sum over k is complete.  (Run over a grid of row blocks for more rows with a long k loop and
+// few output tiles it measured slower than the tiled kernel with 256-deep slabs: x_proj 10.4 vs 10.5 us,
+// out_proj 30 vs 17 us on 2048 tokens.)
+// grid: (ceil(N / 32), ceil(M / (32 MB)))
 __device__ __forceinline__ void wave_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -240,7 +245,7 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;                       // fragment view: row, k half
     const int lrow = lane >> 3, lch = lane & 7;                   // load view: row (+ 8 i), 16-byte slot
-    const int64_t n0 = (int64_t)blockIdx.x * 32;
+    const int64_t n0 = (int64_t)blockIdx.x * 32, m0 = (int64_t)blockIdx.y * (32 * MB);
     const int64_t kchunks = K / 8, kblocks = (K + 63) / 64;
     uint4 *patch_w = reinterpret_cast<uint4 *>(lds + wave * 8192), *patch_x = patch_w + 256;
     const int put = lrow * 8 + (lch ^ lrow);                      // + 64 i: slot of row lrow + 8 i ((lrow + 8 i) & 7 == lrow)
@@ -258,7 +263,7 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
         wptr[i] = reinterpret_cast<const uint4 *>(w + wr * K);
 #pragma unroll
         for (int b = 0; b < MB; ++b) {
-            const int64_t m = b * 32 + lrow + 8 * i;
+            const int64_t m = m0 + b * 32 + lrow + 8 * i;
             xlive[b][i] = m < M;                                  // rows past M stay zero
             xptr[b][i] = reinterpret_cast<const uint4 *>(x + (xlive[b][i] ? m : 0) * K);
         }
@@ -290,7 +295,7 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
 #pragma unroll
         for (int k = 0; k < 3; ++k) t.carried[k] = 0x7fc0;        // NaN unless a valid parent supplies it
         const int o = tid + j * NW * 64, i = o >> 6, l = o & 63;
-        const int64_t m = b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
+        const int64_t m = m0 + b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
         if (m >= M || n >= N) return t;
         if (bias) t.bias = bias[n];
         int64_t col;
@@ -415,7 +420,7 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
 #pragma unroll
             for (int q = 0; q < NW; ++q) v += part[q][i][l];
             if (norm_w) v *= row_scale[8 * (i >> 2) + 4 * (l >> 5) + (i & 3)];
-            const int64_t m = b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
+            const int64_t m = m0 + b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
             if (m >= M || n >= N) continue;
             v = bf16_to_f32(f32_to_bf16(v + t.bias));             // same two roundings as the tiled kernel
             int64_t col;
@@ -462,15 +467,18 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     const bf16_t *res = static_cast<const bf16_t *>(a.residual);
     // few rows: the split-k kernel, except for very wide outputs (the LM head), where the tiled kernel's
     // shared x tile reads less
-    if (a.M <= 64 && (N < 8192 || a.norm_w || a.conv_w)) {
-        const unsigned grid = (unsigned)((N + 31) / 32);
+    const int64_t col_blocks = (N + 31) / 32;
+    const bool few_rows = a.M <= 64 && (N < 8192 || a.norm_w || a.conv_w);
+    if (few_rows) {
         const ConvTail ct{a.conv_w, a.conv_b, static_cast<const bf16_t *>(a.conv_src), static_cast<bf16_t *>(a.conv_dst),
                           a.conv_parent, a.conv_n_in, a.conv_k};
         const bool deep = a.K > 512;                              // more wavefronts share a long k loop
         if (a.M <= 32) {
+            const dim3 grid((unsigned)col_blocks, 1);
             if (deep) linear_skinny_kernel<8, 1><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
             else      linear_skinny_kernel<4, 1><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
         } else {
+            const dim3 grid((unsigned)col_blocks, (unsigned)((a.M + 63) / 64));
             if (deep) linear_skinny_kernel<8, 2><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
             else      linear_skinny_kernel<4, 2><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
         }
@@ -483,6 +491,12 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     } else if (tiles(64, 128) >= MAMBA_LINEAR_MID) {
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 63) / 64));
         linear_kernel<64, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
+    } else if (a.K >= 512 && tiles(64, 64) < MAMBA_LINEAR_DEEP) {
+        // few tiles and a long k loop (x_proj, out_proj on a context of a few thousand tokens): with one or two
+        // workgroups per CU nothing hides the fetch of the next slab, so the slabs are made four times deeper
+        // and the loop four times shorter
+        dim3 grid((unsigned)((N + 63) / 64), (unsigned)((a.M + 63) / 64));
+        linear_kernel<64, 64, 256><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
     } else {
         dim3 grid((unsigned)((N + 63) / 64), (unsigned)((a.M + 63) / 64));
         linear_kernel<64, 64, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
