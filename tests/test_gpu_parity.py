@@ -920,7 +920,7 @@ def ssd_case(rng, B, L, H, P, N, io):
 
 
 @pytest.mark.parametrize("B,L,H,N", [(1, 64, 2, 64), (2, 200, 3, 128), (1, 1, 1, 128), (1, 63, 2, 64), (1, 65, 2, 128),
-                                     (1, 1000, 24, 128)])
+                                     (1, 1000, 24, 128), (2, 500, 64, 64), (1, 330, 100, 128)])
 def test_ssd_scan_against_oracle(m, B, L, H, N):
     """Chunked scalar-decay scan on the matrix cores against the plain float64 recurrence: outputs and final
     state, with and without gate / skip / initial state, and in two pieces with the state carried."""
@@ -949,6 +949,27 @@ def test_ssd_scan_against_oracle(m, B, L, H, N):
                                   g["Dskip"], sl(g["z"], cut, L), g["dt_bias"], h1)
         assert_close(values(to_host(torch.cat([o1, o2], 1))), ro, tol, "ssd pieces out")
         assert_close(to_host(h2), rh, tol, "ssd pieces state")
+
+
+def test_ssd_scan_at_bench_size_sampled_heads(m):
+    """The scan at the size and launch configuration bench.py times (32768 tokens, 24 heads, 128 states: ten
+    segments per head in the output pass, twenty in the state pass).  Heads are independent, so the oracle runs
+    on two sampled heads only and is compared with the same heads of the full-size result."""
+    from oracle import ssd
+    B, L, H, P, N = 1, 32768, 24, 64, 128
+    say(B=B, L=L, H=H, N=N)
+    rng = np.random.default_rng(5)
+    c = ssd_case(rng, B, L, H, P, N, synth.BF16)
+    g = {k: to_dev(v) for k, v in c.items()}
+    out, hf = m.mamba2_ssd_fwd(g["x"], g["dt"], g["A"], g["Bm"], g["Cm"], g["Dskip"], g["z"], g["dt_bias"], g["h0"])
+    out, hf = values(to_host(out)), to_host(hf)
+    tol = TOL[synth.BF16]
+    w = {k: W(v) for k, v in c.items()}
+    for h in (3, 23):
+        ro, rh = ssd.ssd_scan(w["x"][:, :, h:h + 1], w["dt"][:, :, h:h + 1], w["A"][h:h + 1], w["Bm"], w["Cm"], w["Dskip"][h:h + 1],
+                              w["z"][:, :, h:h + 1], w["dt_bias"][h:h + 1], w["h0"][:, h:h + 1])
+        assert_close(out[:, :, h:h + 1], ro, tol, "ssd out, head %d" % h)
+        assert_close(hf[:, h:h + 1], rh, tol, "ssd final state, head %d" % h)
 
 
 @pytest.mark.parametrize("io", [synth.F32, synth.BF16])
