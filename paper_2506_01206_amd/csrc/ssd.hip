@@ -64,7 +64,7 @@ __device__ __forceinline__ void lds_barrier()
 
 #ifdef MAMBA_SSD_TIMING
 // tuning builds only: shader clock at the phase boundaries of one chunk of one workgroup, per wavefront
-__device__ long long g_ssd_clock[8][8];
+__device__ long long g_ssd_clock[8][16];
 #define SSD_STAMP(i)                                                                                       \
     do {                                                                                                   \
         if (blockIdx.x == 3 && blockIdx.y == 1 && chunk == c_first + 6 && lane == 0)                       \
@@ -348,13 +348,23 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                         ds[g] = delta4[buf][half * 8 + 2 * g + up];
                     }
                     const float ct = cum[buf][t];
+                    SSD_STAMP(8);
                     f32x16 gacc;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) gacc[i] = 0.0f;
+                    {
+                        // all fragments are requested before the first product, so that the products do not
+                        // each wait out an LDS round trip
+                        bf16x8 bf[N / 16], cf[N / 16];
 #pragma unroll
-                    for (int ks = 0; ks < N / 16; ++ks)
-                        gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(b_rows, kRowN, half * 32 + r, ks * 16 + hk),
-                                                                       frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk), gacc, 0, 0, 0);
+                        for (int ks = 0; ks < N / 16; ++ks) {
+                            bf[ks] = frag(b_rows, kRowN, half * 32 + r, ks * 16 + hk);
+                            cf[ks] = frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk);
+                        }
+#pragma unroll
+                        for (int ks = 0; ks < N / 16; ++ks) gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ks], cf[ks], gacc, 0, 0, 0);
+                    }
+                    SSD_STAMP(9);
                     // gacc[4 g + q] = C_t . B_s, t = 32 tt + lane % 32, s = 32 half + 8 g + 4 (lane / 32) + q
                     // M = G * exp(s_t - s_s) * delta_s for s <= t (steps past L have delta = 0), + D on the diagonal
 #pragma unroll
@@ -375,19 +385,37 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                 SSD_STAMP(4);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) inter[i] = intra[i] = 0.0f;
+                {
+                    // C with the incoming state, then M (with D) with x (M is zero right of the diagonal block);
+                    // again the fragments of a product are requested before it starts
+                    bf16x8 cf[N / 16], hh[N / 16], hl[N / 16], xf[kLc / 16], mh[kLc / 16], ml[kLc / 16];
 #pragma unroll
-                for (int ks = 0; ks < N / 16; ++ks) {                 // C with the incoming state
-                    const bf16x8 cf = frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk);
-                    inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h_hi, kRowN, half * 32 + r, ks * 16 + hk), cf, inter, 0, 0, 0);
-                    inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h_lo, kRowN, half * 32 + r, ks * 16 + hk), cf, inter, 0, 0, 0);
-                }
-#pragma unroll
-                for (int ks = 0; ks < kLc / 16; ++ks)                 // M (with D) with x
-                    if (ks < 2 * (tt + 1)) {                          // M is zero right of the diagonal block
-                        const bf16x8 xf = tfrag(xt, half * 32 + r, ks * 16 + hk);
-                        intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, frag(mm_hi, kRowS, tt * 32 + r, ks * 16 + hk), intra, 0, 0, 0);
-                        intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, frag(mm_lo, kRowS, tt * 32 + r, ks * 16 + hk), intra, 0, 0, 0);
+                    for (int ks = 0; ks < N / 16; ++ks) {
+                        cf[ks] = frag(c_rows, kRowN, tt * 32 + r, ks * 16 + hk);
+                        hh[ks] = frag(h_hi, kRowN, half * 32 + r, ks * 16 + hk);
                     }
+#pragma unroll
+                    for (int ks = 0; ks < N / 16; ++ks) hl[ks] = frag(h_lo, kRowN, half * 32 + r, ks * 16 + hk);
+#pragma unroll
+                    for (int ks = 0; ks < N / 16; ++ks) inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hh[ks], cf[ks], inter, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int ks = 0; ks < kLc / 16; ++ks)
+                        if (ks < 2 * (tt + 1)) {
+                            xf[ks] = tfrag(xt, half * 32 + r, ks * 16 + hk);
+                            mh[ks] = frag(mm_hi, kRowS, tt * 32 + r, ks * 16 + hk);
+                            ml[ks] = frag(mm_lo, kRowS, tt * 32 + r, ks * 16 + hk);
+                        }
+#pragma unroll
+                    for (int ks = 0; ks < N / 16; ++ks) inter = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hl[ks], cf[ks], inter, 0, 0, 0);
+#pragma unroll
+                    for (int ks = 0; ks < kLc / 16; ++ks)
+                        if (ks < 2 * (tt + 1)) {
+                            intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[ks], mh[ks], intra, 0, 0, 0);
+                            intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[ks], ml[ks], intra, 0, 0, 0);
+                        }
+                }
+                SSD_STAMP(10);
                 // inter / intra [4 g + q]: step t = 32 tt + lane % 32, channel p = 32 half + 8 g + 4 (lane / 32) + q;
                 // what the gate needs leaves LDS now, the arithmetic waits for the next chunk's first phase
                 e_t = exp2_hw(cum[buf][t] * kLog2e);
@@ -431,6 +459,7 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
             if (scan_wave && chunk + 1 < c_last) prefix(chunk + 1, dt_next, buf ^ 1);
             dt_next = dt_after;
             dt_after = fetch_dt(chunk + 3);
+            if constexpr (PASS2) SSD_STAMP(8);
             // state: acc <- exp(s_end) acc + sum_s bt[n][s] xw[p][s]
             const float dec = exp2_hw(cum[buf][kLc - 1] * kLog2e);
 #pragma unroll
@@ -636,6 +665,6 @@ hipError_t launch_ssd_step(const SsdStepArgs &a, hipStream_t stream)
 #ifdef MAMBA_SSD_TIMING
 extern "C" int mamba2_debug_clock(long long *host)
 {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mamba::g_ssd_clock), sizeof(long long) * 64);
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mamba::g_ssd_clock), sizeof(long long) * 128);
 }
 #endif
