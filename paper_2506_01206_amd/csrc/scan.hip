@@ -9,7 +9,7 @@
 // C_t are the same for all channels of a batch row: they are staged through LDS as float32 and
 // read back with wave-uniform (broadcast) loads.  The recurrence is elementwise: 4 VALU
 // operations and one hardware exp2 per state update, no matrix product anywhere, and it is this
-// instruction stream (the exp2 issues at a quarter of the FMA rate), not HBM, that bounds it.
+// instruction stream (the exp2 issues at half the FMA rate), not HBM, that bounds it.
 //
 // Time chunking.  A batch row offers only D / (64 CPL) wavefronts, far fewer than the 1024
 // SIMDs of the chip, so long sequences are cut into n_chunks time chunks that run in parallel:
