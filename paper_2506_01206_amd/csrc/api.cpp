@@ -256,6 +256,7 @@ namespace {
 struct BlockBuffers {
     char *a, *b, *c, *d;        // four (rows, d_inner) bf16 buffers: x then dt | z | x_c | normed then y
     char *dtl, *bm, *cm;        // (rows, dt_rank), (rows, d_state), (rows, d_state) bf16
+    char *xpart;                // one token on up to 64 rows: (rows, dt_rank + 2 d_state, d_inner / 32) float32 partial sums
     char *scan_ws;
     size_t scan_ws_bytes, total;
 };
@@ -278,6 +279,9 @@ bool block_layout(const mamba_block_params_t *p, int64_t batch, int64_t L, void 
     auto take = [&](int64_t n) { char *r = q + off; off += align256(n); return r; };
     bb->a = take(big); bb->b = take(big); bb->c = take(big); bb->d = take(big);
     bb->dtl = take(dtl); bb->bm = take(bc); bb->cm = take(bc);
+    int64_t xp = 0;
+    if (L == 1 && rows <= 64 && !size3(p->d_inner / 32 + 1, rows, p->dt_rank + 2 * p->d_state, 4, &xp)) return false;
+    bb->xpart = take(xp);
     bb->scan_ws = take((int64_t)sws);
     bb->scan_ws_bytes = sws;
     bb->total = (size_t)off;
@@ -401,12 +405,27 @@ int mamba_block_step(const mamba_block_params_t *p, const void *hidden, void *hi
         in.conv_parent = parent_idx;
         in.conv_n_in = n_in;
         in.conv_k = p->d_conv;
+        // With a wide enough model the x projection rides along as well: every in_proj workgroup multiplies its 32
+        // finished x_c columns into it and the state step adds the partial sums up, which takes the launch of a
+        // product with three output tiles out of the chain.
+        const bool fuse_xproj = p->d_model > 512 && Di % 128 == 0 && R + 2 * N <= 256;
+        if (fuse_xproj) {
+            in.xproj_w = p->x_proj_w;
+            in.xproj_part = reinterpret_cast<float *>(bb.xpart);
+            in.xproj_n = (int)(R + 2 * N);
+        }
         if (hipError_t e = launch_linear(in, stream)) return (int)e;
-        if ((rc = mamba_linear_fwd(bb.c, p->x_proj_w, nullptr, nullptr, bb.dtl, R, bb.bm, N, bb.cm, N, n_out, Di, io, hip_stream))) return rc;
+        if (!fuse_xproj &&
+            (rc = mamba_linear_fwd(bb.c, p->x_proj_w, nullptr, nullptr, bb.dtl, R, bb.bm, N, bb.cm, N, n_out, Di, io, hip_stream)))
+            return rc;
         StepArgs sa{ssm_dst, ssm_src, parent_idx, bb.c, bb.dtl, bb.bm, bb.cm, bb.b, p->A, p->Dskip, p->dt_bias, bb.d,
                     n_out, n_in, Di, (int)N, kIoBf16, 1};
         sa.dt_w = p->dt_proj_w;
         sa.dt_rank = R;
+        if (fuse_xproj) {
+            sa.xpart = reinterpret_cast<const float *>(bb.xpart);
+            sa.n_parts = (int)(Di / 32);
+        }
         if (hipError_t e = launch_step(sa, stream)) return (int)e;
         return mamba_linear_fwd(bb.d, p->out_proj_w, nullptr, hidden, hidden_out, p->d_model, nullptr, 0, nullptr, 0, n_out, Di, io, hip_stream);
     }

@@ -86,6 +86,11 @@ struct StepArgs {
     // (n_out, dt_rank) tensor and delta_raw[j,d] = sum_r dt[j,r] dt_w[d,r]  (bf16 I/O only, dt_rank % 4 == 0)
     const void *dt_w = nullptr;
     int64_t dt_rank = 0;
+    // with xpart ((n_out, dt_rank + 2 N, n_parts) float32 partial sums of the x projection, n_parts % 4 == 0) the
+    // kernel adds the parts up itself and takes dt (low rank), Bm and Cm from the sums, rounded to bf16 as the stored tensors
+    // would be; dt, Bm, Cm are then not read (needs dt_w, dt_rank + 2 N <= 256)
+    const float *xpart = nullptr;
+    int n_parts = 0;
 };
 hipError_t launch_step(const StepArgs &a, hipStream_t stream);
 
@@ -124,6 +129,13 @@ struct LinearArgs {
     const int32_t *conv_parent = nullptr;
     int64_t conv_n_in = 0;
     int conv_k = 0;
+    // with xproj_w (xproj_n, width[0]) bf16 every workgroup also multiplies its 32 finished columns of the first
+    // output tensor (as stored, i.e. after the conv step) into the next projection and leaves the partial sums in
+    // xproj_part[(row, j, column block)] (float32, (M, xproj_n, width[0] / 32)); whoever consumes them adds the
+    // column blocks up in order.  (M <= 64, K > 512 and width[0] % 32 == 0 only.)
+    const void *xproj_w = nullptr;
+    float *xproj_part = nullptr;
+    int xproj_n = 0;
 };
 hipError_t launch_linear(const LinearArgs &a, hipStream_t stream);
 

@@ -52,6 +52,14 @@ struct ConvTail {
     int k;
 };
 
+// the next projection applied to the first output tensor on its way out, as partial sums per column block
+struct XprojTail {
+    const bf16_t *w;            // (n, ldw) bf16; nullptr: off
+    float *part;                // (M, n, column blocks of the first output tensor)
+    int n;
+    int64_t ldw;                // row length of w = width of the first output tensor
+};
+
 // column n of the virtual (M, N) output -> tensor and column inside it
 __device__ __forceinline__ int locate(const OutSplit &o, int64_t n, int64_t *col)
 {
@@ -233,7 +241,7 @@ template <int NW, int MB>
 __global__ void __launch_bounds__(NW * 64)
 linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const float *__restrict__ bias,
                      const bf16_t *residual, OutSplit out, int64_t M, int64_t N, int64_t K,
-                     const float *__restrict__ norm_w, float eps, ConvTail conv)
+                     const float *__restrict__ norm_w, float eps, ConvTail conv, XprojTail xp)
 {
     // LDS: in the main loop two 4 KiB patches per wavefront (w block, x block); afterwards the same
     // memory holds the partial tiles, the sums of x^2 (with norm_w) and the row factors
@@ -242,6 +250,10 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
     float (*ssq)[MB][4][64] = reinterpret_cast<float (*)[MB][4][64]>(lds + NW * 4096);
     float *row_scale = reinterpret_cast<float *>(lds + NW * 4096 + NW * MB * 1024);
     static_assert(NW * 4096 + NW * MB * 1024 + 128 <= NW * 8192, "LDS reuse");
+    // with eight wavefronts there is room for the finished columns of the first output (float32), which the
+    // projection tail multiplies on
+    constexpr bool kTailRoom = NW * 4096 + NW * MB * 1024 + 128 + MB * 4096 <= NW * 8192;
+    float (*xc)[32][32] = reinterpret_cast<float (*)[32][32]>(lds + NW * 4096 + NW * MB * 1024 + 128);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;                       // fragment view: row, k half
     const int lrow = lane >> 3, lch = lane & 7;                   // load view: row (+ 8 i), 16-byte slot
@@ -316,6 +328,16 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
         }
         return t;
     };
+    // projection tail: thread (group g, output j) of NW * 64 / n groups takes rows g, g + groups, ... of the
+    // block; its 32 weights are fetched here, ahead of the main loop
+    uint4 xw4[4] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+    const bool tail_on = kTailRoom && xp.w && n0 < out.width[0];  // uniform: a column block lies in one output tensor
+    const int tail_groups = tail_on ? (NW * 64) / xp.n : 0, tail_g = tail_on ? tid / xp.n : 0, tail_j = tail_on ? tid - tail_g * xp.n : 0;
+    if (tail_on && tail_g < tail_groups) {
+        const uint4 *wr = reinterpret_cast<const uint4 *>(xp.w + (int64_t)tail_j * xp.ldw + n0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) xw4[c] = wr[c];
+    }
     Tail early[OPT];
     if constexpr (MB == 1) {
 #pragma unroll
@@ -447,7 +469,35 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
                 if (H > 0) nwin[H - 1] = (bf16_t)f32_to_bf16(v);
                 v = silu_f32(a);
             }
-            out.ptr[sp][off] = (bf16_t)f32_to_bf16(v);
+            const uint32_t stored = f32_to_bf16(v);
+            out.ptr[sp][off] = (bf16_t)stored;
+            if constexpr (kTailRoom) {
+                if (xp.w && sp == 0) xc[b][8 * (i >> 2) + 4 * (l >> 5) + (i & 3)][l & 31] = bf16_to_f32(stored);
+            }
+        }
+    }
+    if constexpr (kTailRoom) {
+        if (tail_on) {
+            __syncthreads();
+            const int rows = (int)((M - m0 < 32 * MB) ? M - m0 : 32 * MB);
+            for (int ml = tail_g; ml < rows && tail_g < tail_groups; ml += tail_groups) {
+                const int j = tail_j;
+                const float *xr = xc[ml >> 5][ml & 31];
+                float acc = 0.0f;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint4 q = xw4[c];
+                    acc = fmaf(xr[8 * c + 0], bf16_lo(q.x), acc);
+                    acc = fmaf(xr[8 * c + 1], bf16_hi(q.x), acc);
+                    acc = fmaf(xr[8 * c + 2], bf16_lo(q.y), acc);
+                    acc = fmaf(xr[8 * c + 3], bf16_hi(q.y), acc);
+                    acc = fmaf(xr[8 * c + 4], bf16_lo(q.z), acc);
+                    acc = fmaf(xr[8 * c + 5], bf16_hi(q.z), acc);
+                    acc = fmaf(xr[8 * c + 6], bf16_lo(q.w), acc);
+                    acc = fmaf(xr[8 * c + 7], bf16_hi(q.w), acc);
+                }
+                xp.part[((m0 + ml) * xp.n + j) * (xp.ldw / 32) + blockIdx.x] = acc;
+            }
         }
     }
 }
@@ -473,14 +523,15 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
         const ConvTail ct{a.conv_w, a.conv_b, static_cast<const bf16_t *>(a.conv_src), static_cast<bf16_t *>(a.conv_dst),
                           a.conv_parent, a.conv_n_in, a.conv_k};
         const bool deep = a.K > 512;                              // more wavefronts share a long k loop
+        const XprojTail xt{deep ? static_cast<const bf16_t *>(a.xproj_w) : nullptr, a.xproj_part, a.xproj_n, a.width[0]};
         if (a.M <= 32) {
             const dim3 grid((unsigned)col_blocks, 1);
-            if (deep) linear_skinny_kernel<8, 1><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
-            else      linear_skinny_kernel<4, 1><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
+            if (deep) linear_skinny_kernel<8, 1><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct, xt);
+            else      linear_skinny_kernel<4, 1><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct, xt);
         } else {
             const dim3 grid((unsigned)col_blocks, (unsigned)((a.M + 63) / 64));
-            if (deep) linear_skinny_kernel<8, 2><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
-            else      linear_skinny_kernel<4, 2><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct);
+            if (deep) linear_skinny_kernel<8, 2><<<grid, 512, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct, xt);
+            else      linear_skinny_kernel<4, 2><<<grid, 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, a.norm_w, a.eps, ct, xt);
         }
         return hipGetLastError();
     }

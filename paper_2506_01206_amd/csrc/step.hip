@@ -55,48 +55,65 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
                   const T *__restrict__ Bm, const T *__restrict__ Cm,
                   const float *__restrict__ Dskip, const T *__restrict__ z,
                   const float *__restrict__ dt_bias, T *__restrict__ out, int64_t n_in, int64_t D,
-                  const bf16_t *__restrict__ dt_w, int64_t dt_rank)
+                  const bf16_t *__restrict__ dt_w, int64_t dt_rank, const float *__restrict__ xpart, int n_parts)
 {
     constexpr int Q = N / 4;
+    constexpr int CW = 4;                                         // dt_w pieces a lane can hold ahead of the x projection sums
     const int64_t j = blockIdx.y;
     const int64_t row4 = D * Q;  // float4s per branch
     const float4 *a4 = reinterpret_cast<const float4 *>(A);
+    __shared__ __attribute__((aligned(16))) float xs[256];
+    const bool fused_dt = sizeof(T) == 2 && dt_w;
+    const bool hold_w = xpart && dt_rank / 4 <= CW * Q;
 
     int64_t f[U], d[U];
+    int q[U];
     bool live[U];
     float4 h[U], a[U], bv[U], cv[U];
     float xv[U], dv[U], zv[U], bias[U], dsk[U];
+    uint2 wq[U][CW];
+    // everything that does not depend on the x projection is requested first
 #pragma unroll
     for (int i = 0; i < U; ++i) {
         const int64_t f_raw = ((int64_t)blockIdx.x * U + i) * kBlock + threadIdx.x;
         live[i] = f_raw < row4;
         f[i] = live[i] ? f_raw : row4 - 1;
         d[i] = f[i] / Q;
-        const int q = (int)(f[i] - d[i] * Q);
+        q[i] = (int)(f[i] - d[i] * Q);
         a[i] = a4[f[i]];
-        bv[i] = ld4_io<N>(Bm + j * N + 4 * q);
-        cv[i] = ld4_io<N>(Cm + j * N + 4 * q);
         xv[i] = ld_io(x, j * D + d[i]);
-        if (sizeof(T) == 2 && dt_w) {
-            // dt projection fused in: the Q lanes of a channel share the dt_rank products (4 at a time)
-            const uint2 *wrow = reinterpret_cast<const uint2 *>(dt_w + d[i] * dt_rank);
-            const uint2 *lrow = reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(dt) + j * dt_rank);
-            float acc = 0.0f;
-#pragma unroll 4
-            for (int64_t c = q; c < dt_rank / 4; c += Q) {
-                const uint2 a2 = wrow[c], b2 = lrow[c];
-                acc = fmaf(bf16_lo(a2.x), bf16_lo(b2.x), acc);
-                acc = fmaf(bf16_hi(a2.x), bf16_hi(b2.x), acc);
-                acc = fmaf(bf16_lo(a2.y), bf16_lo(b2.y), acc);
-                acc = fmaf(bf16_hi(a2.y), bf16_hi(b2.y), acc);
-            }
-            dv[i] = bf16_to_f32(f32_to_bf16(channel_sum<Q>(acc)));     // rounded like the stored tensor it replaces
-        } else {
-            dv[i] = ld_io(dt, j * D + d[i]);
-        }
         zv[i] = HAS_Z ? ld_io(z, j * D + d[i]) : 0.0f;
         bias[i] = dt_bias ? dt_bias[d[i]] : 0.0f;
         dsk[i] = Dskip ? Dskip[d[i]] : 0.0f;
+#pragma unroll
+        for (int c = 0; c < CW; ++c) wq[i][c] = make_uint2(0, 0);
+        if (hold_w) {
+            const uint2 *wrow = reinterpret_cast<const uint2 *>(dt_w + d[i] * dt_rank);
+#pragma unroll
+            for (int c = 0; c < CW; ++c)
+                if (q[i] + c * Q < dt_rank / 4) wq[i][c] = wrow[q[i] + c * Q];
+        }
+        if (!xpart) {
+            bv[i] = ld4_io<N>(Bm + j * N + 4 * q[i]);
+            cv[i] = ld4_io<N>(Cm + j * N + 4 * q[i]);
+            if (fused_dt) {
+                // dt projection fused in: the Q lanes of a channel share the dt_rank products (4 at a time)
+                const uint2 *wrow = reinterpret_cast<const uint2 *>(dt_w + d[i] * dt_rank);
+                const uint2 *lrow = reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(dt) + j * dt_rank);
+                float acc = 0.0f;
+#pragma unroll 4
+                for (int64_t c = q[i]; c < dt_rank / 4; c += Q) {
+                    const uint2 a2 = wrow[c], b2 = lrow[c];
+                    acc = fmaf(bf16_lo(a2.x), bf16_lo(b2.x), acc);
+                    acc = fmaf(bf16_hi(a2.x), bf16_hi(b2.x), acc);
+                    acc = fmaf(bf16_lo(a2.y), bf16_lo(b2.y), acc);
+                    acc = fmaf(bf16_hi(a2.y), bf16_hi(b2.y), acc);
+                }
+                dv[i] = bf16_to_f32(f32_to_bf16(channel_sum<Q>(acc)));     // rounded like the stored tensor it replaces
+            } else {
+                dv[i] = ld_io(dt, j * D + d[i]);
+            }
+        }
     }
     // the state row is the only load that has to wait for the parent index
     const int64_t p = parent ? (int64_t)parent[j] : j;
@@ -104,6 +121,56 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
     const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
 #pragma unroll
     for (int i = 0; i < U; ++i) h[i] = hin4[f[i]];
+    // With xpart the branch's row of the x projection (dt low rank | B | C) arrives as n_parts partial sums:
+    // they are added up in order and rounded to bf16, as the stored tensors they replace would have been.
+    if (xpart) {
+        const int xn = (int)dt_rank + 2 * N;
+        for (int k = threadIdx.x; k < xn; k += kBlock) {
+            // the parts of one sum lie side by side (n_parts % 4 == 0): four 16-byte loads in flight at a time
+            const float4 *pr = reinterpret_cast<const float4 *>(xpart + (j * xn + k) * n_parts);
+            float sum = 0.0f;
+            for (int c = 0; c < n_parts / 4; c += 4) {
+                float4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = pr[min(c + u, n_parts / 4 - 1)];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (c + u < n_parts / 4) sum = (((sum + v[u].x) + v[u].y) + v[u].z) + v[u].w;
+            }
+            xs[k] = bf16_to_f32(f32_to_bf16(sum));
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            bv[i] = *reinterpret_cast<const float4 *>(&xs[dt_rank + 4 * q[i]]);
+            cv[i] = *reinterpret_cast<const float4 *>(&xs[dt_rank + N + 4 * q[i]]);
+            float acc = 0.0f;
+            if (hold_w) {
+#pragma unroll
+                for (int c = 0; c < CW; ++c) {
+                    const int cc = q[i] + c * Q;
+                    if (cc < dt_rank / 4) {
+                        const float4 b4 = *reinterpret_cast<const float4 *>(&xs[4 * cc]);
+                        acc = fmaf(bf16_lo(wq[i][c].x), b4.x, acc);
+                        acc = fmaf(bf16_hi(wq[i][c].x), b4.y, acc);
+                        acc = fmaf(bf16_lo(wq[i][c].y), b4.z, acc);
+                        acc = fmaf(bf16_hi(wq[i][c].y), b4.w, acc);
+                    }
+                }
+            } else {
+                const uint2 *wrow = reinterpret_cast<const uint2 *>(dt_w + d[i] * dt_rank);
+                for (int64_t c = q[i]; c < dt_rank / 4; c += Q) {
+                    const uint2 a2 = wrow[c];
+                    const float4 b4 = *reinterpret_cast<const float4 *>(&xs[4 * c]);
+                    acc = fmaf(bf16_lo(a2.x), b4.x, acc);
+                    acc = fmaf(bf16_hi(a2.x), b4.y, acc);
+                    acc = fmaf(bf16_lo(a2.y), b4.z, acc);
+                    acc = fmaf(bf16_hi(a2.y), b4.w, acc);
+                }
+            }
+            dv[i] = bf16_to_f32(f32_to_bf16(channel_sum<Q>(acc)));
+        }
+    }
 #pragma unroll
     for (int i = 0; i < U; ++i) {
         const float v = dv[i] + bias[i];
@@ -127,7 +194,7 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
         }
         if (live[i]) {
             reinterpret_cast<float4 *>(h_out)[j * row4 + f[i]] = hh;
-            if (f[i] - d[i] * Q == 0) {
+            if (q[i] == 0) {
                 y = fmaf(dsk[i], xv[i], y);
                 if constexpr (HAS_Z) y *= silu_f32(zv[i]);
                 st_io(out, j * D + d[i], y);
@@ -146,7 +213,7 @@ template <typename T, int N, int U> hipError_t launch_step_u(const StepArgs &a, 
         a.h_out, a.h_in, a.parent, static_cast<const T *>(a.x), static_cast<const T *>(a.dt), a.A, \
         static_cast<const T *>(a.Bm), static_cast<const T *>(a.Cm), a.Dskip,                      \
         static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D,                \
-        static_cast<const bf16_t *>(a.dt_w), a.dt_rank)
+        static_cast<const bf16_t *>(a.dt_w), a.dt_rank, a.dt_w ? a.xpart : nullptr, a.n_parts)
     if (a.z) {
         if (a.dt_softplus) MAMBA_STEP(true, true);
         else MAMBA_STEP(true, false);
