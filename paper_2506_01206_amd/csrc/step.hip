@@ -55,6 +55,102 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
                   const T *__restrict__ Bm, const T *__restrict__ Cm,
                   const float *__restrict__ Dskip, const T *__restrict__ z,
                   const float *__restrict__ dt_bias, T *__restrict__ out, int64_t n_in, int64_t D,
+                  const bf16_t *__restrict__ dt_w, int64_t dt_rank)
+{
+    constexpr int Q = N / 4;
+    const int64_t j = blockIdx.y;
+    const int64_t row4 = D * Q;  // float4s per branch
+    const float4 *a4 = reinterpret_cast<const float4 *>(A);
+
+    int64_t f[U], d[U];
+    bool live[U];
+    float4 h[U], a[U], bv[U], cv[U];
+    float xv[U], dv[U], zv[U], bias[U], dsk[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const int64_t f_raw = ((int64_t)blockIdx.x * U + i) * kBlock + threadIdx.x;
+        live[i] = f_raw < row4;
+        f[i] = live[i] ? f_raw : row4 - 1;
+        d[i] = f[i] / Q;
+        const int q = (int)(f[i] - d[i] * Q);
+        a[i] = a4[f[i]];
+        bv[i] = ld4_io<N>(Bm + j * N + 4 * q);
+        cv[i] = ld4_io<N>(Cm + j * N + 4 * q);
+        xv[i] = ld_io(x, j * D + d[i]);
+        if (sizeof(T) == 2 && dt_w) {
+            // dt projection fused in: the Q lanes of a channel share the dt_rank products (4 at a time)
+            const uint2 *wrow = reinterpret_cast<const uint2 *>(dt_w + d[i] * dt_rank);
+            const uint2 *lrow = reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(dt) + j * dt_rank);
+            float acc = 0.0f;
+#pragma unroll 4
+            for (int64_t c = q; c < dt_rank / 4; c += Q) {
+                const uint2 a2 = wrow[c], b2 = lrow[c];
+                acc = fmaf(bf16_lo(a2.x), bf16_lo(b2.x), acc);
+                acc = fmaf(bf16_hi(a2.x), bf16_hi(b2.x), acc);
+                acc = fmaf(bf16_lo(a2.y), bf16_lo(b2.y), acc);
+                acc = fmaf(bf16_hi(a2.y), bf16_hi(b2.y), acc);
+            }
+            dv[i] = bf16_to_f32(f32_to_bf16(channel_sum<Q>(acc)));     // rounded like the stored tensor it replaces
+        } else {
+            dv[i] = ld_io(dt, j * D + d[i]);
+        }
+        zv[i] = HAS_Z ? ld_io(z, j * D + d[i]) : 0.0f;
+        bias[i] = dt_bias ? dt_bias[d[i]] : 0.0f;
+        dsk[i] = Dskip ? Dskip[d[i]] : 0.0f;
+    }
+    // the state row is the only load that has to wait for the parent index
+    const int64_t p = parent ? (int64_t)parent[j] : j;
+    const bool p_ok = p >= 0 && p < n_in;
+    const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
+#pragma unroll
+    for (int i = 0; i < U; ++i) h[i] = hin4[f[i]];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const float v = dv[i] + bias[i];
+        const float delta = SOFTPLUS ? softplus_f32(v) : v;
+        const float u = delta * xv[i];
+        const float dl = delta * kLog2e;
+        float4 hh = h[i];
+        hh.x = fmaf(exp2_hw(dl * a[i].x), hh.x, u * bv[i].x);
+        hh.y = fmaf(exp2_hw(dl * a[i].y), hh.y, u * bv[i].y);
+        hh.z = fmaf(exp2_hw(dl * a[i].z), hh.z, u * bv[i].z);
+        hh.w = fmaf(exp2_hw(dl * a[i].w), hh.w, u * bv[i].w);
+        float y = hh.x * cv[i].x;
+        y = fmaf(hh.y, cv[i].y, y);
+        y = fmaf(hh.z, cv[i].z, y);
+        y = fmaf(hh.w, cv[i].w, y);
+        y = channel_sum<Q>(y);
+        if (!p_ok) {
+            const float nan = __int_as_float(0x7fc00000);
+            hh = make_float4(nan, nan, nan, nan);
+            y = nan;
+        }
+        if (live[i]) {
+            reinterpret_cast<float4 *>(h_out)[j * row4 + f[i]] = hh;
+            if (f[i] - d[i] * Q == 0) {
+                y = fmaf(dsk[i], xv[i], y);
+                if constexpr (HAS_Z) y *= silu_f32(zv[i]);
+                st_io(out, j * D + d[i], y);
+            }
+        }
+    }
+}
+
+// The same step for a draft position of the whole block, where the x projection arrives as partial sums (see
+// StepArgs::xpart): what does not depend on it (the state row above all) is requested first, then the parts are
+// added up, and dt (through the fused dt projection), B and C come out of LDS.  Kept apart from the plain kernel,
+// which stays as lean as it was.
+// grid: (ceil(D * N / 4 / (256 * U)), n_out).  A lane owns U float4s of the branch's (D, N) state,
+// 256 float4s apart, so every wavefront load or store is still one contiguous 1 KiB run; all
+// loads of the U pieces are issued before the first one is used, which keeps several KiB per
+// wavefront in flight (the step is a single pass over the state and lives on memory latency).
+template <typename T, int N, int U, bool HAS_Z, bool SOFTPLUS>
+__global__ void __launch_bounds__(kBlock)
+state_step_xproj_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ parent,
+                  const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
+                  const T *__restrict__ Bm, const T *__restrict__ Cm,
+                  const float *__restrict__ Dskip, const T *__restrict__ z,
+                  const float *__restrict__ dt_bias, T *__restrict__ out, int64_t n_in, int64_t D,
                   const bf16_t *__restrict__ dt_w, int64_t dt_rank, const float *__restrict__ xpart, int n_parts)
 {
     constexpr int Q = N / 4;
@@ -63,8 +159,7 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
     const int64_t row4 = D * Q;  // float4s per branch
     const float4 *a4 = reinterpret_cast<const float4 *>(A);
     __shared__ __attribute__((aligned(16))) float xs[256];
-    const bool fused_dt = sizeof(T) == 2 && dt_w;
-    const bool hold_w = xpart && dt_rank / 4 <= CW * Q;
+    const bool hold_w = dt_rank / 4 <= CW * Q;
 
     int64_t f[U], d[U];
     int q[U];
@@ -93,27 +188,6 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
             for (int c = 0; c < CW; ++c)
                 if (q[i] + c * Q < dt_rank / 4) wq[i][c] = wrow[q[i] + c * Q];
         }
-        if (!xpart) {
-            bv[i] = ld4_io<N>(Bm + j * N + 4 * q[i]);
-            cv[i] = ld4_io<N>(Cm + j * N + 4 * q[i]);
-            if (fused_dt) {
-                // dt projection fused in: the Q lanes of a channel share the dt_rank products (4 at a time)
-                const uint2 *wrow = reinterpret_cast<const uint2 *>(dt_w + d[i] * dt_rank);
-                const uint2 *lrow = reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(dt) + j * dt_rank);
-                float acc = 0.0f;
-#pragma unroll 4
-                for (int64_t c = q[i]; c < dt_rank / 4; c += Q) {
-                    const uint2 a2 = wrow[c], b2 = lrow[c];
-                    acc = fmaf(bf16_lo(a2.x), bf16_lo(b2.x), acc);
-                    acc = fmaf(bf16_hi(a2.x), bf16_hi(b2.x), acc);
-                    acc = fmaf(bf16_lo(a2.y), bf16_lo(b2.y), acc);
-                    acc = fmaf(bf16_hi(a2.y), bf16_hi(b2.y), acc);
-                }
-                dv[i] = bf16_to_f32(f32_to_bf16(channel_sum<Q>(acc)));     // rounded like the stored tensor it replaces
-            } else {
-                dv[i] = ld_io(dt, j * D + d[i]);
-            }
-        }
     }
     // the state row is the only load that has to wait for the parent index
     const int64_t p = parent ? (int64_t)parent[j] : j;
@@ -121,9 +195,9 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
     const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
 #pragma unroll
     for (int i = 0; i < U; ++i) h[i] = hin4[f[i]];
-    // With xpart the branch's row of the x projection (dt low rank | B | C) arrives as n_parts partial sums:
-    // they are added up in order and rounded to bf16, as the stored tensors they replace would have been.
-    if (xpart) {
+    // The branch's row of the x projection (dt low rank | B | C) arrives as n_parts partial sums: they are added
+    // up in order and rounded to bf16, as the stored tensors they replace would have been.
+    {
         const int xn = (int)dt_rank + 2 * N;
         for (int k = threadIdx.x; k < xn; k += kBlock) {
             // the parts of one sum lie side by side (n_parts % 4 == 0): four 16-byte loads in flight at a time
@@ -213,7 +287,23 @@ template <typename T, int N, int U> hipError_t launch_step_u(const StepArgs &a, 
         a.h_out, a.h_in, a.parent, static_cast<const T *>(a.x), static_cast<const T *>(a.dt), a.A, \
         static_cast<const T *>(a.Bm), static_cast<const T *>(a.Cm), a.Dskip,                      \
         static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D,                \
-        static_cast<const bf16_t *>(a.dt_w), a.dt_rank, a.dt_w ? a.xpart : nullptr, a.n_parts)
+        static_cast<const bf16_t *>(a.dt_w), a.dt_rank)
+#define MAMBA_STEP_X(HZ, SP)                                                                      \
+    state_step_xproj_kernel<T, N, U, HZ, SP><<<grid, kBlock, 0, stream>>>(                        \
+        a.h_out, a.h_in, a.parent, static_cast<const T *>(a.x), static_cast<const T *>(a.dt), a.A, \
+        static_cast<const T *>(a.Bm), static_cast<const T *>(a.Cm), a.Dskip,                      \
+        static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D,                \
+        static_cast<const bf16_t *>(a.dt_w), a.dt_rank, a.xpart, a.n_parts)
+    if (a.xpart && a.dt_w) {
+        if (a.z) {
+            if (a.dt_softplus) MAMBA_STEP_X(true, true);
+            else MAMBA_STEP_X(true, false);
+        } else {
+            if (a.dt_softplus) MAMBA_STEP_X(false, true);
+            else MAMBA_STEP_X(false, false);
+        }
+        return hipGetLastError();
+    }
     if (a.z) {
         if (a.dt_softplus) MAMBA_STEP(true, true);
         else MAMBA_STEP(true, false);
@@ -222,6 +312,7 @@ template <typename T, int N, int U> hipError_t launch_step_u(const StepArgs &a, 
         else MAMBA_STEP(false, false);
     }
 #undef MAMBA_STEP
+#undef MAMBA_STEP_X
     return hipGetLastError();
 }
 
