@@ -805,6 +805,33 @@ def test_block_decode_steps_against_oracle(m, tree):
         r_conv = W(synth.to_io(r_conv.astype(np.float32), synth.BF16))
 
 
+@pytest.mark.parametrize("dm,D,N,K,R", [(1024, 2048, 32, 3, 64), (640, 1280, 8, 2, 40), (768, 1600, 16, 4, 48)])
+def test_block_decode_steps_other_shapes(m, dm, D, N, K, R):
+    """The fused draft-position chain on other layer shapes: more states and a wider low-rank dt (the x projection
+    then has 128 columns), fewer states, and a d_inner whose column blocks do not come in fours, which takes the
+    chain with the x projection as a launch of its own."""
+    say(dm=dm, D=D, N=N, K=K, R=R)
+    rng = np.random.default_rng(dm + D + N)
+    w, w64, blk = make_block(m, rng, dm, D, N, K, R)
+    conv = synth.to_io(rng.standard_normal((1, D, K - 1)).astype(np.float32), synth.BF16)
+    ssm = rng.standard_normal((1, D, N)).astype(np.float32)
+    g_conv, g_ssm = to_dev(conv), to_dev(ssm)
+    r_conv, r_ssm = W(conv), ssm.astype(np.float64)
+    tol = TOL[synth.BF16]
+    tree = (5, 2, 1)
+    for n_i, b_i, par in zip(tree, synth.tree_batch_sizes(tree), synth.tree_parents(tree)):
+        hid = synth.to_io(rng.standard_normal((b_i, dm)).astype(np.float32), synth.BF16)
+        if n_i > 1:
+            out, g_conv, g_ssm = m.mamba_block_step(blk, to_dev(hid), g_conv, g_ssm, parent_idx=to_dev(par))
+        else:
+            out, g_conv, g_ssm = m.mamba_block_step(blk, to_dev(hid), g_conv, g_ssm)
+        ro, r_conv, r_ssm = oracle.block_fwd(w64, W(hid)[:, None, :], conv_state_in=r_conv[par], h0=r_ssm[par])
+        assert_close(values(to_host(out)), ro[:, 0], tol, "block step out (batch %d)" % b_i)
+        assert_close(to_host(g_ssm), r_ssm, tol, "block step ssm")
+        assert_close(values(to_host(g_conv)), r_conv, tol, "block step conv")
+        r_conv = W(synth.to_io(r_conv.astype(np.float32), synth.BF16))
+
+
 def test_block_step_bad_parent_poisons_only_that_branch(m):
     """A parent index outside the source cache cannot be honoured: that branch's states and hidden row
     come back NaN (never an out-of-bounds read), the other branches are untouched by it."""
