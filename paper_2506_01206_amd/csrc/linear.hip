@@ -30,6 +30,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
+#ifndef MAMBA_LINEAR_BIG
+#define MAMBA_LINEAR_BIG 512
+#endif
 #ifndef MAMBA_LINEAR_MID
 #define MAMBA_LINEAR_MID 512
 #endif
@@ -536,7 +539,7 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
         return hipGetLastError();
     }
     auto tiles = [&](int64_t bm, int64_t bn) { return ((N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
-    if (tiles(128, 128) >= 1024) {
+    if (tiles(128, 128) >= MAMBA_LINEAR_BIG) {
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 127) / 128));
         linear_kernel<128, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
     } else if (tiles(64, 128) >= MAMBA_LINEAR_MID) {
