@@ -288,3 +288,78 @@ def test_ssd_validation(b):
     assert step(h_out=P(1)) == S["ALIAS"]                                                     # in place only without parents
     assert step(out=P(3)) == S["ALIAS"]
     assert step(n_out=0) == 0
+
+
+def _block_params(b, dm=768, D=1536, N=16, R=48, K=4, **ptrs):
+    names = ["norm_w", "in_proj_w", "conv_w", "conv_b", "x_proj_w", "dt_proj_w", "dt_bias", "A", "Dskip", "out_proj_w"]
+    vals = {n: P(20 + i) for i, n in enumerate(names)}
+    vals.update(ptrs)
+    return b.BlockParams(dm, D, N, R, K, 1e-5, *[vals[n] for n in names])
+
+
+def test_block_validation_and_workspace(b):
+    """The whole-block entry points check parameters, pointers, aliasing and the workspace on the host."""
+    S = b.STATUS
+    ws_bytes = b.lib.mamba_block_workspace_bytes
+    p = _block_params(b)
+    need_prefill = ws_bytes(ctypes.byref(p), 1, 2048)
+    need_step = ws_bytes(ctypes.byref(p), 12, 1)
+    assert need_prefill >= 4 * 2048 * 1536 * 2 and need_step >= 4 * 12 * 1536 * 2
+    # one token on a few rows also holds the partial sums of the x projection: (d_inner / 32, rows, dt_rank + 2 N) floats
+    assert need_step >= 4 * 12 * 1536 * 2 + (1536 // 32) * 12 * 80 * 4
+    assert ws_bytes(ctypes.byref(p), 12, 1) < ws_bytes(ctypes.byref(p), 24, 1)
+    assert ws_bytes(ctypes.byref(p), 0, 1) == 0 and ws_bytes(ctypes.byref(p), 1, 0) == 0
+    assert ws_bytes(ctypes.byref(_block_params(b, N=5)), 1, 64) == 0 and ws_bytes(ctypes.byref(_block_params(b, dm=772)), 1, 64) == 0
+
+    def fwd(p=p, hid=P(0), out=P(1), ci=P(2), co=P(3), h0=P(4), hf=P(5), ws=P(6), wsb=need_prefill, batch=1, L=2048):
+        return b.lib.mamba_block_fwd(ctypes.byref(p), hid, out, ci, co, h0, hf, ws, wsb, batch, L, None)
+    assert fwd(hid=None) == S["NULL_POINTER"] and fwd(out=None) == S["NULL_POINTER"]
+    assert fwd(p=_block_params(b, in_proj_w=None)) == S["NULL_POINTER"]
+    assert fwd(batch=-1) == S["BAD_SHAPE"] and fwd(p=_block_params(b, R=0)) == S["BAD_SHAPE"]
+    assert fwd(p=_block_params(b, N=5)) == S["UNSUPPORTED"] and fwd(p=_block_params(b, K=9)) == S["UNSUPPORTED"]
+    assert fwd(p=_block_params(b, dm=8192)) == S["UNSUPPORTED"]
+    assert fwd(hid=P(0) + 2) == S["MISALIGNED"] and fwd(p=_block_params(b, A=P(27) + 4)) == S["MISALIGNED"]
+    assert fwd(ws=None) == S["WORKSPACE"] and fwd(wsb=need_prefill - 1) == S["WORKSPACE"]
+    assert fwd(batch=0) == 0 and fwd(L=0) == 0
+
+    def step(p=p, hid=P(0), out=P(1), cs=P(2), cd=P(3), ss=P(4), sd=P(5), par=P(7), ws=P(6), wsb=need_step, n_out=12, n_in=6):
+        return b.lib.mamba_block_step(ctypes.byref(p), hid, out, cs, cd, ss, sd, par, ws, wsb, n_out, n_in, None)
+    assert step(hid=None) == S["NULL_POINTER"] and step(sd=None) == S["NULL_POINTER"]
+    assert step(n_out=-1) == S["BAD_SHAPE"] and step(n_in=0) == S["BAD_SHAPE"]
+    assert step(par=None) == S["BAD_SHAPE"]                                     # no parents: in place, same batch
+    assert step(cd=P(2)) == S["ALIAS"] and step(sd=P(4)) == S["ALIAS"]          # children never overwrite their parents
+    assert step(par=P(7) + 4) == S["MISALIGNED"] and step(ws=P(6) + 8) == S["MISALIGNED"]
+    assert step(ws=None) == S["WORKSPACE"] and step(wsb=need_step - 1) == S["WORKSPACE"]
+    assert step(out=P(2)) == S["ALIAS"] and step(ws=P(4)) == S["ALIAS"]
+    assert step(n_out=0) == 0 and step(n_out=70000, n_in=70000, wsb=1 << 40) == S["UNSUPPORTED"]
+
+
+def test_linear_norm_and_vocabulary_validation(b):
+    S = b.STATUS
+
+    def lin(x=P(0), w=P(1), bias=P(2), res=None, o0=P(3), w0=3072, o1=None, w1=0, o2=None, w2=0, M=64, K=768, io=1):
+        return b.lib.mamba_linear_fwd(x, w, bias, res, o0, w0, o1, w1, o2, w2, M, K, io, None)
+    assert lin(x=None) == S["NULL_POINTER"] and lin(o0=None) == S["NULL_POINTER"]
+    assert lin(M=-1) == S["BAD_SHAPE"] and lin(w0=-8) == S["BAD_SHAPE"]
+    assert lin(io=0) == S["UNSUPPORTED"] and lin(K=770) == S["UNSUPPORTED"]
+    assert lin(x=P(0) + 2) == S["MISALIGNED"]
+    assert lin(o0=P(0)) == S["ALIAS"] and lin(o0=P(1)) == S["ALIAS"]
+    assert lin(M=0) == 0
+
+    def norm(x=P(0), w=P(1), y=P(2), M=16, C=768, eps=1e-5, io=1):
+        return b.lib.mamba_rmsnorm_fwd(x, w, y, M, C, eps, io, None)
+    assert norm(x=None) == S["NULL_POINTER"] and norm(M=-2) == S["BAD_SHAPE"] and norm(eps=-1.0) == S["BAD_SHAPE"]
+    assert norm(C=772) == S["UNSUPPORTED"] and norm(C=8192) == S["UNSUPPORTED"] and norm(io=0) == S["UNSUPPORTED"]
+    assert norm(y=P(2) + 4) == S["MISALIGNED"] and norm(y=P(0) + 16) == S["ALIAS"] and norm(M=0) == 0
+
+    def emb(tok=P(0), table=P(1), out=P(2), M=12, V=50280, dm=768, io=1):
+        return b.lib.mamba_embedding_fwd(tok, table, out, M, V, dm, io, None)
+    assert emb(tok=None) == S["NULL_POINTER"] and emb(V=0) == S["BAD_SHAPE"] and emb(dm=772) == S["UNSUPPORTED"]
+    assert emb(io=0) == S["UNSUPPORTED"] and emb(out=P(1)) == S["ALIAS"] and emb(M=0) == 0
+
+    def topk(logits=P(0), idx=P(1), val=P(2), M=12, V=50280, k=3, io=1):
+        return b.lib.mamba_topk_fwd(logits, idx, val, M, V, k, io, None)
+    assert topk(idx=None) == S["NULL_POINTER"] and topk(M=-1) == S["BAD_SHAPE"]
+    assert topk(k=0) == S["UNSUPPORTED"] and topk(k=9) == S["UNSUPPORTED"] and topk(V=(1 << 25) + 1) == S["UNSUPPORTED"]
+    assert topk(io=0) == S["UNSUPPORTED"] and topk(val=P(2) + 4) == S["MISALIGNED"] and topk(idx=P(0)) == S["ALIAS"]
+    assert topk(M=0) == 0
