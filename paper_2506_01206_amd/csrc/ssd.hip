@@ -588,7 +588,7 @@ SsdPlan ssd_plan(int64_t batch, int64_t L, int64_t H)
     SsdPlan p;
     p.chunks2 = (int)cps;
     p.n_seg2 = (int)((nc + cps - 1) / cps);
-    p.chunks1 = cps % 2 ? (int)cps : (int)(cps / 2);
+    p.chunks1 = (cps % 2 || p.n_seg2 == 1) ? (int)cps : (int)(cps / 2);   // one segment: it starts from h0, no first pass
     p.n_seg1 = (int)((nc + p.chunks1 - 1) / p.chunks1);
     return p;
 }

@@ -947,7 +947,7 @@ def ssd_case(rng, B, L, H, P, N, io):
 
 
 @pytest.mark.parametrize("B,L,H,N", [(1, 64, 2, 64), (2, 200, 3, 128), (1, 1, 1, 128), (1, 63, 2, 64), (1, 65, 2, 128),
-                                     (1, 1000, 24, 128), (2, 500, 64, 64), (1, 330, 100, 128)])
+                                     (1, 1000, 24, 128), (2, 500, 64, 64), (1, 330, 100, 128), (4, 130, 64, 64)])
 def test_ssd_scan_against_oracle(m, B, L, H, N):
     """Chunked scalar-decay scan on the matrix cores against the plain float64 recurrence: outputs and final
     state, with and without gate / skip / initial state, and in two pieces with the state carried."""
