@@ -104,18 +104,19 @@ __device__ __forceinline__ uint32_t pair_el(const uint4 &a, const uint4 &b, int 
 //       of the selective scan then turns the slots into the states at the segment starts;
 //   PASS2 = true: from the true incoming state (slot seg * slot_step: pass 1 may cut the sequence
 //       slot_step times finer than pass 2, its workgroups being small enough to share a CU), with outputs.
-// Two roles.  The four "state" wavefronts hold the accumulators: per chunk they park B transposed and the
-// weighted x (two bf16 terms) in LDS and multiply them into the state; in pass 2 they also lay out B
-// row-major, x transposed and the state at the chunk start (two bf16 terms) for the output products.  Pass 2 adds four "output" wavefronts, one 32 x 32 block of the chunk's 64 x 64
-// outputs each, computed transposed so that a lane owns one step and four adjacent channels at a time:
-// they lay out C and z, form G^T and M (D goes onto M's diagonal, which adds D x_t to the outputs), after
-// the barrier multiply M with x and C with the incoming state, and gate and store during the next chunk's
-// first phase, when the state role is busy filling LDS.  With one wavefront of each role
-// on every SIMD the conversions of one overlap the products of the other.  Everything a thread moves into LDS transposed is a run of 2 or 4
-// steps of one row (its pieces are adjacent steps), so the writes are 4 or 8 bytes wide.  The raw tiles
-// of the next chunk are fetched (unconditionally: steps past L re-read step L - 1 and are zeroed at use)
-// as soon as the registers of the current one have gone to LDS; delta and its running sum are formed one
-// chunk ahead into the other half of a double buffer.
+// Two roles.  The four "state" wavefronts hold the accumulators: per chunk they multiply the transposed B and
+// the weighted x (two bf16 terms), which they parked in LDS one phase earlier, into the state; in pass 2 they
+// also lay out B row-major, x transposed and the state at the chunk start (two bf16 terms) for the output
+// products.  Pass 2 adds four "output" wavefronts, one 32 x 32 block of the chunk's 64 x 64 outputs each,
+// computed transposed so that a lane owns one step and four adjacent channels at a time: they lay out C and
+// z, form G^T and M (D goes onto M's diagonal, which adds D x_t to the outputs), after the barrier multiply M
+// with x and C with the incoming state, and gate and store during the next chunk's first phase, when the
+// state role is busy filling LDS.  With one wavefront of each role on every SIMD the conversions of one
+// overlap the products of the other.  Everything a thread moves into LDS transposed is a run of 2 or 4 steps
+// of one row (its pieces are adjacent steps), so the writes are 4 or 8 bytes wide.  Raw tiles are fetched
+// unconditionally (steps past L re-read step L - 1 and are zeroed at use), B and x two chunks ahead into
+// register sets used in turn, C and z one chunk ahead; delta and its running sum are formed one chunk ahead
+// into the other half of a double buffer.
 // grid: (n_seg, H, batch); 256 threads in pass 1, 512 in pass 2.
 template <int N, bool PASS2, bool HAS_Z>
 __global__ void __launch_bounds__(PASS2 ? 2 * kThreads : kThreads) __attribute__((amdgpu_waves_per_eu(2)))
