@@ -271,6 +271,52 @@ def test_step_rejects_out_of_range_parent_without_reading(m):
     assert (sd[0, 1:].view(torch.int32) == -1).all()               # 0xFF fill
 
 
+# ------------------------------------------------------------------------------------ seeded sweep
+def _sweep_shapes(n, seed):
+    """Shapes drawn from a fixed seed: lengths around the tile sizes the kernels use (powers of two
+    +- 1, primes), odd and tiny channel counts, every state size, every window length."""
+    rng = np.random.default_rng(seed)
+    lens = [1, 2, 5, 31, 32, 33, 127, 128, 129, 191, 255, 256, 257, 383, 511, 513, 777, 1023, 1025, 1531]
+    chans = [1, 2, 3, 31, 63, 64, 65, 96, 127, 128, 130, 257, 384, 500]
+    out = []
+    for i in range(n):
+        out.append((int(rng.integers(1, 4)), int(rng.choice(lens)), int(rng.choice(chans)),
+                    int(rng.choice([4, 8, 16, 32])), int(rng.choice([2, 3, 4])),
+                    [synth.F32, synth.BF16][i % 2], int(rng.choice([0, 0, 1, 16, 37, 64, 200])), i))
+    return out
+
+
+@pytest.mark.parametrize("B,L,D,N,K,io,chunk_len,i", _sweep_shapes(28, 20250601))
+def test_seeded_shape_sweep_conv_scan_step(m, B, L, D, N, K, io, chunk_len, i):
+    say(B=B, L=L, D=D, N=N, K=K, io=io, chunk_len=chunk_len)
+    if B * L * D > 600000:
+        B = 1
+    rng = np.random.default_rng(9000 + i)
+    c = synth.prefill_case(B, L, D, N, K, io, seed=7000 + i, random_A=bool(i % 3 == 0))
+    c["conv_bias"] = rng.standard_normal(D).astype(np.float32)
+    st0 = synth.to_io(rng.standard_normal((B, D, K - 1)).astype(np.float32), io) if i % 2 else None
+    check_conv(m, c, st0, apply_silu=bool(i % 4 != 3))
+    h0 = rng.standard_normal((B, D, N)).astype(np.float32) if i % 3 != 1 else None
+    kw = {}
+    if i % 5 == 2:
+        kw["z"] = None
+    if i % 7 == 3:
+        kw["Dskip"] = None
+    check_scan(m, c, h0=h0, chunk_len=chunk_len, **kw)
+    # one step for B * 3 branches forked from the B rows
+    n_out = 3 * B
+    tok = synth.token_inputs(rng, (n_out,), D, N, io)
+    h_in = rng.standard_normal((B, D, N)).astype(np.float32)
+    parent = rng.integers(0, B, n_out).astype(np.int32)
+    ho, o = m.mamba_state_step(to_dev(h_in), to_dev(tok["x"]), to_dev(tok["dt"]), to_dev(c["A"]), to_dev(tok["Bm"]),
+                               to_dev(tok["Cm"]), to_dev(c["Dskip"]), to_dev(tok["z"]), to_dev(c["dt_bias"]),
+                               parent_idx=to_dev(parent))
+    rh, ro = oracle.state_step(W(h_in), W(tok["x"]), W(tok["dt"]), W(c["A"]), W(tok["Bm"]), W(tok["Cm"]),
+                               W(c["Dskip"]), W(tok["z"]), W(c["dt_bias"]), parent)
+    assert_close(to_host(ho), rh, TOL[io], "step h")
+    assert_close(values(to_host(o)), ro, TOL[io], "step out")
+
+
 # ------------------------------------------------------------------------------------ fork
 @pytest.mark.parametrize("io", [synth.F32, synth.BF16])
 @pytest.mark.parametrize("D,N,K", [(1536, 16, 4), (17, 4, 2), (5, 8, 4), (100, 32, 3), (3, 4, 2)])
