@@ -20,6 +20,8 @@
 // Epilogue: the accumulators (+ bias) are rounded to bf16 into LDS, then leave as 16-byte row
 // chunks (+ residual), so that stores are coalesced; output splits that are not multiples of 8
 // columns take an element-wise path.
+#include <type_traits>
+
 #include "device_math.h"
 #include "launch.h"
 
@@ -28,13 +30,25 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
+
+// barrier that orders LDS traffic only: global loads in flight stay in flight
+__device__ __forceinline__ void lds_barrier_linear()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 #ifndef MAMBA_LINEAR_BIG
 #define MAMBA_LINEAR_BIG 512
 #endif
 #ifndef MAMBA_LINEAR_MID
 #define MAMBA_LINEAR_MID 512
+#endif
+#ifndef MAMBA_LINEAR_WIDE
+#define MAMBA_LINEAR_WIDE 512
 #endif
 #ifndef MAMBA_LINEAR_DEEP
 #define MAMBA_LINEAR_DEEP 513
@@ -216,6 +230,200 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
                 out.ptr[s][off] = (bf16_t)f32_to_bf16(v);
             }
         }
+    }
+}
+
+
+// ---------------------------------------------------------------------------------------------------
+// Many rows (the projections of a long context).  A 128 x 128 tile asks the L1 for 512 bytes per k and
+// multiplies 8 cycles per k on every SIMD, so the cache, which delivers 64 bytes a cycle, can feed the
+// matrix cores half the time at best.  This kernel takes 256 x 256 (or 256 x 128) tiles, one workgroup
+// per CU and one wavefront per SIMD, each wavefront a 128 x 128 (128 x 64) part held in 256 (128)
+// accumulator registers: per k the same 8 (6) cycles of cache traffic now feed 32 (16) cycles of MFMA.
+// With nothing else resident, the latencies are hidden inside the wavefront instead: slabs of 64 k
+// alternate between two LDS stages, the slab after the next is in flight to registers while one slab is
+// multiplied, it is parked in the free stage at the start of the following slab, and the only barrier per
+// slab orders LDS alone (a full __syncthreads() would also wait for the loads in flight, which is the
+// whole overlap).  The product is formed transposed (w fragments as the row operand), so that a lane's
+// four accumulators of a group are four adjacent output columns of one row and leave as one 8-byte write.
+// Requires M % 256 == 0, N % BN == 0, K % 128 == 0, K >= 256 and output widths that are multiples of 8.
+// grid: 8 * ceil(tiles / 8) workgroups; consecutive workgroups go to different XCDs, so tile numbers are
+// dealt such that each XCD (each L2) works on a contiguous range of tiles, column tiles of one row block
+// adjacent.
+constexpr int kWideBM = 256, kWideBK = 64, kWideRow = kWideBK * 2 + 16;
+
+template <int BN>
+__global__ void __launch_bounds__(256)
+linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ bias, const bf16_t *residual,
+                   OutSplit out, int64_t M, int64_t N, int64_t K, int tiles_n, int n_tiles)
+{
+    constexpr int NT = BN / 64;                                   // 32 x 32 MFMA tiles per wavefront along n
+    constexpr int kWideSets = BN == 256 ? 1 : 2;                  // register sets for slabs in flight: what the register file allows
+    constexpr int kRows = kWideBM + BN;
+    constexpr int kStage = kRows * kWideRow;
+    constexpr int kOutRow = BN * 2 + 16;
+    static_assert(kWideBM * kOutRow <= 2 * kStage, "the output tile is staged in the operand stages");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kStage];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const int per_xcd = (n_tiles + 7) / 8;
+    const int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (tile >= n_tiles) return;
+    const int64_t m0 = (int64_t)(tile / tiles_n) * kWideBM, n0 = (int64_t)(tile % tiles_n) * BN;
+
+    // staging: 8 lanes per row of 128 bytes, 32 rows per instruction
+    constexpr int NX = kWideBM / 32, NWR = BN / 32;
+    const int srow = tid >> 3, sch = tid & 7;
+    // wave-uniform row bases plus one 32-bit lane offset per operand: the addresses cost two registers, not 32
+    const char *xb = reinterpret_cast<const char *>(x + m0 * K);
+    const char *wb = reinterpret_cast<const char *>(w + n0 * K);
+    const uint32_t lane_off = (uint32_t)((srow * K + sch * 8) * 2);
+    const int64_t rows32 = 64 * K;                                 // bytes between rows 32 apart
+    const int park_off = srow * kWideRow + sch * 16;
+    // two register sets: the loads of two slabs are in flight at any time
+    u32x4 regs[kWideSets][NX + NWR];
+    // registers [first, last) of a set: rows 32 i .. of x, then of w
+    auto fetch = [&](auto set, int64_t k0, auto first, auto last) __attribute__((always_inline)) {
+        constexpr int R = decltype(set)::value % kWideSets;
+#pragma unroll
+        for (int i = decltype(first)::value; i < decltype(last)::value; ++i) {
+            const char *base = i < NX ? xb + (i * rows32 + 2 * k0) : wb + ((i - NX) * rows32 + 2 * k0);
+            regs[R][i] = *reinterpret_cast<const u32x4 *>(base + lane_off);
+        }
+    };
+    auto park = [&](auto set, unsigned char *stage, auto first, auto last) __attribute__((always_inline)) {
+        constexpr int R = decltype(set)::value % kWideSets;
+#pragma unroll
+        for (int i = decltype(first)::value; i < decltype(last)::value; ++i)
+            *reinterpret_cast<u32x4 *>(stage + park_off + i * 32 * kWideRow) = regs[R][i];
+    };
+    constexpr int NREG = NX + NWR, kCut1 = (NREG + 2) / 3, kCut2 = kCut1 + (NREG - kCut1 + 1) / 2;
+    typedef std::integral_constant<int, 0> C0;
+    typedef std::integral_constant<int, kCut1> C1;
+    typedef std::integral_constant<int, kCut2> C2;
+    typedef std::integral_constant<int, NREG> C3;
+
+    f32x16 acc[4][NT];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < NT; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+    const int frag_x = (wm * 128 + (lane & 31)) * kWideRow + (lane >> 5) * 16;
+    const int frag_w = (kWideBM + wn * (BN / 2) + (lane & 31)) * kWideRow + (lane >> 5) * 16;
+    struct Frags { bf16x8 xf[4], wf[NT]; };
+    auto load_frags = [&](const unsigned char *stage, int ks, Frags &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) f.xf[t] = *reinterpret_cast<const bf16x8 *>(stage + frag_x + t * 32 * kWideRow + ks * 32);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) f.wf[t] = *reinterpret_cast<const bf16x8 *>(stage + frag_w + t * 32 * kWideRow + ks * 32);
+    };
+    auto multiply = [&](const Frags &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < NT; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.wf[b], f.xf[a], acc[a][b], 0, 0, 0);
+    };
+    // Slab s, read from stage s % 2, whose first fragments are already in f0.  PARK: slab s + 1, which has arrived in
+    // register set s % 2, goes to the other stage; FETCH: slab s + 3 is requested into the same set right after, so
+    // that every request has two slabs of multiplications to come back; NEXT: the first fragments of the other stage
+    // are read during the last quarter.  Four quarters of 16 MFMAs each; the fragments of a quarter are read during
+    // the one before it, and the instruction groups below keep the scheduler from moving the reads next to their use
+    // or the requests down to theirs.  The barrier comes once every read of the stage has returned, one quarter
+    // before the slab ends.
+    Frags f0, f1;
+    auto slab = [&](auto parity, int64_t k_next, auto do_park, auto do_fetch, auto do_next) __attribute__((always_inline)) {
+        constexpr int P = decltype(parity)::value;
+        constexpr bool PARK = decltype(do_park)::value, FETCH = decltype(do_fetch)::value, NEXT = decltype(do_next)::value;
+        const unsigned char *cur = lds + P * kStage;
+        unsigned char *nxt = lds + (1 - P) * kStage;
+        // the park and the requests are spread over the first three quarters, a third each, so that the LDS writes
+        // of the four wavefronts (which run in step) do not pile up in one of them
+#define MAMBA_WIDE_QUARTER(FROM, TO, KS, FA, FB)                                                                      \
+        if constexpr (PARK) park(parity, nxt, FROM(), TO());                                                          \
+        if constexpr (FETCH) fetch(parity, k_next, FROM(), TO());                                                     \
+        load_frags(cur, KS, FB);                                                                                      \
+        multiply(FA);                                                                                                 \
+        if constexpr (PARK) __builtin_amdgcn_sched_group_barrier(0x200, (TO::value - FROM::value + 1) / 2, 0);       \
+        if constexpr (FETCH) __builtin_amdgcn_sched_group_barrier(0x020, (TO::value - FROM::value + 1) / 2, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x100, (4 + NT) / 2, 0);                                                 \
+        __builtin_amdgcn_sched_group_barrier(0x008, NT * 2, 0);                                                       \
+        if constexpr (PARK) __builtin_amdgcn_sched_group_barrier(0x200, (TO::value - FROM::value) / 2, 0);           \
+        if constexpr (FETCH) __builtin_amdgcn_sched_group_barrier(0x020, (TO::value - FROM::value) / 2, 0);          \
+        __builtin_amdgcn_sched_group_barrier(0x100, (4 + NT) / 2, 0);                                                 \
+        __builtin_amdgcn_sched_group_barrier(0x008, NT * 2, 0);                                                       \
+        __builtin_amdgcn_sched_barrier(0);
+        MAMBA_WIDE_QUARTER(C0, C1, 1, f0, f1)
+        MAMBA_WIDE_QUARTER(C1, C2, 2, f1, f0)
+        MAMBA_WIDE_QUARTER(C2, C3, 3, f0, f1)
+#undef MAMBA_WIDE_QUARTER
+        lds_barrier_linear();
+        if constexpr (NEXT) load_frags(nxt, 0, f0);
+        multiply(f1);
+        if constexpr (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, 4 + NT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NT * 4, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    typedef std::integral_constant<int, 0> Even;
+    typedef std::integral_constant<int, 1> Odd;
+    const int S = (int)(K / kWideBK);
+    constexpr int kAhead = 1 + kWideSets;                         // slab s requests slab s + kAhead
+    fetch(Even(), 0, C0(), C3());
+    park(Even(), lds, C0(), C3());
+    fetch(Even(), kWideBK, C0(), C3());
+    if constexpr (kWideSets == 2) fetch(Odd(), 2 * kWideBK, C0(), C3());
+    lds_barrier_linear();
+    load_frags(lds, 0, f0);
+    int s = 0;
+    for (; s + 4 < S; s += 2) {
+        slab(Even(), (int64_t)(s + kAhead) * kWideBK, std::true_type(), std::true_type(), std::true_type());
+        slab(Odd(), (int64_t)(s + 1 + kAhead) * kWideBK, std::true_type(), std::true_type(), std::true_type());
+    }
+    // the last four slabs (S is even and at least 4): less and less left to request
+    slab(Even(), (int64_t)(s + kAhead) * kWideBK, std::true_type(), std::true_type(), std::true_type());
+    slab(Odd(), (int64_t)(s + 1 + kAhead) * kWideBK, std::true_type(), std::integral_constant<bool, kWideSets == 1>(), std::true_type());
+    slab(Even(), 0, std::true_type(), std::false_type(), std::true_type());
+    slab(Odd(), 0, std::false_type(), std::false_type(), std::false_type());
+    __syncthreads();                                              // the stages are free for the output tile
+
+    // epilogue: acc[a][b][4 g + j] is C[m = 32 a + lane % 32][n = 32 b + 8 g + 4 (lane / 32) + j] of the wavefront's part
+#pragma unroll
+    for (int b = 0; b < NT; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int nl = wn * (BN / 2) + b * 32 + 8 * g + 4 * (lane >> 5);
+            float4 bv = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (bias) bv = *reinterpret_cast<const float4 *>(bias + n0 + nl);
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const int ml = wm * 128 + a * 32 + (lane & 31);
+                uint2 v;
+                v.x = f32x2_to_bf16x2(acc[a][b][4 * g + 0] + bv.x, acc[a][b][4 * g + 1] + bv.y);
+                v.y = f32x2_to_bf16x2(acc[a][b][4 * g + 2] + bv.z, acc[a][b][4 * g + 3] + bv.w);
+                *reinterpret_cast<uint2 *>(lds + ml * kOutRow + nl * 2) = v;
+            }
+        }
+    __syncthreads();
+    constexpr int kCpr = BN / 8;
+#pragma unroll 4
+    for (int c = tid; c < kWideBM * kCpr; c += 256) {
+        const int row = c / kCpr, cc = c % kCpr;
+        uint4 v = *reinterpret_cast<const uint4 *>(lds + row * kOutRow + cc * 16);
+        int64_t col;
+        const int sp = locate(out, n0 + cc * 8, &col);
+        const int64_t off = (m0 + row) * out.width[sp] + col;
+        if (residual) {
+            const uint4 r = *reinterpret_cast<const uint4 *>(residual + off);
+            v.x = f32x2_to_bf16x2(bf16_lo(v.x) + bf16_lo(r.x), bf16_hi(v.x) + bf16_hi(r.x));
+            v.y = f32x2_to_bf16x2(bf16_lo(v.y) + bf16_lo(r.y), bf16_hi(v.y) + bf16_hi(r.y));
+            v.z = f32x2_to_bf16x2(bf16_lo(v.z) + bf16_lo(r.z), bf16_hi(v.z) + bf16_hi(r.z));
+            v.w = f32x2_to_bf16x2(bf16_lo(v.w) + bf16_lo(r.w), bf16_hi(v.w) + bf16_hi(r.w));
+        }
+        *reinterpret_cast<uint4 *>(out.ptr[sp] + off) = v;
     }
 }
 
@@ -539,6 +747,20 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
         return hipGetLastError();
     }
     auto tiles = [&](int64_t bm, int64_t bn) { return ((N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
+#ifndef MAMBA_LINEAR_NO_WIDE
+    if (vec && a.M % kWideBM == 0 && a.K % (2 * kWideBK) == 0 && a.K >= 4 * kWideBK) {
+        // big tiles once they fill the chip a few times over; the narrower one when the wide one leaves a ragged last round
+        const int64_t t256 = N % 256 == 0 ? (a.M / kWideBM) * (N / 256) : 0, t128 = N % 128 == 0 ? (a.M / kWideBM) * (N / 128) : 0;
+        if (t256 >= MAMBA_LINEAR_WIDE && (t256 % 256 == 0 || t256 >= 4 * 256 || t128 == 0)) {
+            linear_wide_kernel<256><<<(unsigned)(8 * ((t256 + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 256), (int)t256);
+            return hipGetLastError();
+        }
+        if (t128 >= MAMBA_LINEAR_WIDE) {
+            linear_wide_kernel<128><<<(unsigned)(8 * ((t128 + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 128), (int)t128);
+            return hipGetLastError();
+        }
+    }
+#endif
     if (tiles(128, 128) >= MAMBA_LINEAR_BIG) {
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 127) / 128));
         linear_kernel<128, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);

@@ -756,7 +756,11 @@ def test_scan_invariants_at_size(m):
                                           # whole slabs only (K a multiple of 64): 1, 2, 3, 5 and 7 of them, ragged edges,
                                           # split outputs
                                           (4096, 4096, 64, None), (4100, 4000, 128, (2000, 2000)), (4096, 4104, 192, None),
-                                          (4090, 4096, 320, (4088, 8)), (5000, 3400, 448, (1000, 1200, 1200))])
+                                          (4090, 4096, 320, (4088, 8)), (5000, 3400, 448, (1000, 1200, 1200)),
+                                          # 256-row tiles, 256 and 128 columns wide (M % 256 == 0, K % 128 == 0, >= 512 tiles):
+                                          # 4, 6, 8 and 10 slabs, splits on and off the tile edges
+                                          (16384, 2048, 256, (1024, 1024)), (16384, 1152, 384, None), (8192, 4096, 512, None),
+                                          (16384, 1152, 640, (1000, 152))])
 def test_linear_against_oracle(m, M, N, K, splits):
     say(M=M, N=N, K=K, splits=splits)
     rng = np.random.default_rng(M + N + K)
