@@ -240,17 +240,30 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
 // matrix cores half the time at best.  This kernel takes 256 x 256 (or 256 x 128) tiles, one workgroup
 // per CU and one wavefront per SIMD, each wavefront a 128 x 128 (128 x 64) part held in 256 (128)
 // accumulator registers: per k the same 8 (6) cycles of cache traffic now feed 32 (16) cycles of MFMA.
-// With nothing else resident, the latencies are hidden inside the wavefront instead: slabs of 64 k
-// alternate between two LDS stages, the slab after the next is in flight to registers while one slab is
-// multiplied, it is parked in the free stage at the start of the following slab, and the only barrier per
-// slab orders LDS alone (a full __syncthreads() would also wait for the loads in flight, which is the
-// whole overlap).  The product is formed transposed (w fragments as the row operand), so that a lane's
-// four accumulators of a group are four adjacent output columns of one row and leave as one 8-byte write.
-// Requires M % 256 == 0, N % BN == 0, K % 128 == 0, K >= 256 and output widths that are multiples of 8.
+//
+// Operands go from memory straight into LDS (global_load_lds_dwordx4: lane l of a wavefront lands at
+// M0 + 16 l, so one instruction fills eight 128-byte rows): no staging registers, and none of the LDS
+// write instructions whose data path the counters showed full when the slabs were parked from registers.
+// Rows lie 128 bytes apart without padding; the 16-byte slot c of row r sits at slot c ^ ((r >> 1) & 7), chosen
+// on the memory side of the load, which makes the fragment reads (32 rows, one slot each) conflict-free.
+// The instruction is issued from inline assembly so that the compiler's wait-count pass does not see an LDS
+// write it cannot place (it would wait for every load in flight before each LDS read); the waits are explicit:
+// vmcnt(0) before the one barrier per slab.  Slabs of 64 k alternate between two stages.  The barrier of
+// slab s comes when its last fragments have been read, a quarter before its end; slab s + 2 is requested
+// right after it into the stage just freed and has a whole slab of multiplications to arrive.
+// The product is formed transposed (w fragments as the row operand), so that a lane's four accumulators
+// of a group are four adjacent output columns of one row and leave as one 8-byte write.
+// Requires M % 256 == 0, N % BN == 0, K % 128 == 0 and output widths that are multiples of 8.
 // grid: 8 * ceil(tiles / 8) workgroups; consecutive workgroups go to different XCDs, so tile numbers are
 // dealt such that each XCD (each L2) works on a contiguous range of tiles, column tiles of one row block
 // adjacent.
-constexpr int kWideBM = 256, kWideBK = 64, kWideRow = kWideBK * 2 + 16;
+constexpr int kWideBM = 256, kWideBK = 64, kWideRow = kWideBK * 2;
+
+// 16 bytes per lane from base + lane_off into LDS at lds_addr + 16 * lane (lds_addr wave-uniform)
+__device__ __forceinline__ void load_to_lds16(const char *base, uint32_t lane_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+}
 
 template <int BN>
 __global__ void __launch_bounds__(256)
@@ -258,13 +271,13 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
                    OutSplit out, int64_t M, int64_t N, int64_t K, int tiles_n, int n_tiles)
 {
     constexpr int NT = BN / 64;                                   // 32 x 32 MFMA tiles per wavefront along n
-    constexpr int kWideSets = BN == 256 ? 1 : 2;                  // register sets for slabs in flight: what the register file allows
     constexpr int kRows = kWideBM + BN;
     constexpr int kStage = kRows * kWideRow;
     constexpr int kOutRow = BN * 2 + 16;
-    static_assert(kWideBM * kOutRow <= 2 * kStage, "the output tile is staged in the operand stages");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kStage];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int kLds = 2 * kStage > kWideBM * kOutRow ? 2 * kStage : kWideBM * kOutRow;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kLds];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
     const int per_xcd = (n_tiles + 7) / 8;
@@ -272,37 +285,28 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
     if (tile >= n_tiles) return;
     const int64_t m0 = (int64_t)(tile / tiles_n) * kWideBM, n0 = (int64_t)(tile % tiles_n) * BN;
 
-    // staging: 8 lanes per row of 128 bytes, 32 rows per instruction
-    constexpr int NX = kWideBM / 32, NWR = BN / 32;
-    const int srow = tid >> 3, sch = tid & 7;
-    // wave-uniform row bases plus one 32-bit lane offset per operand: the addresses cost two registers, not 32
-    const char *xb = reinterpret_cast<const char *>(x + m0 * K);
-    const char *wb = reinterpret_cast<const char *>(w + n0 * K);
-    const uint32_t lane_off = (uint32_t)((srow * K + sch * 8) * 2);
+    // Loads: wavefront v takes the row groups g = 4 j + v (rows 8 g .. 8 g + 7 of the stage; x rows first, then w);
+    // lane l lands in row 8 g + l / 8, slot l % 8, and therefore fetches slot (l % 8) ^ ((4 (g & 1) + l / 16) & 7)
+    // of that row (g & 1 == v & 1).
+    constexpr int NLX = kWideBM / 32, NLW = BN / 32;              // loads per wavefront and slab
+    const uint32_t lane_off = (uint32_t)((lane >> 3) * K * 2 + (((lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7)) << 4));
+    const char *xrow = reinterpret_cast<const char *>(x + (m0 + 8 * wave) * K);
+    const char *wrow = reinterpret_cast<const char *>(w + (n0 + 8 * wave) * K);
     const int64_t rows32 = 64 * K;                                 // bytes between rows 32 apart
-    const int park_off = srow * kWideRow + sch * 16;
-    // two register sets: the loads of two slabs are in flight at any time
-    u32x4 regs[kWideSets][NX + NWR];
-    // registers [first, last) of a set: rows 32 i .. of x, then of w
-    auto fetch = [&](auto set, int64_t k0, auto first, auto last) __attribute__((always_inline)) {
-        constexpr int R = decltype(set)::value % kWideSets;
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    // loads [first, last) of the slab at k0 into the stage at byte `stage`
+    auto request = [&](int64_t k0, int stage, auto first, auto last) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = decltype(first)::value; i < decltype(last)::value; ++i) {
-            const char *base = i < NX ? xb + (i * rows32 + 2 * k0) : wb + ((i - NX) * rows32 + 2 * k0);
-            regs[R][i] = *reinterpret_cast<const u32x4 *>(base + lane_off);
+            const char *base = i < NLX ? xrow + (i * rows32 + 2 * k0) : wrow + ((i - NLX) * rows32 + 2 * k0);
+            load_to_lds16(base, lane_off, lds0 + stage + (i < NLX ? 0 : kWideBM * kWideRow) + wave * 1024 + (i < NLX ? i : i - NLX) * 4096);
         }
     };
-    auto park = [&](auto set, unsigned char *stage, auto first, auto last) __attribute__((always_inline)) {
-        constexpr int R = decltype(set)::value % kWideSets;
-#pragma unroll
-        for (int i = decltype(first)::value; i < decltype(last)::value; ++i)
-            *reinterpret_cast<u32x4 *>(stage + park_off + i * 32 * kWideRow) = regs[R][i];
-    };
-    constexpr int NREG = NX + NWR, kCut1 = (NREG + 2) / 3, kCut2 = kCut1 + (NREG - kCut1 + 1) / 2;
-    typedef std::integral_constant<int, 0> C0;
-    typedef std::integral_constant<int, kCut1> C1;
-    typedef std::integral_constant<int, kCut2> C2;
-    typedef std::integral_constant<int, NREG> C3;
+    typedef std::integral_constant<int, 0> L0;
+    typedef std::integral_constant<int, (NLX + NLW) / 4> L1;
+    typedef std::integral_constant<int, (NLX + NLW) / 2> L2;
+    typedef std::integral_constant<int, 3 * (NLX + NLW) / 4> L3;
+    typedef std::integral_constant<int, NLX + NLW> L4;
 
     f32x16 acc[4][NT];
 #pragma unroll
@@ -312,82 +316,94 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
-    const int frag_x = (wm * 128 + (lane & 31)) * kWideRow + (lane >> 5) * 16;
-    const int frag_w = (kWideBM + wn * (BN / 2) + (lane & 31)) * kWideRow + (lane >> 5) * 16;
+    // fragment of k16 step ks: row lane % 32 of a 32-row block, slot (2 ks + lane / 32) ^ ((lane >> 1) & 7)
+    int frag_x[4], frag_w[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        const int slot = ((2 * ks + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4;
+        frag_x[ks] = (wm * 128 + (lane & 31)) * kWideRow + slot;
+        frag_w[ks] = (kWideBM + wn * (BN / 2) + (lane & 31)) * kWideRow + slot;
+    }
     struct Frags { bf16x8 xf[4], wf[NT]; };
+    auto load_x = [&](const unsigned char *stage, int ks, Frags &f, int t) __attribute__((always_inline)) {
+        f.xf[t] = *reinterpret_cast<const bf16x8 *>(stage + frag_x[ks] + t * 32 * kWideRow);
+    };
+    auto load_w = [&](const unsigned char *stage, int ks, Frags &f, int t) __attribute__((always_inline)) {
+        f.wf[t] = *reinterpret_cast<const bf16x8 *>(stage + frag_w[ks] + t * 32 * kWideRow);
+    };
     auto load_frags = [&](const unsigned char *stage, int ks, Frags &f) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) f.xf[t] = *reinterpret_cast<const bf16x8 *>(stage + frag_x + t * 32 * kWideRow + ks * 32);
+        for (int t = 0; t < 4; ++t) load_x(stage, ks, f, t);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) f.wf[t] = *reinterpret_cast<const bf16x8 *>(stage + frag_w + t * 32 * kWideRow + ks * 32);
+        for (int t = 0; t < NT; ++t) load_w(stage, ks, f, t);
+    };
+    auto multiply_row = [&](const Frags &f, int a) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < NT; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.wf[b], f.xf[a], acc[a][b], 0, 0, 0);
     };
     auto multiply = [&](const Frags &f) __attribute__((always_inline)) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < NT; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.wf[b], f.xf[a], acc[a][b], 0, 0, 0);
+        for (int a = 0; a < 4; ++a) multiply_row(f, a);
     };
-    // Slab s, read from stage s % 2, whose first fragments are already in f0.  PARK: slab s + 1, which has arrived in
-    // register set s % 2, goes to the other stage; FETCH: slab s + 3 is requested into the same set right after, so
-    // that every request has two slabs of multiplications to come back; NEXT: the first fragments of the other stage
-    // are read during the last quarter.  Four quarters of 16 MFMAs each; the fragments of a quarter are read during
-    // the one before it, and the instruction groups below keep the scheduler from moving the reads next to their use
-    // or the requests down to theirs.  The barrier comes once every read of the stage has returned, one quarter
-    // before the slab ends.
+    // Slab s, read from stage s % 2, whose first fragments are already in f0.  Four quarters of 4 NT MFMAs; the
+    // fragments of a quarter are read during the one before it (the instruction groups keep the scheduler from
+    // moving the reads next to their use).  After the third quarter every read of this stage has been issued: the
+    // slab s + 1 must have landed by then (requested a slab ago), the barrier publishes it, the stage of slab s is
+    // free, and the last quarter requests slab s + 2 into it (REQUEST) and reads the first fragments of slab s + 1
+    // (NEXT) between its multiplications.
     Frags f0, f1;
-    auto slab = [&](auto parity, int64_t k_next, auto do_park, auto do_fetch, auto do_next) __attribute__((always_inline)) {
+    auto slab = [&](auto parity, int64_t k_next, auto do_request, auto do_next) __attribute__((always_inline)) {
         constexpr int P = decltype(parity)::value;
-        constexpr bool PARK = decltype(do_park)::value, FETCH = decltype(do_fetch)::value, NEXT = decltype(do_next)::value;
+        constexpr bool REQUEST = decltype(do_request)::value, NEXT = decltype(do_next)::value;
         const unsigned char *cur = lds + P * kStage;
-        unsigned char *nxt = lds + (1 - P) * kStage;
-        // the park and the requests are spread over the first three quarters, a third each, so that the LDS writes
-        // of the four wavefronts (which run in step) do not pile up in one of them
-#define MAMBA_WIDE_QUARTER(FROM, TO, KS, FA, FB)                                                                      \
-        if constexpr (PARK) park(parity, nxt, FROM(), TO());                                                          \
-        if constexpr (FETCH) fetch(parity, k_next, FROM(), TO());                                                     \
+        const unsigned char *nxt = lds + (1 - P) * kStage;
+/* one fragment read per two MFMAs */
+#define MAMBA_WIDE_SPREAD __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); __builtin_amdgcn_sched_group_barrier(0x008, NT / 2, 0);
+#define MAMBA_WIDE_QUARTER(KS, FA, FB)                                                                                \
         load_frags(cur, KS, FB);                                                                                      \
         multiply(FA);                                                                                                 \
-        if constexpr (PARK) __builtin_amdgcn_sched_group_barrier(0x200, (TO::value - FROM::value + 1) / 2, 0);       \
-        if constexpr (FETCH) __builtin_amdgcn_sched_group_barrier(0x020, (TO::value - FROM::value + 1) / 2, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x100, (4 + NT) / 2, 0);                                                 \
-        __builtin_amdgcn_sched_group_barrier(0x008, NT * 2, 0);                                                       \
-        if constexpr (PARK) __builtin_amdgcn_sched_group_barrier(0x200, (TO::value - FROM::value) / 2, 0);           \
-        if constexpr (FETCH) __builtin_amdgcn_sched_group_barrier(0x020, (TO::value - FROM::value) / 2, 0);          \
-        __builtin_amdgcn_sched_group_barrier(0x100, (4 + NT) / 2, 0);                                                 \
+        MAMBA_WIDE_SPREAD MAMBA_WIDE_SPREAD MAMBA_WIDE_SPREAD MAMBA_WIDE_SPREAD                                       \
+        __builtin_amdgcn_sched_group_barrier(0x100, NT, 0);                                                           \
         __builtin_amdgcn_sched_group_barrier(0x008, NT * 2, 0);                                                       \
         __builtin_amdgcn_sched_barrier(0);
-        MAMBA_WIDE_QUARTER(C0, C1, 1, f0, f1)
-        MAMBA_WIDE_QUARTER(C1, C2, 2, f1, f0)
-        MAMBA_WIDE_QUARTER(C2, C3, 3, f0, f1)
+        MAMBA_WIDE_QUARTER(1, f0, f1)
+        MAMBA_WIDE_QUARTER(2, f1, f0)
+        MAMBA_WIDE_QUARTER(3, f0, f1)
 #undef MAMBA_WIDE_QUARTER
+#undef MAMBA_WIDE_SPREAD
+        __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0): this wavefront's part of slab s + 1 is in LDS
         lds_barrier_linear();
-        if constexpr (NEXT) load_frags(nxt, 0, f0);
-        multiply(f1);
-        if constexpr (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, 4 + NT, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, NT * 4, 0);
+#define MAMBA_WIDE_LAST(A, FROM, TO)                                                                                  \
+        if constexpr (REQUEST) request(k_next, P * kStage, FROM(), TO());                                             \
+        if constexpr (NEXT) {                                                                                         \
+            load_x(nxt, 0, f0, A);                                                                                    \
+            if (A < NT) load_w(nxt, 0, f0, A);                                                                        \
+        }                                                                                                             \
+        multiply_row(f1, A);                                                                                          \
         __builtin_amdgcn_sched_barrier(0);
+        MAMBA_WIDE_LAST(0, L0, L1)
+        MAMBA_WIDE_LAST(1, L1, L2)
+        MAMBA_WIDE_LAST(2, L2, L3)
+        MAMBA_WIDE_LAST(3, L3, L4)
+#undef MAMBA_WIDE_LAST
     };
     typedef std::integral_constant<int, 0> Even;
     typedef std::integral_constant<int, 1> Odd;
     const int S = (int)(K / kWideBK);
-    constexpr int kAhead = 1 + kWideSets;                         // slab s requests slab s + kAhead
-    fetch(Even(), 0, C0(), C3());
-    park(Even(), lds, C0(), C3());
-    fetch(Even(), kWideBK, C0(), C3());
-    if constexpr (kWideSets == 2) fetch(Odd(), 2 * kWideBK, C0(), C3());
+    request(0, 0, L0(), L4());
+    request(kWideBK, kStage, L0(), L4());
+    // vmcnt(loads of one slab): slab 0 is in, slab 1 may be under way (vmcnt is split over bits 3:0 and 15:14)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((NLX + NLW) & 15) | (((NLX + NLW) >> 4) << 14));
     lds_barrier_linear();
     load_frags(lds, 0, f0);
     int s = 0;
-    for (; s + 4 < S; s += 2) {
-        slab(Even(), (int64_t)(s + kAhead) * kWideBK, std::true_type(), std::true_type(), std::true_type());
-        slab(Odd(), (int64_t)(s + 1 + kAhead) * kWideBK, std::true_type(), std::true_type(), std::true_type());
+    for (; s + 2 < S; s += 2) {
+        slab(Even(), (int64_t)(s + 2) * kWideBK, std::true_type(), std::true_type());
+        slab(Odd(), (int64_t)(s + 3) * kWideBK, std::true_type(), std::true_type());
     }
-    // the last four slabs (S is even and at least 4): less and less left to request
-    slab(Even(), (int64_t)(s + kAhead) * kWideBK, std::true_type(), std::true_type(), std::true_type());
-    slab(Odd(), (int64_t)(s + 1 + kAhead) * kWideBK, std::true_type(), std::integral_constant<bool, kWideSets == 1>(), std::true_type());
-    slab(Even(), 0, std::true_type(), std::false_type(), std::true_type());
-    slab(Odd(), 0, std::false_type(), std::false_type(), std::false_type());
+    slab(Even(), 0, std::false_type(), std::true_type());         // S is even: two slabs left, nothing more to request
+    slab(Odd(), 0, std::false_type(), std::false_type());
     __syncthreads();                                              // the stages are free for the output tile
 
     // epilogue: acc[a][b][4 g + j] is C[m = 32 a + lane % 32][n = 32 b + 8 g + 4 (lane / 32) + j] of the wavefront's part
@@ -406,6 +422,7 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
                 v.y = f32x2_to_bf16x2(acc[a][b][4 * g + 2] + bv.z, acc[a][b][4 * g + 3] + bv.w);
                 *reinterpret_cast<uint2 *>(lds + ml * kOutRow + nl * 2) = v;
             }
+            __builtin_amdgcn_sched_barrier(0);                    // one group at a time: the accumulators stay where they are until used
         }
     __syncthreads();
     constexpr int kCpr = BN / 8;
@@ -748,7 +765,7 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     }
     auto tiles = [&](int64_t bm, int64_t bn) { return ((N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
 #ifndef MAMBA_LINEAR_NO_WIDE
-    if (vec && a.M % kWideBM == 0 && a.K % (2 * kWideBK) == 0 && a.K >= 4 * kWideBK) {
+    if (vec && a.M % kWideBM == 0 && a.K % (2 * kWideBK) == 0 && a.K >= 2 * kWideBK) {
         // big tiles once they fill the chip a few times over; the narrower one when the wide one leaves a ragged last round
         const int64_t t256 = N % 256 == 0 ? (a.M / kWideBM) * (N / 256) : 0, t128 = N % 128 == 0 ? (a.M / kWideBM) * (N / 128) : 0;
         if (t256 >= MAMBA_LINEAR_WIDE && (t256 % 256 == 0 || t256 >= 4 * 256 || t128 == 0)) {
