@@ -760,7 +760,7 @@ def test_scan_invariants_at_size(m):
                                           # 256-row tiles, 256 and 128 columns wide (M % 256 == 0, K % 128 == 0, >= 512 tiles):
                                           # 4, 6, 8 and 10 slabs, splits on and off the tile edges
                                           (16384, 2048, 256, (1024, 1024)), (16384, 1152, 384, None), (8192, 4096, 512, None),
-                                          (16384, 1152, 640, (1000, 152))])
+                                          (16384, 1152, 640, (1000, 152)), (1024, 3072, 768, (1536, 1536)), (512, 6144, 128, None)])
 def test_linear_against_oracle(m, M, N, K, splits):
     say(M=M, N=N, K=K, splits=splits)
     rng = np.random.default_rng(M + N + K)
