@@ -13,9 +13,9 @@
 // MFMA tiles of v_mfma_f32_32x32x16_bf16.  K is walked in slabs of BK = 64: the x and w slabs are
 // fetched with 16-byte loads one slab ahead into registers, parked in LDS (rows padded by 16 B)
 // and read back as MFMA fragments with 16-byte LDS reads: lane l holds row l % 32,
-// k = 8 * (l / 32) .. + 7 of each k16 step.  (A 128 x 256 tile halves the LDS reads per MFMA but
-// leaves one wavefront per SIMD and measured slower: three resident workgroups hide more latency;
-// so did 256 x 128 and 128 x 128 tiles with 32-wide slabs in two LDS buffers and one barrier per slab.)
+// k = 8 * (l / 32) .. + 7 of each k16 step.  Three resident workgroups per CU hide the latencies.  (Larger
+// tiles on this scheme, with its register staging and full barriers, measured slower; long contexts
+// take the 256-row tiles of linear_wide_kernel below, which is built differently.)
 // Rows past M or N re-read the last valid row and are never stored; a K tail is zero-filled.
 // Epilogue: the accumulators (+ bias) are rounded to bf16 into LDS, then leave as 16-byte row
 // chunks (+ residual), so that stores are coalesced; output splits that are not multiples of 8
