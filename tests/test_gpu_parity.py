@@ -798,7 +798,9 @@ def make_block(m, rng, dm, D, N, K, R):
 
 
 @pytest.mark.parametrize("B,L,dm,D,N,K,R", [(2, 96, 64, 128, 16, 4, 8), (1, 700, 768, 1536, 16, 4, 48),
-                                           (3, 33, 256, 512, 8, 3, 16)])
+                                           (3, 33, 256, 512, 8, 3, 16),
+                                           # long enough for the 256-row projection tiles (in_proj and out_proj)
+                                           (1, 4096, 768, 1536, 16, 4, 48)])
 def test_block_prefill_against_oracle(m, B, L, dm, D, N, K, R):
     """RMSNorm -> in_proj -> conv1d -> x_proj -> dt_proj -> selective scan -> out_proj + residual as one
     call; the oracle rounds the tensors between stages to bf16 as the workspace does.  Also checked
