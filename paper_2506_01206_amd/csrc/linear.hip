@@ -404,9 +404,23 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
     }
     slab(Even(), 0, std::false_type(), std::true_type());         // S is even: two slabs left, nothing more to request
     slab(Odd(), 0, std::false_type(), std::false_type());
-    __syncthreads();                                              // the stages are free for the output tile
+    // Epilogue.  The residual chunks this thread will add are requested first, all at once: with one workgroup per
+    // CU nothing else would hide their latency, and fetched four at a time inside the store loop they cost a third
+    // of the tile's time.
+    constexpr int kCpr = BN / 8, kChunks = kWideBM * kCpr / 256;
+    u32x4 res[kChunks];
+    if (residual) {
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i) {
+            const int c = tid + i * 256, row = c / kCpr, cc = c % kCpr;
+            int64_t col;
+            const int sp = locate(out, n0 + cc * 8, &col);
+            res[i] = *reinterpret_cast<const u32x4 *>(residual + (m0 + row) * out.width[sp] + col);
+        }
+    }
+    lds_barrier_linear();                                         // the stages are free for the output tile (the requests stay in flight)
 
-    // epilogue: acc[a][b][4 g + j] is C[m = 32 a + lane % 32][n = 32 b + 8 g + 4 (lane / 32) + j] of the wavefront's part
+    // acc[a][b][4 g + j] is C[m = 32 a + lane % 32][n = 32 b + 8 g + 4 (lane / 32) + j] of the wavefront's part
 #pragma unroll
     for (int b = 0; b < NT; ++b)
 #pragma unroll
@@ -424,17 +438,16 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
             }
             __builtin_amdgcn_sched_barrier(0);                    // one group at a time: the accumulators stay where they are until used
         }
-    __syncthreads();
-    constexpr int kCpr = BN / 8;
-#pragma unroll 4
-    for (int c = tid; c < kWideBM * kCpr; c += 256) {
-        const int row = c / kCpr, cc = c % kCpr;
+    lds_barrier_linear();
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i) {
+        const int c = tid + i * 256, row = c / kCpr, cc = c % kCpr;
         uint4 v = *reinterpret_cast<const uint4 *>(lds + row * kOutRow + cc * 16);
         int64_t col;
         const int sp = locate(out, n0 + cc * 8, &col);
         const int64_t off = (m0 + row) * out.width[sp] + col;
         if (residual) {
-            const uint4 r = *reinterpret_cast<const uint4 *>(residual + off);
+            const u32x4 r = res[i];
             v.x = f32x2_to_bf16x2(bf16_lo(v.x) + bf16_lo(r.x), bf16_hi(v.x) + bf16_hi(r.x));
             v.y = f32x2_to_bf16x2(bf16_lo(v.y) + bf16_lo(r.y), bf16_hi(v.y) + bf16_hi(r.y));
             v.z = f32x2_to_bf16x2(bf16_lo(v.z) + bf16_lo(r.z), bf16_hi(v.z) + bf16_hi(r.z));
@@ -443,7 +456,6 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
         *reinterpret_cast<uint4 *>(out.ptr[sp] + off) = v;
     }
 }
-
 
 // ---------------------------------------------------------------------------------------------------
 // Few rows (M <= 64: the branches of one draft position, Sec. 4.1).  The product is then bound by
