@@ -778,6 +778,24 @@ def test_linear_against_oracle(m, M, N, K, splits):
         assert_close(values(to_host(o)), oracle.linear(W(x), W(w), None, W(res)), TOL[synth.BF16], "linear + residual")
 
 
+def test_linear_at_block_bench_size_sampled_rows(m):
+    """in_proj and out_proj of the whole-block leg of bench.py (32768 tokens, Mamba-130M widths), in the launch
+    configuration it times; rows are independent, so the oracle computes a seeded sample of them (every row block
+    of the first and last tiles, and rows scattered over the rest)."""
+    M = 32768
+    rng = np.random.default_rng(321)
+    rows = np.unique(np.concatenate([np.arange(0, 256, 5), np.arange(M - 256, M, 7), rng.integers(0, M, 300)]))
+    for (N, K, splits, with_res) in ((3072, 768, (1536, 1536), False), (768, 1536, None, True)):
+        say(M=M, N=N, K=K, splits=splits, residual=with_res, sampled_rows=len(rows))
+        x = synth.to_io(rng.standard_normal((M, K)).astype(np.float32), synth.BF16)
+        w = synth.to_io((rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32), synth.BF16)
+        res = synth.to_io(rng.standard_normal((M, N)).astype(np.float32), synth.BF16) if with_res else None
+        outs = m.mamba_linear_fwd(to_dev(x), to_dev(w), None, residual=to_dev(res), splits=splits)
+        got = np.concatenate([values(to_host(o[torch.as_tensor(rows, device=DEV)])) for o in outs], axis=1)
+        ref = oracle.linear(W(x[rows]), W(w), None, None if res is None else W(res[rows]))
+        assert_close(got, ref, TOL[synth.BF16], "linear at bench size")
+
+
 @pytest.mark.parametrize("M,C", [(1, 8), (7, 768), (1000, 768), (33, 2048), (5, 4096), (3, 40)])
 def test_rmsnorm_against_oracle(m, M, C):
     rng = np.random.default_rng(M + C)
