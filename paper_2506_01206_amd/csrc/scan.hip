@@ -469,59 +469,76 @@ scan_carry(const float *__restrict__ A, const float *h0, float *ws_state,
     carry_walk<true>(h, a2, st, sd, c0, c1, DN, D);
 }
 
-// The same carry for up to kFastSegs * kFastPer links with a single trip to memory: 16 segments of at
-// most 16 chunks; a lane fetches all local states and delta sums of its segment at once, folds them in
-// registers, and after the exchange walks the registers again, so the second walk loads nothing.
-// block: (64 lanes over (b,d,n), 16 segments)
+// The same carry for up to kFastSegs * PER links with a single trip to memory: 16 segments of at most PER
+// chunks; a lane owns VEC adjacent states of one channel (N % 4 == 0), fetches all local states and delta sums
+// of its segment at once (8- or 16-byte loads, 512 B or 1 KiB per wavefront and chunk), folds them in registers,
+// and after the exchange walks the registers again, so the second walk loads nothing.  <4, 8> serves up to 128
+// links, <2, 16> up to 256 (both hold 32 state registers per lane).
+// block: (64 lanes over (b, d, n / VEC), 16 segments)
 constexpr int kFastSegs = 16;
-constexpr int kFastPer = 16;
 
+template <int VEC, int PER>
 __global__ void __launch_bounds__(kWave * kFastSegs)
 scan_carry_fast(const float *__restrict__ A, const float *h0, float *ws_state,
                 const float *__restrict__ ws_sumdt, int64_t batch, int64_t D, int N, int n_chunks)
 {
-    __shared__ float decay[kFastSegs][kWave], offset[kFastSegs][kWave];
+    typedef float vec_t __attribute__((ext_vector_type(VEC)));
+    __shared__ vec_t decay[kFastSegs][kWave], offset[kFastSegs][kWave];
     const int lane = threadIdx.x, seg = threadIdx.y;
-    const int64_t DN = D * N;
+    const int64_t DNV = D * N / VEC;
     const int64_t idx_raw = (int64_t)blockIdx.x * kWave + lane;
-    const bool live = idx_raw < batch * DN;
-    const int64_t idx = live ? idx_raw : batch * DN - 1;
-    const int64_t b = idx / DN;
-    const int64_t dn = idx - b * DN;
-    const int64_t d = dn / N;
-    const float a2 = A[dn] * kLog2e;
-    float *st = ws_state + b * n_chunks * DN + dn;
+    const bool live = idx_raw < batch * DNV;
+    const int64_t idx = live ? idx_raw : batch * DNV - 1;
+    const int64_t b = idx / DNV;
+    const int64_t dnv = idx - b * DNV;
+    const int64_t d = dnv / (N / VEC);
+    const vec_t a2 = reinterpret_cast<const vec_t *>(A)[dnv] * kLog2e;
+    vec_t *st = reinterpret_cast<vec_t *>(ws_state) + b * n_chunks * DNV + dnv;
     const float *sd = ws_sumdt + b * n_chunks * D + d;
-    const int per = (n_chunks - 1 + kFastSegs - 1) / kFastSegs;   // <= kFastPer, checked by the launcher
+    const int per = (n_chunks - 1 + kFastSegs - 1) / kFastSegs;   // <= PER, checked by the launcher
     int c0 = 1 + seg * per, c1 = c0 + per;
     if (c0 > n_chunks) c0 = n_chunks;
     if (c1 > n_chunks) c1 = n_chunks;
 
-    float loc[kFastPer], e[kFastPer];
+    vec_t loc[PER];
+    float e[PER];
 #pragma unroll
-    for (int i = 0; i < kFastPer; ++i) {
+    for (int i = 0; i < PER; ++i) {
         const bool in = c0 + i < c1;
-        loc[i] = in ? st[(int64_t)(c0 + i) * DN] : 0.0f;
-        e[i] = in ? sd[(int64_t)(c0 + i - 1) * D] : 0.0f;        // delta sum first, decay below
+        loc[i] = in ? st[(int64_t)(c0 + i) * DNV] : vec_t(0.0f);
+        e[i] = in ? sd[(int64_t)(c0 + i - 1) * D] : 0.0f;         // delta sum of the chunk before; 0 for the unused tail
     }
-    float sum = 0.0f, h = 0.0f;
+    auto step = [&](vec_t h, int i) __attribute__((always_inline)) {
+        // decay 1 for the unused tail (delta sum 0), with loc 0: no effect
 #pragma unroll
-    for (int i = 0; i < kFastPer; ++i) {
+        for (int v = 0; v < VEC; ++v) h[v] = fmaf(exp2_hw(a2[v] * e[i]), h[v], loc[i][v]);
+        return h;
+    };
+    float sum = 0.0f;
+    vec_t h = vec_t(0.0f);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
         sum += e[i];
-        e[i] = exp2_hw(a2 * e[i]);                                // 1 for the unused tail (sum 0), with loc 0: no effect
-        h = fmaf(e[i], h, loc[i]);
+        h = step(h, i);
     }
-    decay[seg][lane] = exp2_hw(a2 * sum);
+    vec_t dc;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) dc[v] = exp2_hw(a2[v] * sum);
+    decay[seg][lane] = dc;
     offset[seg][lane] = h;
     __syncthreads();
-    h = h0 ? h0[idx] : 0.0f;
-    for (int s = 0; s < seg; ++s) h = fmaf(decay[s][lane], h, offset[s][lane]);
+    h = h0 ? reinterpret_cast<const vec_t *>(h0)[idx] : vec_t(0.0f);
+    for (int s = 0; s < seg; ++s) {
+        const vec_t ds = decay[s][lane], of = offset[s][lane];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) h[v] = fmaf(ds[v], h[v], of[v]);
+    }
     if (!live) return;
     if (seg == 0) st[0] = h;
 #pragma unroll
-    for (int i = 0; i < kFastPer; ++i) {
-        h = fmaf(e[i], h, loc[i]);
-        if (c0 + i < c1) st[(int64_t)(c0 + i) * DN] = h;
+    for (int i = 0; i < PER; ++i) {
+        h = step(h, i);
+        if (c0 + i < c1) st[(int64_t)(c0 + i) * DNV] = h;
     }
 }
 
@@ -652,8 +669,10 @@ hipError_t launch_chunk_carry(const float *A, const float *h0, float *ws_state, 
     const unsigned blocks = (unsigned)((total + kWave - 1) / kWave);
     if (n_slots <= kSerialSlots)
         scan_carry_serial<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
-    else if (n_slots - 1 <= kFastSegs * kFastPer)
-        scan_carry_fast<<<blocks, dim3(kWave, kFastSegs), 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
+    else if (n_slots - 1 <= kFastSegs * 8)
+        scan_carry_fast<4, 8><<<(unsigned)((total / 4 + kWave - 1) / kWave), dim3(kWave, kFastSegs), 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
+    else if (n_slots - 1 <= kFastSegs * 16)
+        scan_carry_fast<2, 16><<<(unsigned)((total / 2 + kWave - 1) / kWave), dim3(kWave, kFastSegs), 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
     else
         scan_carry<<<blocks, dim3(kWave, kCarrySegs), 0, stream>>>(A, h0, ws_state, ws_sumdt, batch, D, N, n_slots);
     return hipGetLastError();
