@@ -34,7 +34,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published: 256 CUs x 128 
 # HBM bytes per scan launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE summed over the scan's
 # three kernels, each scaled by what the same counter reads for the 1 GiB copy below; figures and
 # commands in profiles/).  Keyed by workload; None for a workload that has not been profiled.
-SCAN_TRAFFIC_BYTES = {("cfg3", 1, 32768, 1536, 16): 744_400_000}
+SCAN_TRAFFIC_BYTES = {("cfg3", 1, 32768, 1536, 16): 738_000_000}
 
 
 def scan_bytes(B, L, D, N, e):
