@@ -40,6 +40,22 @@ template <int N> __device__ __forceinline__ float4 ld4_io(const bf16_t *p)
     return make_float4(bf16_lo(r.x), bf16_hi(r.x), bf16_lo(r.y), bf16_hi(r.y));
 }
 
+// The state is read once and written once per step: streaming (non-temporal) accesses keep it from displacing the
+// weights and token rows in the caches (measured cold in a replayed graph: 64 branches x 4096 channels 9.9 -> 9.2 us,
+// 32 x 1536 3.5 -> 2.9 us).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld_stream(const float4 *p)
+{
+    const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void st_stream(float4 *p, float4 v)
+{
+    f32x4 t;
+    t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+    __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(p));
+}
+
 #ifndef MAMBA_STEP_UNROLL
 #define MAMBA_STEP_UNROLL 4
 #endif
@@ -103,7 +119,7 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
     const bool p_ok = p >= 0 && p < n_in;
     const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
 #pragma unroll
-    for (int i = 0; i < U; ++i) h[i] = hin4[f[i]];
+    for (int i = 0; i < U; ++i) h[i] = ld_stream(hin4 + f[i]);
 #pragma unroll
     for (int i = 0; i < U; ++i) {
         const float v = dv[i] + bias[i];
@@ -126,7 +142,7 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
             y = nan;
         }
         if (live[i]) {
-            reinterpret_cast<float4 *>(h_out)[j * row4 + f[i]] = hh;
+            st_stream(reinterpret_cast<float4 *>(h_out) + j * row4 + f[i], hh);
             if (f[i] - d[i] * Q == 0) {
                 y = fmaf(dsk[i], xv[i], y);
                 if constexpr (HAS_Z) y *= silu_f32(zv[i]);
@@ -194,7 +210,7 @@ state_step_xproj_kernel(float *h_out, const float *h_in, const int32_t *__restri
     const bool p_ok = p >= 0 && p < n_in;
     const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
 #pragma unroll
-    for (int i = 0; i < U; ++i) h[i] = hin4[f[i]];
+    for (int i = 0; i < U; ++i) h[i] = ld_stream(hin4 + f[i]);
     // The branch's row of the x projection (dt low rank | B | C) arrives as n_parts partial sums: they are added
     // up in order and rounded to bf16, as the stored tensors they replace would have been.
     {
@@ -267,7 +283,7 @@ state_step_xproj_kernel(float *h_out, const float *h_in, const int32_t *__restri
             y = nan;
         }
         if (live[i]) {
-            reinterpret_cast<float4 *>(h_out)[j * row4 + f[i]] = hh;
+            st_stream(reinterpret_cast<float4 *>(h_out) + j * row4 + f[i], hh);
             if (q[i] == 0) {
                 y = fmaf(dsk[i], xv[i], y);
                 if constexpr (HAS_Z) y *= silu_f32(zv[i]);
