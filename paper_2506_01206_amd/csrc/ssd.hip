@@ -544,7 +544,10 @@ ssd_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ par
     const float a = exp2_hw(delta * A[hh] * kLog2e), u = delta * xv;
     const int64_t p = parent ? (int64_t)parent[j] : j;
     const bool p_ok = p >= 0 && p < n_in;
-    float4 hv = reinterpret_cast<const float4 *>(h_in)[(p_ok ? p : 0) * row4 + f];
+    // the state is touched once per step: streaming accesses, as in the selective step
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 hraw = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(h_in) + (p_ok ? p : 0) * row4 + f);
+    float4 hv = make_float4(hraw.x, hraw.y, hraw.z, hraw.w);
     hv.x = fmaf(a, hv.x, u * bq[0]);
     hv.y = fmaf(a, hv.y, u * bq[1]);
     hv.z = fmaf(a, hv.z, u * bq[2]);
@@ -561,7 +564,9 @@ ssd_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ par
         y = nan;
     }
     if (!live) return;
-    reinterpret_cast<float4 *>(h_out)[j * row4 + f] = hv;
+    f32x4 hst;
+    hst.x = hv.x; hst.y = hv.y; hst.z = hv.z; hst.w = hv.w;
+    __builtin_nontemporal_store(hst, reinterpret_cast<f32x4 *>(h_out) + j * row4 + f);
     if (q == 0) {
         y = fmaf(Dskip ? Dskip[hh] : 0.0f, xv, y);
         if (z) y *= silu_f32(ld_io(z, j * H * P + d));
