@@ -796,6 +796,21 @@ def test_linear_at_block_bench_size_sampled_rows(m):
         assert_close(got, ref, TOL[synth.BF16], "linear at bench size")
 
 
+def test_linear_wide_tiles_are_deterministic(m):
+    """The 256-row tiles stream their operands into LDS asynchronously and order them with explicit waits; a
+    missing wait would show as run-to-run differences.  Ten launches each, both tile widths, on fresh outputs."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(77)
+    for (M, N, K) in ((8192, 4096, 768), (16384, 1152, 1536)):
+        x = torch.randn(M, K, device=DEV, generator=g).bfloat16()
+        w = (torch.randn(N, K, device=DEV, generator=g) / K ** 0.5).bfloat16()
+        (first,) = m.mamba_linear_fwd(x, w)
+        for _ in range(9):
+            out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+            m.mamba_linear_fwd(x, w, outs=[out])
+            assert torch.equal(out, first)
+
+
 @pytest.mark.parametrize("M,C", [(1, 8), (7, 768), (1000, 768), (33, 2048), (5, 4096), (3, 40)])
 def test_rmsnorm_against_oracle(m, M, C):
     rng = np.random.default_rng(M + C)
