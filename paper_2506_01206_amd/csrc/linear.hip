@@ -87,8 +87,10 @@ __device__ __forceinline__ int locate(const OutSplit &o, int64_t n, int64_t *col
     return s;
 }
 
-// grid: (ceil(N / BN), ceil(M / BM))
-template <int BM, int BN, int BK>
+// grid: (ceil(N / BN), ceil(M / BM)).  WSTREAM: w is read once and is large (the LM head on a draft position): its
+// loads are streaming, so that they do not push the blocks' weights, which the next position reads again, out of
+// the last-level cache.
+template <int BM, int BN, int BK, bool WSTREAM = false>
 __global__ void __launch_bounds__(kThreads)
 linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const float *__restrict__ bias,
               const bf16_t *residual, OutSplit out, int64_t M, int64_t N, int64_t K, int vector_out)
@@ -134,7 +136,12 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
             const int64_t ch = k0 / 8 + chunk[i];
-            regs[i] = ch < kchunks ? src[i][ch] : make_uint4(0, 0, 0, 0);
+            if (WSTREAM && i * kThreads >= BM * kCpr) {         // chunks of w rows (whole multiples of the block: BM * kCpr % kThreads == 0)
+                const u32x4 t = ch < kchunks ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src[i] + ch)) : u32x4(0u);
+                regs[i] = make_uint4(t.x, t.y, t.z, t.w);
+            } else {
+                regs[i] = ch < kchunks ? src[i][ch] : make_uint4(0, 0, 0, 0);
+            }
         }
     };
     auto park = [&]() {
@@ -806,7 +813,10 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
         linear_kernel<64, 64, 256><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
     } else {
         dim3 grid((unsigned)((N + 63) / 64), (unsigned)((a.M + 63) / 64));
-        linear_kernel<64, 64, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
+        if (a.M <= 64 && N >= 8192)
+            linear_kernel<64, 64, 64, true><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
+        else
+            linear_kernel<64, 64, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
     }
     return hipGetLastError();
 }

@@ -751,6 +751,8 @@ def test_scan_invariants_at_size(m):
                                           (18, 3072, 768, (1536, 1536)), (12, 80, 1536, (48, 16, 16)), (32, 768, 1536, None),
                                           (33, 100, 520, (3, 90, 7)), (64, 50, 1544, None), (3, 1000, 72, None),
                                           (65, 96, 512, None),
+                                          # few rows, very wide (the LM head): tiled kernel with streaming weight loads
+                                          (12, 8200, 136, None), (64, 9000, 64, (8192, 808)),
                                           # more than a thousand 128 x 128 tiles (ragged edges, short and odd slab counts)
                                           (8190, 4100, 136, (2052, 2048)), (8192, 4096, 40, None), (8300, 4000, 32, (8, 3992)),
                                           # whole slabs only (K a multiple of 64): 1, 2, 3, 5 and 7 of them, ragged edges,
