@@ -5,10 +5,12 @@ One "step" is one pass of the whole hot path over one batch of synthetic input:
   prefill  conv1d + selective scan over the long context (Mamba-130M-shaped layer, batch 1,
            L = 32768 tokens, bf16 I/O, fp32 state), then
   decode   tree drafting over 24 such layers: 5 draft steps of 32 live branches; per draft step
-           one conv-state fork for all layers, and per layer a conv step and a state step with
-           the SSM-state fork fused in (parent index).  The 245 launches are captured once in a
-           HIP graph (every call has a fixed shape, which is what makes the paper's per-batch-size
-           graph cache possible, Sec. 4.1) and replayed; --eager-decode launches them one by one.
+           and layer one launch that forks the conv and SSM state by parent index, does the conv
+           step and the state update (checked bit for bit against the three-stage path: conv-state
+           fork, conv step, state step; --staged-decode times that one, 245 launches).  The 120
+           launches are captured once in a HIP graph (every call has a fixed shape, which is what
+           makes the paper's per-batch-size graph cache possible, Sec. 4.1) and replayed;
+           --eager-decode launches them one by one.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
 The roofline object covers the dominant call, the selective scan (its three kernels together),
@@ -76,6 +78,8 @@ def main():
                     help="skip the whole-drafter timing (Mamba-130M shapes, prefix encoding and draft rounds)")
     ap.add_argument("--no-tree-draft", action="store_true",
                     help="skip the sequential-versus-tree draft round timing")
+    ap.add_argument("--staged-decode", action="store_true",
+                    help="decode leg as fork + conv step + state step (245 launches) instead of one launch per layer and step")
     ap.add_argument("--eager-decode", action="store_true",
                     help="launch the decode kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--prefill", default="cfg3", help="synthetic config of the prefill leg")
@@ -135,7 +139,8 @@ def main():
         m.mamba_scan_fwd(xc, P["dt"], P["A"], P["Bm"], P["Cm"], P["Dskip"], P["z"], P["dt_bias"],
                          out=out, h_final=h_final, workspace=ws)
 
-    def decode_eager():
+    def decode_staged():
+        # three stages: conv-state fork for all layers, then per layer a conv step and a state step (SSM fork fused in)
         src_ssm, src_conv = ssm0, conv0
         for s in range(nsteps):
             dst_ssm, dst_conv = ssm[s & 1], conv[s & 1]
@@ -148,6 +153,30 @@ def main():
                                    LP[l]["Dskip"], t["z"], LP[l]["dt_bias"], parent_idx=PAR[s],
                                    h_out=dst_ssm[l], out=dout[s, l])
             src_ssm, src_conv = dst_ssm, dst_conv
+
+    def decode_fused():
+        # one launch per layer and draft step: fork of both states, conv step and state update together
+        src_ssm, src_conv = ssm0, conv0
+        for s in range(nsteps):
+            dst_ssm, dst_conv = ssm[s & 1], conv[s & 1]
+            for l in range(nl):
+                t = TOK[s][l]
+                m.mamba_conv_state_step(src_ssm[l], src_conv[l], t["x"], LP[l]["conv_w"], LP[l]["conv_bias"], t["dt"],
+                                        LP[l]["A"], t["Bm"], t["Cm"], LP[l]["Dskip"], t["z"], LP[l]["dt_bias"],
+                                        parent_idx=PAR[s], h_out=dst_ssm[l], conv_state_out=dst_conv[l], out=dout[s, l])
+            src_ssm, src_conv = dst_ssm, dst_conv
+
+    decode_eager = decode_staged if args.staged_decode else decode_fused
+    if not args.staged_decode:
+        # the single launch must give what the three stages give, bit for bit
+        decode_staged()
+        torch.cuda.synchronize()
+        st_out, st_ssm, st_conv = dout.clone(), ssm[(nsteps - 1) & 1].clone(), conv[(nsteps - 1) & 1].clone()
+        dout.zero_()
+        decode_fused()
+        torch.cuda.synchronize()
+        assert torch.equal(dout, st_out) and torch.equal(ssm[(nsteps - 1) & 1], st_ssm) and \
+            torch.equal(conv[(nsteps - 1) & 1], st_conv), "fused layer step differs from fork + conv step + state step"
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     prefill()
@@ -556,8 +585,13 @@ def main():
                 "frac_of_copy_kernel": round(achieved / copy_gbs, 4)},
     }
     units = nb * nsteps * nl
-    dec_bytes = nsteps * nl * (step_bytes(nb, Dd, Nd, ed) + nb * (2 * Dd * (Kd - 1) * ed + 2 * Dd * ed)) \
-        + nsteps * nl * nb * 2 * Dd * (Kd - 1) * ed
+    if args.staged_decode:
+        # state step + conv step (window in and out, x in, x_c out) + conv-state fork (window in and out)
+        dec_bytes = nsteps * nl * (step_bytes(nb, Dd, Nd, ed) + nb * (2 * Dd * (Kd - 1) * ed + 2 * Dd * ed)) \
+            + nsteps * nl * nb * 2 * Dd * (Kd - 1) * ed
+    else:
+        # one launch: the state step's bytes (its x is the input before the conv) + the window in and out
+        dec_bytes = nsteps * nl * (step_bytes(nb, Dd, Nd, ed) + nb * 2 * Dd * (Kd - 1) * ed)
     detail = {
         "prefill_conv_ms": round(conv_ms, 5), "prefill_scan_ms": round(scan_ms, 5),
         "prefill_tokens_per_s": round(tokens / ((conv_ms + scan_ms) * 1e-3), 1),
@@ -566,7 +600,8 @@ def main():
         "decode_ms": round(dec_ms, 5),
         "decode_branch_steps_per_s_per_layer": round(units / (dec_ms * 1e-3), 1),
         "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
-        "decode_launches": nsteps * (1 + 2 * nl), "decode_mode": "eager" if args.eager_decode else "hip_graph",
+        "decode_launches": nsteps * (1 + 2 * nl) if args.staged_decode else nsteps * nl,
+        "decode_stages": "fork + conv step + state step" if args.staged_decode else "one launch per layer and step (mamba_conv_state_step)", "decode_mode": "eager" if args.eager_decode else "hip_graph",
         "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide,
         "tree_draft_round": tree_detail, "whole_block": block_detail,
         "whole_drafter": drafter_detail, "mamba2_core": ssd_detail, "per_config": per_config,
@@ -579,8 +614,8 @@ def main():
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s prefill (conv1d+scan, batch %d x L=%d, D=%d, N=%d, %s I/O) + %s tree "
-                               "decode (%d layers x %d branches x %d draft steps, fork+conv step+state step)"
-                               % (args.prefill, B, L, D, N, pc["io"], args.decode, nl, nb, nsteps),
+                               "decode (%d layers x %d branches x %d draft steps, fork+conv step+state step%s)"
+                               % (args.prefill, B, L, D, N, pc["io"], args.decode, nl, nb, nsteps, "" if args.staged_decode else " in one launch per layer"),
                    "io_dtype": pc["io"], "state_dtype": "f32"},
         "roofline": roofline, "detail": detail,
     }

@@ -132,6 +132,31 @@ int mamba_state_step(float *h_out, const float *h_in, const int32_t *parent_idx,
                      void *hip_stream);
 
 /*
+ * Fork, conv step and state update of one layer for all branches in ONE launch (Sec. 4.1: tree
+ * drafting advances every branch of a depth at once, each child from a copy of its parent's conv
+ * and SSM state; this is the body of that loop for one layer).  x is the input BEFORE the conv:
+ *   p = parent_idx[j] (or j);  win = conv_state_in[p,d,:]
+ *   x_c[j,d] = act(conv_bias[d] + sum_{k<K-1} conv_w[d,k] win[k] + conv_w[d,K-1] x[j,d])
+ *   conv_state_out[j,d,:] = (win[1:], x[j,d])
+ *   then mamba_state_step on x_c rounded to the I/O type (h_out, out as there).
+ * The result is bit for bit what mamba_conv1d_fwd (L = 1, carried window gathered by parent) followed
+ * by mamba_state_step (same parent_idx) gives.
+ *   conv_state_in (n_in,D,K-1), conv_state_out (n_out,D,K-1), x, dt, z, out, xc_out (n_out,D),
+ *   Bm, Cm (n_out,N) in the I/O type; conv_w (D,K), conv_bias (D) or NULL, A, Dskip, dt_bias f32.
+ *   xc_out may be NULL (x_c is then not stored).  K in 2..4, N as for mamba_state_step.
+ * conv_state_out == conv_state_in and h_out == h_in are allowed only when parent_idx is NULL.
+ * A parent index outside [0,n_in) reads nothing out of bounds: that branch's states and outputs
+ * become NaN (its new window still ends with x[j,d]).
+ */
+int mamba_conv_state_step(float *h_out, const float *h_in, void *conv_state_out,
+                          const void *conv_state_in, const int32_t *parent_idx, const void *x,
+                          const float *conv_w, const float *conv_bias, const void *dt,
+                          const float *A, const void *Bm, const void *Cm, const float *Dskip,
+                          const void *z, const float *dt_bias, void *out, void *xc_out,
+                          int64_t n_out, int64_t n_in, int64_t D, int64_t N, int K, int apply_silu,
+                          int dt_softplus, mamba_dtype_t io, void *hip_stream);
+
+/*
  * State copy by parent index for all layers at once (Sec. 4.1: creating the children
  * of a node "only requires copying the current state"; destination buffers are the
  * pre-allocated caches of the next batch size, hence out of place):

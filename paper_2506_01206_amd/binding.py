@@ -92,13 +92,15 @@ def _declare(lib):
     lib.mamba_state_step.restype = _int
     lib.mamba_state_fork.argtypes = [_vp] * 5 + [_i64] * 5 + [_int, _int, _vp]
     lib.mamba_state_fork.restype = _int
+    lib.mamba_conv_state_step.argtypes = [_vp] * 17 + [_i64] * 4 + [_int] * 4 + [_vp]
+    lib.mamba_conv_state_step.restype = _int
     return lib
 
 
 lib = _declare(ctypes.CDLL(LIB_PATH))
 
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
-           "mamba_scan_fwd", "mamba_state_step", "mamba_state_fork", "mamba_tree_plan",
+           "mamba_scan_fwd", "mamba_state_step", "mamba_conv_state_step", "mamba_state_fork", "mamba_tree_plan",
            "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "mamba_block_workspace_bytes",
            "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd",
            "mamba2_ssd_workspace_bytes", "mamba2_ssd_fwd", "mamba2_state_step")
@@ -218,6 +220,40 @@ def mamba_state_step(h_in, x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, p
         n_out, n_in, D, N, int(bool(dt_softplus)), io, _stream(stream))
     _check("mamba_state_step", st)
     return h_out, out
+
+
+def mamba_conv_state_step(h_in, conv_state_in, x, conv_w, conv_bias, dt, A, Bm, Cm, Dskip=None, z=None,
+                          dt_bias=None, parent_idx=None, h_out=None, conv_state_out=None, out=None, xc_out=None,
+                          want_xc=False, apply_silu=True, dt_softplus=True, stream=None):
+    """Fork + conv step + state update of one layer in one launch.  h_in (n_in,D,N) f32, conv_state_in
+    (n_in,D,K-1), x (n_out,D) the input before the conv, conv_w (D,K) f32; the rest as mamba_state_step.
+    -> h_out, conv_state_out (n_out,D,K-1), out (n_out,D), x_c (n_out,D) or None."""
+    n_in, D, N = h_in.shape
+    n_out = x.shape[0]
+    K = conv_w.shape[1]
+    io = _io_code(x)
+    if h_out is None:
+        h_out = torch.empty((n_out, D, N), dtype=torch.float32, device=x.device)
+    if conv_state_out is None:
+        conv_state_out = torch.empty((n_out, D, K - 1), dtype=x.dtype, device=x.device)
+    if out is None:
+        out = torch.empty_like(x)
+    if xc_out is None and want_xc:
+        xc_out = torch.empty_like(x)
+    st = lib.mamba_conv_state_step(
+        _ptr(h_out, torch.float32, (n_out, D, N), "h_out"), _ptr(h_in, torch.float32, name="h_in"),
+        _ptr(conv_state_out, x.dtype, (n_out, D, K - 1), "conv_state_out"),
+        _ptr(conv_state_in, x.dtype, (n_in, D, K - 1), "conv_state_in"),
+        _ptr(parent_idx, torch.int32, (n_out,), "parent_idx"), _ptr(x, name="x"),
+        _ptr(conv_w, torch.float32, (D, K), "conv_w"), _ptr(conv_bias, torch.float32, (D,), "conv_bias"),
+        _ptr(dt, x.dtype, (n_out, D), "dt"), _ptr(A, torch.float32, (D, N), "A"),
+        _ptr(Bm, x.dtype, (n_out, N), "Bm"), _ptr(Cm, x.dtype, (n_out, N), "Cm"),
+        _ptr(Dskip, torch.float32, (D,), "Dskip"), _ptr(z, x.dtype, (n_out, D), "z"),
+        _ptr(dt_bias, torch.float32, (D,), "dt_bias"), _ptr(out, x.dtype, (n_out, D), "out"),
+        _ptr(xc_out, x.dtype, (n_out, D), "xc_out"),
+        n_out, n_in, D, N, K, int(bool(apply_silu)), int(bool(dt_softplus)), io, _stream(stream))
+    _check("mamba_conv_state_step", st)
+    return h_out, conv_state_out, out, xc_out
 
 
 def mamba_state_fork(conv_src, ssm_src, parent_idx, conv_dst=None, ssm_dst=None, stream=None):

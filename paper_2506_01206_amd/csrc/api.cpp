@@ -168,6 +168,63 @@ int mamba_state_step(float *h_out, const float *h_in, const int32_t *parent_idx,
     return (int)launch_step(a, static_cast<hipStream_t>(hip_stream));
 }
 
+int mamba_conv_state_step(float *h_out, const float *h_in, void *conv_state_out, const void *conv_state_in,
+                          const int32_t *parent_idx, const void *x, const float *conv_w, const float *conv_bias,
+                          const void *dt, const float *A, const void *Bm, const void *Cm, const float *Dskip,
+                          const void *z, const float *dt_bias, void *out, void *xc_out, int64_t n_out, int64_t n_in,
+                          int64_t D, int64_t N, int K, int apply_silu, int dt_softplus, mamba_dtype_t io,
+                          void *hip_stream)
+{
+    const int e = io_size(io);
+    if (e == 0) return MAMBA_ERR_UNSUPPORTED;
+    if (N < 0) return MAMBA_ERR_BAD_SHAPE;
+    if (K < 2 || K > 4) return MAMBA_ERR_UNSUPPORTED;
+    int64_t out_bytes, hin_bytes, hout_bytes, cin_bytes, cout_bytes;
+    if (!size3(n_out, D, 1, e, &out_bytes) || !size3(n_in, D, N, 4, &hin_bytes) ||
+        !size3(n_out, D, N, 4, &hout_bytes) || !size3(n_in, D, K - 1, e, &cin_bytes) ||
+        !size3(n_out, D, K - 1, e, &cout_bytes))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (!parent_idx && n_in != n_out) return MAMBA_ERR_BAD_SHAPE;
+    if (n_out > 0 && n_in == 0) return MAMBA_ERR_BAD_SHAPE;
+    if (!n_supported(N) || n_out > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    if (n_out == 0 || D == 0) return MAMBA_OK;
+    if (!h_out || !h_in || !conv_state_out || !conv_state_in || !x || !conv_w || !dt || !A || !Bm || !Cm || !out)
+        return MAMBA_ERR_NULL_POINTER;
+    if (!aligned16(h_out) || !aligned16(h_in) || !aligned16(conv_state_out) || !aligned16(conv_state_in) ||
+        !aligned16(parent_idx) || !aligned16(x) || !aligned16(conv_w) || !aligned16(conv_bias) || !aligned16(dt) ||
+        !aligned16(A) || !aligned16(Bm) || !aligned16(Cm) || !aligned16(Dskip) || !aligned16(z) ||
+        !aligned16(dt_bias) || !aligned16(out) || !aligned16(xc_out))
+        return MAMBA_ERR_MISALIGNED;
+    if (!(h_out == h_in && !parent_idx) && overlap(h_out, hout_bytes, h_in, hin_bytes)) return MAMBA_ERR_ALIAS;
+    if (!(conv_state_out == conv_state_in && !parent_idx) && overlap(conv_state_out, cout_bytes, conv_state_in, cin_bytes))
+        return MAMBA_ERR_ALIAS;
+    // no output may overlap an input or another output
+    const void *outs[4] = {h_out, conv_state_out, out, xc_out};
+    const int64_t out_sz[4] = {hout_bytes, cout_bytes, out_bytes, out_bytes};
+    const void *ins[5] = {x, dt, z, h_in, conv_state_in};
+    const int64_t in_sz[5] = {out_bytes, out_bytes, out_bytes, hin_bytes, cin_bytes};
+    for (int i = 0; i < 4; ++i) {
+        if (!outs[i]) continue;
+        for (int k = i + 1; k < 4; ++k)
+            if (outs[k] && overlap(outs[i], out_sz[i], outs[k], out_sz[k])) return MAMBA_ERR_ALIAS;
+        for (int k = 0; k < 5; ++k) {
+            if (!ins[k]) continue;
+            if ((i == 0 && k == 3) || (i == 1 && k == 4)) continue;      // the in-place pairs were judged above
+            if (overlap(outs[i], out_sz[i], ins[k], in_sz[k])) return MAMBA_ERR_ALIAS;
+        }
+    }
+    StepArgs a{h_out, h_in, parent_idx, x, dt, Bm, Cm, z, A, Dskip, dt_bias, out,
+               n_out, n_in, D, (int)N, (int)io, dt_softplus};
+    a.conv_w = conv_w;
+    a.conv_bias = conv_bias;
+    a.conv_src = conv_state_in;
+    a.conv_dst = conv_state_out;
+    a.xc_out = xc_out;
+    a.conv_k = K;
+    a.conv_silu = apply_silu ? 1 : 0;
+    return (int)launch_step(a, static_cast<hipStream_t>(hip_stream));
+}
+
 int mamba_state_fork(void *conv_dst, const void *conv_src, float *ssm_dst, const float *ssm_src,
                      const int32_t *parent_idx, int64_t n_layers, int64_t n_out, int64_t n_in,
                      int64_t D, int64_t N, int K, mamba_dtype_t conv_dtype, void *hip_stream)

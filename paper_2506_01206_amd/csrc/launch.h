@@ -91,6 +91,13 @@ struct StepArgs {
     // would be; dt, Bm, Cm are then not read (needs dt_w, dt_rank + 2 N <= 256)
     const float *xpart = nullptr;
     int n_parts = 0;
+    // with conv_w ((D, conv_k) float32) the kernel also does the conv step: ``x`` is then the input before the conv,
+    // conv_src (n_in, D, conv_k - 1) the carried windows (read through the parent index), conv_dst (n_out, D, conv_k - 1)
+    // the new ones, xc_out (n_out, D) the conv output if wanted; conv_k in 2..4
+    const float *conv_w = nullptr, *conv_bias = nullptr;
+    const void *conv_src = nullptr;
+    void *conv_dst = nullptr, *xc_out = nullptr;
+    int conv_k = 0, conv_silu = 1;
 };
 hipError_t launch_step(const StepArgs &a, hipStream_t stream);
 

@@ -152,6 +152,119 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
     }
 }
 
+// Fork, conv step and state update of one layer in a single launch (Sec. 4.1: a child continues from its parent's
+// states; the draft loop of a tree is this, once per layer and position).  x is the input *before* the conv:
+//   win = conv_src[p, d, :];  a = conv_bias[d] + sum_k w[d,k] win[k] + w[d,K-1] x[j,d];  x_c = silu(a)
+//   conv_dst[j, d, :] = (win[1..], x[j,d]);  then the step above on x_c rounded to the I/O type
+// in the arithmetic order of the conv kernel and of the step kernel, so that the result is bit for bit what
+// mamba_conv1d_fwd (L = 1, through the parent index) followed by mamba_state_step gives.  The N/4 lanes of a channel
+// all evaluate the conv (a handful of operations); the first of them writes the new window and x_c.
+// grid: (ceil(D * N / 4 / (256 * U)), n_out)
+template <typename T, int N, int U, bool HAS_Z, bool SOFTPLUS>
+__global__ void __launch_bounds__(kBlock)
+state_step_conv_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ parent,
+                       const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
+                       const T *__restrict__ Bm, const T *__restrict__ Cm,
+                       const float *__restrict__ Dskip, const T *__restrict__ z,
+                       const float *__restrict__ dt_bias, T *__restrict__ out, int64_t n_in, int64_t D,
+                       const float *__restrict__ conv_w, const float *__restrict__ conv_bias, const T *conv_src,
+                       T *conv_dst, T *__restrict__ xc_out, int conv_k, int conv_silu)
+{
+    constexpr int Q = N / 4;
+    const int H = conv_k - 1;                                     // 1 .. 3 carried inputs per channel
+    const int64_t j = blockIdx.y;
+    const int64_t row4 = D * Q;  // float4s per branch
+    const float4 *a4 = reinterpret_cast<const float4 *>(A);
+
+    int64_t f[U], d[U];
+    bool live[U];
+    float4 h[U], a[U], bv[U], cv[U];
+    float xpre[U], dv[U], zv[U], bias[U], dsk[U], wk[U][4], cb[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const int64_t f_raw = ((int64_t)blockIdx.x * U + i) * kBlock + threadIdx.x;
+        live[i] = f_raw < row4;
+        f[i] = live[i] ? f_raw : row4 - 1;
+        d[i] = f[i] / Q;
+        const int q = (int)(f[i] - d[i] * Q);
+        a[i] = a4[f[i]];
+        bv[i] = ld4_io<N>(Bm + j * N + 4 * q);
+        cv[i] = ld4_io<N>(Cm + j * N + 4 * q);
+        xpre[i] = ld_io(x, j * D + d[i]);
+        dv[i] = ld_io(dt, j * D + d[i]);
+        zv[i] = HAS_Z ? ld_io(z, j * D + d[i]) : 0.0f;
+        bias[i] = dt_bias ? dt_bias[d[i]] : 0.0f;
+        dsk[i] = Dskip ? Dskip[d[i]] : 0.0f;
+        cb[i] = conv_bias ? conv_bias[d[i]] : 0.0f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) wk[i][k] = k <= H ? conv_w[d[i] * conv_k + k] : 0.0f;
+    }
+    // the state row and the window are the loads that have to wait for the parent index
+    const int64_t p = parent ? (int64_t)parent[j] : j;
+    const bool p_ok = p >= 0 && p < n_in;
+    const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
+    float carried[U][3];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        h[i] = ld_stream(hin4 + f[i]);
+        const T *win = conv_src + ((p_ok ? p : 0) * D + d[i]) * H;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) carried[i][k] = k < H ? ld_io(win, k) : 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        // conv step, same order of operations as the conv kernel: bias, taps oldest to newest, then the new input
+        float acc = cb[i];
+#pragma unroll
+        for (int k = 0; k < 3; ++k)
+            if (k < H) acc = fmaf(wk[i][k], carried[i][k], acc);
+        float wlast = wk[i][0];
+#pragma unroll
+        for (int k = 1; k < 4; ++k)
+            if (k == H) wlast = wk[i][k];
+        acc = fmaf(wlast, xpre[i], acc);
+        const float xc = conv_silu ? silu_f32(acc) : acc;
+        // the stored tensor the step would read
+        const float xv = sizeof(T) == 2 ? bf16_to_f32(f32_to_bf16(xc)) : xc;
+
+        const float v = dv[i] + bias[i];
+        const float delta = SOFTPLUS ? softplus_f32(v) : v;
+        const float u = delta * xv;
+        const float dl = delta * kLog2e;
+        float4 hh = h[i];
+        hh.x = fmaf(exp2_hw(dl * a[i].x), hh.x, u * bv[i].x);
+        hh.y = fmaf(exp2_hw(dl * a[i].y), hh.y, u * bv[i].y);
+        hh.z = fmaf(exp2_hw(dl * a[i].z), hh.z, u * bv[i].z);
+        hh.w = fmaf(exp2_hw(dl * a[i].w), hh.w, u * bv[i].w);
+        float y = hh.x * cv[i].x;
+        y = fmaf(hh.y, cv[i].y, y);
+        y = fmaf(hh.z, cv[i].z, y);
+        y = fmaf(hh.w, cv[i].w, y);
+        y = channel_sum<Q>(y);
+        const float nan = __int_as_float(0x7fc00000);
+        if (!p_ok) {
+            hh = make_float4(nan, nan, nan, nan);
+            y = nan;
+        }
+        if (live[i]) {
+            st_stream(reinterpret_cast<float4 *>(h_out) + j * row4 + f[i], hh);
+            if (f[i] - d[i] * Q == 0) {
+                y = fmaf(dsk[i], xv, y);
+                if constexpr (HAS_Z) y *= silu_f32(zv[i]);
+                st_io(out, j * D + d[i], y);
+                // new window: the carried inputs move up, the new input comes last (NaN where the parent was bad,
+                // as the conv kernel leaves it)
+                T *nwin = conv_dst + (j * D + d[i]) * H;
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+                    if (k + 1 < H) st_io(nwin, k, p_ok ? carried[i][k + 1] : nan);
+                st_io(nwin, H - 1, xpre[i]);
+                if (xc_out) st_io(xc_out, j * D + d[i], p_ok ? xc : nan);
+            }
+        }
+    }
+}
+
 // The same step for a draft position of the whole block, where the x projection arrives as partial sums (see
 // StepArgs::xpart): what does not depend on it (the state row above all) is requested first, then the parts are
 // added up, and dt (through the fused dt projection), B and C come out of LDS.  Kept apart from the plain kernel,
@@ -310,6 +423,28 @@ template <typename T, int N, int U> hipError_t launch_step_u(const StepArgs &a, 
         static_cast<const T *>(a.Bm), static_cast<const T *>(a.Cm), a.Dskip,                      \
         static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D,                \
         static_cast<const bf16_t *>(a.dt_w), a.dt_rank, a.xpart, a.n_parts)
+    if (a.conv_w) {
+        if constexpr (U == 2) {
+            return hipErrorInvalidValue;                          // the conv variant is built for U = 1 and 4 only (see launch_step_n)
+        } else {
+#define MAMBA_STEP_C(HZ, SP)                                                                      \
+    state_step_conv_kernel<T, N, U, HZ, SP><<<grid, kBlock, 0, stream>>>(                         \
+        a.h_out, a.h_in, a.parent, static_cast<const T *>(a.x), static_cast<const T *>(a.dt), a.A, \
+        static_cast<const T *>(a.Bm), static_cast<const T *>(a.Cm), a.Dskip,                      \
+        static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D, a.conv_w,   \
+        a.conv_bias, static_cast<const T *>(a.conv_src), static_cast<T *>(a.conv_dst),             \
+        static_cast<T *>(a.xc_out), a.conv_k, a.conv_silu)
+            if (a.z) {
+                if (a.dt_softplus) MAMBA_STEP_C(true, true);
+                else MAMBA_STEP_C(true, false);
+            } else {
+                if (a.dt_softplus) MAMBA_STEP_C(false, true);
+                else MAMBA_STEP_C(false, false);
+            }
+#undef MAMBA_STEP_C
+            return hipGetLastError();
+        }
+    }
     if (a.xpart && a.dt_w) {
         if (a.z) {
             if (a.dt_softplus) MAMBA_STEP_X(true, true);
@@ -338,7 +473,7 @@ template <typename T, int N> hipError_t launch_step_n(const StepArgs &a, hipStre
     const int64_t row4 = a.D * (N / 4);
     auto blocks = [&](int u) { return a.n_out * ((row4 + kBlock * u - 1) / (kBlock * u)); };
     if (blocks(MAMBA_STEP_UNROLL) >= 768) return launch_step_u<T, N, MAMBA_STEP_UNROLL>(a, stream);
-    if (MAMBA_STEP_UNROLL > 2 && blocks(2) >= 768) return launch_step_u<T, N, 2>(a, stream);
+    if (MAMBA_STEP_UNROLL > 2 && blocks(2) >= 768 && !a.conv_w) return launch_step_u<T, N, 2>(a, stream);
     return launch_step_u<T, N, 1>(a, stream);
 }
 

@@ -7,9 +7,9 @@ size plus the parent-index arrays, and keeps one captured HIP graph per draft po
 call there has the fixed shape (B_i, 1), which is what makes the capture possible).  It only
 arranges buffers and launches: every computation is a call into the C-ABI kernels.
 
-The per-layer work of a draft position is what the selective-SSM core does there: the conv-state
-rows of all layers are copied by parent index, then every layer runs its conv step on the new
-token's features and its selective state update with the SSM-state copy fused in.  What lies
+The per-layer work of a draft position is what the selective-SSM core does there: the conv and SSM
+state rows are taken from the parent, the layer runs its conv step on the new token's features and
+its selective state update, all in one launch per layer (``mamba_conv_state_step``).  What lies
 between those two in a full model (the projections that produce dt, B, C) is not part of this
 library, so the caller provides the per-layer token tensors in the static input buffers
 ``inputs[i][l]`` before a position is run.
@@ -60,12 +60,21 @@ class TreeDraftCache:
         self.conv[0].copy_(conv_state)
         self.ssm[0].copy_(ssm_state)
 
-    def run_position(self, i, params):
+    def run_position(self, i, params, staged=False):
         """Eager launches for draft position i (1-based). ``params[l]`` holds A, Dskip, dt_bias,
-        conv_w, conv_bias of layer l."""
+        conv_w, conv_bias of layer l.  One launch per layer (fork of both states, conv step and state
+        update); ``staged`` runs the same as conv-state fork, conv step and state step instead."""
         src, dst = self.cache_index(i - 1), self.cache_index(i)
         par = self.parent[i]
         inp = self.inputs[i]
+        if not staged:
+            for l in range(self.n_layers):
+                p = params[l]
+                m.mamba_conv_state_step(self.ssm[src][l], self.conv[src][l], inp["x"][l], p["conv_w"], p["conv_bias"],
+                                        inp["dt"][l], p["A"], inp["Bm"][l], inp["Cm"][l], p["Dskip"], inp["z"][l],
+                                        p["dt_bias"], parent_idx=par, h_out=self.ssm[dst][l],
+                                        conv_state_out=self.conv[dst][l], out=self.out[i][l])
+            return
         if par is not None:
             m.mamba_state_fork(self.conv[src], None, par, conv_dst=self.conv[dst])
         for l in range(self.n_layers):

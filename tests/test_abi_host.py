@@ -159,6 +159,35 @@ def test_step_validation(b):
     assert step(b, D=0) == 0
 
 
+def conv_step(b, ho=P(0), hi=P(1), co=P(2), ci=P(3), par=P(4), x=P(5), cw=P(6), cb=P(7), dt=P(8), A=P(9), Bm=P(10),
+              Cm=P(11), Dk=P(12), z=P(13), bias=P(14), out=P(15), xc=P(16), n_out=8, n_in=4, D=64, N=16, K=4, silu=1,
+              sp=1, io=1):
+    return b.lib.mamba_conv_state_step(ho, hi, co, ci, par, x, cw, cb, dt, A, Bm, Cm, Dk, z, bias, out, xc, n_out, n_in,
+                                       D, N, K, silu, sp, io, None)
+
+
+def test_conv_state_step_validation(b):
+    S = b.STATUS
+    assert conv_step(b, ci=None) == S["NULL_POINTER"]
+    assert conv_step(b, cw=None) == S["NULL_POINTER"]
+    assert conv_step(b, co=None) == S["NULL_POINTER"]
+    assert conv_step(b, K=1) == S["UNSUPPORTED"]
+    assert conv_step(b, K=5) == S["UNSUPPORTED"]
+    assert conv_step(b, N=12) == S["UNSUPPORTED"]
+    assert conv_step(b, io=7) == S["UNSUPPORTED"]
+    assert conv_step(b, par=None) == S["BAD_SHAPE"]                  # identity needs n_in == n_out
+    assert conv_step(b, n_in=0) == S["BAD_SHAPE"]
+    assert conv_step(b, ho=P(1)) == S["ALIAS"]                       # in place only without a parent index
+    assert conv_step(b, co=P(3)) == S["ALIAS"]
+    assert conv_step(b, co=P(3) + 32, par=None, n_in=8) == S["ALIAS"]   # partial overlap never
+    assert conv_step(b, xc=P(15)) == S["ALIAS"]                      # two outputs on each other
+    assert conv_step(b, out=P(5)) == S["ALIAS"]                      # output on an input
+    assert conv_step(b, co=P(1)) == S["ALIAS"]                       # new windows on the old SSM state
+    assert conv_step(b, x=P(5) + 2) == S["MISALIGNED"]
+    assert conv_step(b, xc=None, cb=None, Dk=None, z=None, bias=None, n_out=0) == 0
+    assert conv_step(b, D=0) == 0
+
+
 def fork(b, cd=P(0), cs=P(1), sd=P(2), ss=P(3), par=P(4), nl=24, n_out=8, n_in=4, D=64, N=16, K=4,
          io=1):
     return b.lib.mamba_state_fork(cd, cs, sd, ss, par, nl, n_out, n_in, D, N, K, io, None)

@@ -255,6 +255,53 @@ def test_step_against_oracle(m, io, N, D):
         assert_close(values(to_host(o)), ro, TOL[io], "step out")
 
 
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("N,D,K", [(16, 1536, 4), (4, 17, 2), (8, 100, 3), (32, 64, 4), (16, 1, 4), (16, 4096, 4)])
+def test_conv_state_step_equals_conv_then_step(m, io, N, D, K):
+    """One launch against the two-stage path (conv step through the parent index, then the state step), bit for
+    bit, with and without gate / skip / conv bias / SiLU, a bad parent among the branches, and in place without
+    a parent index; the two-stage path itself is compared with the oracle elsewhere."""
+    say(io=io, N=N, D=D, K=K)
+    n_in, n_out = 5, (70 if D >= 1536 else 11)
+    rng = np.random.default_rng(N * 1000 + D + K)
+    p = synth.layer_params(rng, D, N, K, random_A=True)
+    p["conv_bias"] = rng.standard_normal(D).astype(np.float32)
+    tok = synth.token_inputs(rng, (n_out,), D, N, io)
+    h_in = to_dev(rng.standard_normal((n_in, D, N)).astype(np.float32))
+    c_in = to_dev(synth.to_io(rng.standard_normal((n_in, D, K - 1)).astype(np.float32), io))
+    parent = rng.integers(0, n_in, n_out).astype(np.int32)
+    parent[3] = n_in + 2                                        # out of range: that branch becomes NaN in both paths
+    par = to_dev(parent)
+    g = {k: to_dev(v) for k, v in tok.items()}
+    P = {k: to_dev(v) for k, v in p.items()}
+    good = torch.as_tensor([j for j in range(n_out) if j != 3], device=DEV)
+    for gate, skip, cbias, silu in ((True, True, True, True), (False, False, False, False), (True, False, True, False)):
+        forked, _ = m.mamba_state_fork(c_in.unsqueeze(0), None, par)
+        xc, cst = m.mamba_conv1d_fwd(g["x"].unsqueeze(1), P["conv_w"], P["conv_bias"] if cbias else None,
+                                     conv_state_in=forked[0], apply_silu=silu)
+        ho, o = m.mamba_state_step(h_in, xc.squeeze(1), g["dt"], P["A"], g["Bm"], g["Cm"], P["Dskip"] if skip else None,
+                                   g["z"] if gate else None, P["dt_bias"], parent_idx=par)
+        ho2, cst2, o2, xc2 = m.mamba_conv_state_step(h_in, c_in, g["x"], P["conv_w"], P["conv_bias"] if cbias else None,
+                                                     g["dt"], P["A"], g["Bm"], g["Cm"], P["Dskip"] if skip else None,
+                                                     g["z"] if gate else None, P["dt_bias"], parent_idx=par,
+                                                     want_xc=True, apply_silu=silu)
+        same = lambda a, b: to_host(a[good]).tobytes() == to_host(b[good]).tobytes()
+        assert same(ho, ho2) and same(o, o2) and same(cst, cst2) and same(xc.squeeze(1), xc2)
+        # the branch with the bad parent: NaN everywhere, except that its new window ends with its own input
+        for t in (ho2[3], o2[3], xc2[3], cst2[3][:, :-1]):
+            assert torch.isnan(t.float()).all()
+        assert torch.equal(cst2[3][:, -1], g["x"][3])
+    # sequential decode: no parent index, both states updated in place
+    h = h_in.clone()
+    c = c_in.clone()
+    x5 = {k: v[:n_in].contiguous() for k, v in g.items()}
+    xc, cst = m.mamba_conv1d_fwd(x5["x"].unsqueeze(1), P["conv_w"], P["conv_bias"], conv_state_in=c_in)
+    ho, o = m.mamba_state_step(h_in, xc.squeeze(1), x5["dt"], P["A"], x5["Bm"], x5["Cm"], P["Dskip"], x5["z"], P["dt_bias"])
+    _, _, o2, _ = m.mamba_conv_state_step(h, c, x5["x"], P["conv_w"], P["conv_bias"], x5["dt"], P["A"], x5["Bm"], x5["Cm"],
+                                          P["Dskip"], x5["z"], P["dt_bias"], h_out=h, conv_state_out=c)
+    assert torch.equal(h, ho) and torch.equal(c, cst) and torch.equal(o, o2)
+
+
 def test_step_rejects_out_of_range_parent_without_reading(m):
     D, N = 64, 16
     rng = np.random.default_rng(0)
@@ -417,7 +464,8 @@ def test_cfg3_long_prefill_sampled_channels(m):
 
 def decode_chain_gpu(m, dc, fused):
     """fork -> conv step -> state step for every layer and draft step; returns final states and
-    all step outputs."""
+    all step outputs.  fused: False (three stages), True (the SSM gather inside the step), "all" (one launch
+    per layer: mamba_conv_state_step)."""
     nl, nb = dc["n_layers"], dc["branches"]
     ssm = to_dev(dc["ssm0"])
     conv = to_dev(dc["conv0"])
@@ -425,6 +473,17 @@ def decode_chain_gpu(m, dc, fused):
     outs = []
     for s in range(dc["steps"]):
         par = to_dev(dc["parents"][s])
+        if fused == "all":
+            conv_next, ssm_next = torch.empty_like(conv), torch.empty_like(ssm)
+            for l in range(nl):
+                tok = {k: to_dev(v) for k, v in dc["tokens"][s][l].items()}
+                _, _, o, _ = m.mamba_conv_state_step(ssm[l], conv[l], tok["x"], P[l]["conv_w"], P[l]["conv_bias"],
+                                                     tok["dt"], P[l]["A"], tok["Bm"], tok["Cm"], P[l]["Dskip"], tok["z"],
+                                                     P[l]["dt_bias"], parent_idx=par, h_out=ssm_next[l],
+                                                     conv_state_out=conv_next[l])
+                outs.append(o)
+            conv, ssm = conv_next, ssm_next
+            continue
         if fused:
             conv, _ = m.mamba_state_fork(conv, None, par)
             ssm_next = torch.empty_like(ssm)
@@ -475,6 +534,9 @@ def test_cfg2_tree_decode_fused_and_unfused(m):
     conv_f, ssm_f, out_f = decode_chain_gpu(m, dc, fused=True)
     # fusing the gather into the step changes no bit
     assert torch.equal(ssm_u, ssm_f) and torch.equal(conv_u, conv_f) and torch.equal(out_u, out_f)
+    # nor does doing fork, conv step and state update of a layer in one launch
+    conv_a, ssm_a, out_a = decode_chain_gpu(m, dc, fused="all")
+    assert torch.equal(ssm_u, ssm_a) and torch.equal(conv_u, conv_a) and torch.equal(out_u, out_a)
     layers = [0, 7, 23]
     rconv, rssm, routs = decode_chain_oracle(dc, layers)
     nl = dc["n_layers"]
