@@ -487,13 +487,17 @@ def main():
                                                   ssm_dst=hout[i].unsqueeze(0))
             conv_i = lambda i: m.mamba_conv1d_fwd(tk["x"].unsqueeze(1), lp["conv_w"], lp["conv_bias"],
                                                   conv_state_in=cout[i], y=sxc, conv_state_out=cout[i])
+            full_i = lambda i: m.mamba_conv_state_step(hin[i], cin[i], tk["x"], lp["conv_w"], lp["conv_bias"], tk["dt"],
+                                                       lp["A"], tk["Bm"], tk["Cm"], lp["Dskip"], tk["z"], lp["dt_bias"],
+                                                       parent_idx=par, h_out=hout[i], conv_state_out=cout[i], out=so)
             sb_ = step_bytes(cnb, cD, cN, ce)
             fb_ = cnb * 2 * (cD * cN * 4 + cD * (cK - 1) * ce)
             cb_ = cnb * (2 * cD * (cK - 1) * ce + 2 * cD * ce)
             ent = {"shape": "%d branches, D %d, N %d, K %d, %s I/O, one layer; %d rotating buffer sets" %
                             (cnb, cD, cN, cK, c["io"], R)}
             for label, fn_i, nbytes in (("state_step_fused_parent", step_i, sb_), ("state_fork_unfused", fork_i, fb_),
-                                        ("conv_step", conv_i, cb_)):
+                                        ("conv_step", conv_i, cb_),
+                                        ("fork_conv_step_state_step_one_launch", full_i, sb_ + cnb * 2 * cD * (cK - 1) * ce)):
                 cold = graph_us(lambda: [fn_i(i) for i in range(R)], R)
                 warm = graph_us(lambda: [fn_i(0) for _ in range(R)], R)
                 ent[label] = {"algorithmic_bytes": nbytes, "cold_us": round(cold, 3), "warm_us": round(warm, 3),

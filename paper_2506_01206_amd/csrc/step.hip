@@ -157,8 +157,11 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
 //   win = conv_src[p, d, :];  a = conv_bias[d] + sum_k w[d,k] win[k] + w[d,K-1] x[j,d];  x_c = silu(a)
 //   conv_dst[j, d, :] = (win[1..], x[j,d]);  then the step above on x_c rounded to the I/O type
 // in the arithmetic order of the conv kernel and of the step kernel, so that the result is bit for bit what
-// mamba_conv1d_fwd (L = 1, through the parent index) followed by mamba_state_step gives.  The N/4 lanes of a channel
-// all evaluate the conv (a handful of operations); the first of them writes the new window and x_c.
+// mamba_conv1d_fwd (L = 1, on the window gathered by parent) followed by mamba_state_step gives.
+// The workgroup's channels (256 U / (N/4) of them) are convolved first, one channel per thread: window, taps,
+// bias and input are loaded once per channel, not once per lane (with the conv evaluated by every lane of a channel
+// the wide step was bound by the issue of its many small loads: 17.7 us against 13.1 us for two launches); x_c goes
+// through LDS to the lanes that own the channel's states, whose state rows are already on their way by then.
 // grid: (ceil(D * N / 4 / (256 * U)), n_out)
 template <typename T, int N, int U, bool HAS_Z, bool SOFTPLUS>
 __global__ void __launch_bounds__(kBlock)
@@ -171,15 +174,18 @@ state_step_conv_kernel(float *h_out, const float *h_in, const int32_t *__restric
                        T *conv_dst, T *__restrict__ xc_out, int conv_k, int conv_silu)
 {
     constexpr int Q = N / 4;
+    constexpr int kChannels = kBlock * U / Q;                     // channels whose states this workgroup owns
+    __shared__ float xs[kChannels];
     const int H = conv_k - 1;                                     // 1 .. 3 carried inputs per channel
     const int64_t j = blockIdx.y;
     const int64_t row4 = D * Q;  // float4s per branch
+    const int64_t d_lo = (int64_t)blockIdx.x * kChannels;
     const float4 *a4 = reinterpret_cast<const float4 *>(A);
 
     int64_t f[U], d[U];
     bool live[U];
     float4 h[U], a[U], bv[U], cv[U];
-    float xpre[U], dv[U], zv[U], bias[U], dsk[U], wk[U][4], cb[U];
+    float dv[U], zv[U], bias[U], dsk[U];
 #pragma unroll
     for (int i = 0; i < U; ++i) {
         const int64_t f_raw = ((int64_t)blockIdx.x * U + i) * kBlock + threadIdx.x;
@@ -190,43 +196,56 @@ state_step_conv_kernel(float *h_out, const float *h_in, const int32_t *__restric
         a[i] = a4[f[i]];
         bv[i] = ld4_io<N>(Bm + j * N + 4 * q);
         cv[i] = ld4_io<N>(Cm + j * N + 4 * q);
-        xpre[i] = ld_io(x, j * D + d[i]);
         dv[i] = ld_io(dt, j * D + d[i]);
         zv[i] = HAS_Z ? ld_io(z, j * D + d[i]) : 0.0f;
         bias[i] = dt_bias ? dt_bias[d[i]] : 0.0f;
         dsk[i] = Dskip ? Dskip[d[i]] : 0.0f;
-        cb[i] = conv_bias ? conv_bias[d[i]] : 0.0f;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) wk[i][k] = k <= H ? conv_w[d[i] * conv_k + k] : 0.0f;
     }
     // the state row and the window are the loads that have to wait for the parent index
     const int64_t p = parent ? (int64_t)parent[j] : j;
     const bool p_ok = p >= 0 && p < n_in;
     const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
-    float carried[U][3];
 #pragma unroll
-    for (int i = 0; i < U; ++i) {
-        h[i] = ld_stream(hin4 + f[i]);
-        const T *win = conv_src + ((p_ok ? p : 0) * D + d[i]) * H;
+    for (int i = 0; i < U; ++i) h[i] = ld_stream(hin4 + f[i]);
+
+    // conv step, one channel per thread, same order of operations as the conv kernel: bias, taps oldest to newest,
+    // then the new input
+    const float nan = __int_as_float(0x7fc00000);
+    for (int c = threadIdx.x; c < kChannels; c += kBlock) {
+        const int64_t dc = d_lo + c;
+        if (dc >= D) break;
+        float wk[4], carried[3];
 #pragma unroll
-        for (int k = 0; k < 3; ++k) carried[i][k] = k < H ? ld_io(win, k) : 0.0f;
-    }
+        for (int k = 0; k < 4; ++k) wk[k] = k <= H ? conv_w[dc * conv_k + k] : 0.0f;
+        const T *win = conv_src + ((p_ok ? p : 0) * D + dc) * H;
 #pragma unroll
-    for (int i = 0; i < U; ++i) {
-        // conv step, same order of operations as the conv kernel: bias, taps oldest to newest, then the new input
-        float acc = cb[i];
+        for (int k = 0; k < 3; ++k) carried[k] = k < H ? ld_io(win, k) : 0.0f;
+        const float xpre = ld_io(x, j * D + dc);
+        float acc = conv_bias ? conv_bias[dc] : 0.0f;
 #pragma unroll
         for (int k = 0; k < 3; ++k)
-            if (k < H) acc = fmaf(wk[i][k], carried[i][k], acc);
-        float wlast = wk[i][0];
+            if (k < H) acc = fmaf(wk[k], carried[k], acc);
+        float wlast = wk[0];
 #pragma unroll
         for (int k = 1; k < 4; ++k)
-            if (k == H) wlast = wk[i][k];
-        acc = fmaf(wlast, xpre[i], acc);
+            if (k == H) wlast = wk[k];
+        acc = fmaf(wlast, xpre, acc);
         const float xc = conv_silu ? silu_f32(acc) : acc;
         // the stored tensor the step would read
-        const float xv = sizeof(T) == 2 ? bf16_to_f32(f32_to_bf16(xc)) : xc;
+        xs[c] = sizeof(T) == 2 ? bf16_to_f32(f32_to_bf16(xc)) : xc;
+        // new window: the carried inputs move up, the new input comes last (NaN in front where the parent was bad)
+        T *nwin = conv_dst + (j * D + dc) * H;
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            if (k + 1 < H) st_io(nwin, k, p_ok ? carried[k + 1] : nan);
+        st_io(nwin, H - 1, xpre);
+        if (xc_out) st_io(xc_out, j * D + dc, p_ok ? xc : nan);
+    }
+    __syncthreads();
 
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const float xv = xs[d[i] - d_lo];
         const float v = dv[i] + bias[i];
         const float delta = SOFTPLUS ? softplus_f32(v) : v;
         const float u = delta * xv;
@@ -241,7 +260,6 @@ state_step_conv_kernel(float *h_out, const float *h_in, const int32_t *__restric
         y = fmaf(hh.z, cv[i].z, y);
         y = fmaf(hh.w, cv[i].w, y);
         y = channel_sum<Q>(y);
-        const float nan = __int_as_float(0x7fc00000);
         if (!p_ok) {
             hh = make_float4(nan, nan, nan, nan);
             y = nan;
@@ -252,14 +270,6 @@ state_step_conv_kernel(float *h_out, const float *h_in, const int32_t *__restric
                 y = fmaf(dsk[i], xv, y);
                 if constexpr (HAS_Z) y *= silu_f32(zv[i]);
                 st_io(out, j * D + d[i], y);
-                // new window: the carried inputs move up, the new input comes last (NaN where the parent was bad,
-                // as the conv kernel leaves it)
-                T *nwin = conv_dst + (j * D + d[i]) * H;
-#pragma unroll
-                for (int k = 0; k < 2; ++k)
-                    if (k + 1 < H) st_io(nwin, k, p_ok ? carried[i][k + 1] : nan);
-                st_io(nwin, H - 1, xpre[i]);
-                if (xc_out) st_io(xc_out, j * D + d[i], p_ok ? xc : nan);
             }
         }
     }
