@@ -8,7 +8,8 @@
  * every child starts from a copy of its parent's state (Sec. 4.1).  The four
  * operations below are the per-layer core of that path: causal depthwise
  * conv1d and selective scan for the prefill, a one-step state update for all
- * branches of the tree at once, and the state copy by parent index.
+ * branches of the tree at once, and the state copy by parent index; a fifth
+ * entry point does copy, conv step and state update of a layer in one launch.
  *
  * Conventions common to all entry points
  *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
