@@ -50,6 +50,12 @@ __device__ __forceinline__ void lds_barrier_linear()
 #ifndef MAMBA_LINEAR_WIDE
 #define MAMBA_LINEAR_WIDE 96
 #endif
+#ifndef MAMBA_LINEAR_WIDE_SMALL
+#define MAMBA_LINEAR_WIDE_SMALL 192
+#endif
+#ifndef MAMBA_LINEAR_WIDE_SMALL_MAX
+#define MAMBA_LINEAR_WIDE_SMALL_MAX 512
+#endif
 #ifndef MAMBA_LINEAR_DEEP
 #define MAMBA_LINEAR_DEEP 513
 #endif
@@ -247,6 +253,8 @@ linear_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, const 
 // matrix cores half the time at best.  This kernel takes 256 x 256 (or 256 x 128) tiles, one workgroup
 // per CU and one wavefront per SIMD, each wavefront a 128 x 128 (128 x 64) part held in 256 (128)
 // accumulator registers: per k the same 8 (6) cycles of cache traffic now feed 32 (16) cycles of MFMA.
+// (With BM = 128 it also runs 128 x 128 tiles, two workgroups to a CU, for products too small to give every CU
+// a 256-row tile: the feeding scheme below, not the tile size, is what those gain from.)
 //
 // Operands go from memory straight into LDS (global_load_lds_dwordx4: lane l of a wavefront lands at
 // M0 + 16 l, so one instruction fills eight 128-byte rows): no staging registers, and none of the LDS
@@ -272,16 +280,16 @@ __device__ __forceinline__ void load_to_lds16(const char *base, uint32_t lane_of
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
 
-template <int BN>
+template <int BM, int BN>
 __global__ void __launch_bounds__(256)
 linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ bias, const bf16_t *residual,
                    OutSplit out, int64_t M, int64_t N, int64_t K, int tiles_n, int n_tiles)
 {
-    constexpr int NT = BN / 64;                                   // 32 x 32 MFMA tiles per wavefront along n
-    constexpr int kRows = kWideBM + BN;
+    constexpr int MT = BM / 64, NT = BN / 64;                     // 32 x 32 MFMA tiles per wavefront along m and n
+    constexpr int kRows = BM + BN;
     constexpr int kStage = kRows * kWideRow;
     constexpr int kOutRow = BN * 2 + 16;
-    constexpr int kLds = 2 * kStage > kWideBM * kOutRow ? 2 * kStage : kWideBM * kOutRow;
+    constexpr int kLds = 2 * kStage > BM * kOutRow ? 2 * kStage : BM * kOutRow;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[kLds];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -290,12 +298,12 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
     const int per_xcd = (n_tiles + 7) / 8;
     const int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
     if (tile >= n_tiles) return;
-    const int64_t m0 = (int64_t)(tile / tiles_n) * kWideBM, n0 = (int64_t)(tile % tiles_n) * BN;
+    const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
 
     // Loads: wavefront v takes the row groups g = 4 j + v (rows 8 g .. 8 g + 7 of the stage; x rows first, then w);
     // lane l lands in row 8 g + l / 8, slot l % 8, and therefore fetches slot (l % 8) ^ ((4 (g & 1) + l / 16) & 7)
     // of that row (g & 1 == v & 1).
-    constexpr int NLX = kWideBM / 32, NLW = BN / 32;              // loads per wavefront and slab
+    constexpr int NLX = BM / 32, NLW = BN / 32;              // loads per wavefront and slab
     const uint32_t lane_off = (uint32_t)((lane >> 3) * K * 2 + (((lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7)) << 4));
     const char *xrow = reinterpret_cast<const char *>(x + (m0 + 8 * wave) * K);
     const char *wrow = reinterpret_cast<const char *>(w + (n0 + 8 * wave) * K);
@@ -306,7 +314,7 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
 #pragma unroll
         for (int i = decltype(first)::value; i < decltype(last)::value; ++i) {
             const char *base = i < NLX ? xrow + (i * rows32 + 2 * k0) : wrow + ((i - NLX) * rows32 + 2 * k0);
-            load_to_lds16(base, lane_off, lds0 + stage + (i < NLX ? 0 : kWideBM * kWideRow) + wave * 1024 + (i < NLX ? i : i - NLX) * 4096);
+            load_to_lds16(base, lane_off, lds0 + stage + (i < NLX ? 0 : BM * kWideRow) + wave * 1024 + (i < NLX ? i : i - NLX) * 4096);
         }
     };
     typedef std::integral_constant<int, 0> L0;
@@ -315,9 +323,9 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
     typedef std::integral_constant<int, 3 * (NLX + NLW) / 4> L3;
     typedef std::integral_constant<int, NLX + NLW> L4;
 
-    f32x16 acc[4][NT];
+    f32x16 acc[MT][NT];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < MT; ++a)
 #pragma unroll
         for (int b = 0; b < NT; ++b)
 #pragma unroll
@@ -328,10 +336,10 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         const int slot = ((2 * ks + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4;
-        frag_x[ks] = (wm * 128 + (lane & 31)) * kWideRow + slot;
-        frag_w[ks] = (kWideBM + wn * (BN / 2) + (lane & 31)) * kWideRow + slot;
+        frag_x[ks] = (wm * (BM / 2) + (lane & 31)) * kWideRow + slot;
+        frag_w[ks] = (BM + wn * (BN / 2) + (lane & 31)) * kWideRow + slot;
     }
-    struct Frags { bf16x8 xf[4], wf[NT]; };
+    struct Frags { bf16x8 xf[MT], wf[NT]; };
     auto load_x = [&](const unsigned char *stage, int ks, Frags &f, int t) __attribute__((always_inline)) {
         f.xf[t] = *reinterpret_cast<const bf16x8 *>(stage + frag_x[ks] + t * 32 * kWideRow);
     };
@@ -340,7 +348,7 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
     };
     auto load_frags = [&](const unsigned char *stage, int ks, Frags &f) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) load_x(stage, ks, f, t);
+        for (int t = 0; t < MT; ++t) load_x(stage, ks, f, t);
 #pragma unroll
         for (int t = 0; t < NT; ++t) load_w(stage, ks, f, t);
     };
@@ -351,9 +359,9 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
     };
     auto multiply = [&](const Frags &f) __attribute__((always_inline)) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a) multiply_row(f, a);
+        for (int a = 0; a < MT; ++a) multiply_row(f, a);
     };
-    // Slab s, read from stage s % 2, whose first fragments are already in f0.  Four quarters of 4 NT MFMAs; the
+    // Slab s, read from stage s % 2, whose first fragments are already in f0.  Four quarters of MT NT MFMAs; the
     // fragments of a quarter are read during the one before it (the instruction groups keep the scheduler from
     // moving the reads next to their use).  After the third quarter every read of this stage has been issued: the
     // slab s + 1 must have landed by then (requested a slab ago), the barrier publishes it, the stage of slab s is
@@ -370,9 +378,10 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
 #define MAMBA_WIDE_QUARTER(KS, FA, FB)                                                                                \
         load_frags(cur, KS, FB);                                                                                      \
         multiply(FA);                                                                                                 \
-        MAMBA_WIDE_SPREAD MAMBA_WIDE_SPREAD MAMBA_WIDE_SPREAD MAMBA_WIDE_SPREAD                                       \
+        MAMBA_WIDE_SPREAD MAMBA_WIDE_SPREAD                                                                           \
+        if constexpr (MT == 4) { MAMBA_WIDE_SPREAD MAMBA_WIDE_SPREAD }                                                \
         __builtin_amdgcn_sched_group_barrier(0x100, NT, 0);                                                           \
-        __builtin_amdgcn_sched_group_barrier(0x008, NT * 2, 0);                                                       \
+        __builtin_amdgcn_sched_group_barrier(0x008, MT * NT / 2, 0);                                                  \
         __builtin_amdgcn_sched_barrier(0);
         MAMBA_WIDE_QUARTER(1, f0, f1)
         MAMBA_WIDE_QUARTER(2, f1, f0)
@@ -384,10 +393,10 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
 #define MAMBA_WIDE_LAST(A, FROM, TO)                                                                                  \
         if constexpr (REQUEST) request(k_next, P * kStage, FROM(), TO());                                             \
         if constexpr (NEXT) {                                                                                         \
-            load_x(nxt, 0, f0, A);                                                                                    \
-            if (A < NT) load_w(nxt, 0, f0, A);                                                                        \
+            if constexpr (A < MT) load_x(nxt, 0, f0, A);                                                              \
+            if constexpr (A < NT) load_w(nxt, 0, f0, A);                                                              \
         }                                                                                                             \
-        multiply_row(f1, A);                                                                                          \
+        if constexpr (A < MT) multiply_row(f1, A);                                                                    \
         __builtin_amdgcn_sched_barrier(0);
         MAMBA_WIDE_LAST(0, L0, L1)
         MAMBA_WIDE_LAST(1, L1, L2)
@@ -414,7 +423,7 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
     // Epilogue.  The residual chunks this thread will add are requested first, all at once: with one workgroup per
     // CU nothing else would hide their latency, and fetched four at a time inside the store loop they cost a third
     // of the tile's time.
-    constexpr int kCpr = BN / 8, kChunks = kWideBM * kCpr / 256;
+    constexpr int kCpr = BN / 8, kChunks = BM * kCpr / 256;
     u32x4 res[kChunks];
     if (residual) {
 #pragma unroll
@@ -436,8 +445,8 @@ linear_wide_kernel(const bf16_t *x, const bf16_t *w, const float *__restrict__ b
             float4 bv = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             if (bias) bv = *reinterpret_cast<const float4 *>(bias + n0 + nl);
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int ml = wm * 128 + a * 32 + (lane & 31);
+            for (int a = 0; a < MT; ++a) {
+                const int ml = wm * (BM / 2) + a * 32 + (lane & 31);
                 uint2 v;
                 v.x = f32x2_to_bf16x2(acc[a][b][4 * g + 0] + bv.x, acc[a][b][4 * g + 1] + bv.y);
                 v.y = f32x2_to_bf16x2(acc[a][b][4 * g + 2] + bv.z, acc[a][b][4 * g + 3] + bv.w);
@@ -784,17 +793,27 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
     }
     auto tiles = [&](int64_t bm, int64_t bn) { return ((N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
 #ifndef MAMBA_LINEAR_NO_WIDE
-    if (vec && a.M % kWideBM == 0 && a.K % (2 * kWideBK) == 0 && a.K >= 2 * kWideBK) {
-        // 256-row tiles from about a hundred of them on (measured against the 128 x 128 kernel: in_proj on 2048 tokens
-        // 21.6 -> 17.9 us, out_proj on 8192 tokens 38 -> 26 us; below that the smaller tiles fill more CUs); the
-        // 128-column variant when the 256-column one would leave a ragged last round
-        const int64_t t256 = N % 256 == 0 ? (a.M / kWideBM) * (N / 256) : 0, t128 = N % 128 == 0 ? (a.M / kWideBM) * (N / 128) : 0;
+    if (vec && a.M % 128 == 0 && a.K % (2 * kWideBK) == 0 && a.K >= 2 * kWideBK) {
+        // The memory-to-LDS kernel with 128 x 128 tiles (two workgroups to a CU) from 192 tiles on, while 256 x 128
+        // ones would come to fewer than two per CU: in_proj on 2048 tokens 17.6 -> 16.3 us, on 4096 tokens 32 -> 29 us,
+        // out_proj on 4096 tokens 22 -> 16 us.  (With fewer tiles it wins only on operands that are already in cache
+        // -- out_proj on 2048 tokens, 96 tiles: 17.2 -> 12.7 us alone in a loop, but 17.6 -> 19.5 us inside the block,
+        // where two 32 KiB stages per CU are too little in flight for operands that come from memory.)  Beyond that
+        // 256-row tiles (in_proj on 32768 tokens 222 -> 172 us), 256 columns wide unless that leaves a ragged last round.
+        const bool m256 = a.M % kWideBM == 0;
+        const int64_t t256 = m256 && N % 256 == 0 ? (a.M / kWideBM) * (N / 256) : 0;
+        const int64_t t128 = m256 && N % 128 == 0 ? (a.M / kWideBM) * (N / 128) : 0;
+        const int64_t t128s = N % 128 == 0 ? (a.M / 128) * (N / 128) : 0;
+        if (t128s >= MAMBA_LINEAR_WIDE_SMALL && t128 < MAMBA_LINEAR_WIDE_SMALL_MAX) {
+            linear_wide_kernel<128, 128><<<(unsigned)(8 * ((t128s + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 128), (int)t128s);
+            return hipGetLastError();
+        }
         if (t256 >= MAMBA_LINEAR_WIDE && (t256 % 256 == 0 || t256 >= 4 * 256 || t128 == 0)) {
-            linear_wide_kernel<256><<<(unsigned)(8 * ((t256 + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 256), (int)t256);
+            linear_wide_kernel<256, 256><<<(unsigned)(8 * ((t256 + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 256), (int)t256);
             return hipGetLastError();
         }
         if (t128 >= MAMBA_LINEAR_WIDE) {
-            linear_wide_kernel<128><<<(unsigned)(8 * ((t128 + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 128), (int)t128);
+            linear_wide_kernel<256, 128><<<(unsigned)(8 * ((t128 + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 128), (int)t128);
             return hipGetLastError();
         }
     }

@@ -824,7 +824,9 @@ def test_scan_invariants_at_size(m):
                                           # 256-row tiles, 256 and 128 columns wide (M % 256 == 0, K % 128 == 0, >= 512 tiles):
                                           # 4, 6, 8 and 10 slabs, splits on and off the tile edges
                                           (16384, 2048, 256, (1024, 1024)), (16384, 1152, 384, None), (8192, 4096, 512, None),
-                                          (16384, 1152, 640, (1000, 152)), (1024, 3072, 768, (1536, 1536)), (512, 6144, 128, None)])
+                                          (16384, 1152, 640, (1000, 152)), (1024, 3072, 768, (1536, 1536)), (512, 6144, 128, None),
+                                          # 128 x 128 tiles of the same kernel (M % 128 == 0, 192 .. a few hundred tiles)
+                                          (4096, 768, 1536, None), (2688, 1152, 256, (1000, 152)), (384, 8192, 384, None)])
 def test_linear_against_oracle(m, M, N, K, splits):
     say(M=M, N=N, K=K, splits=splits)
     rng = np.random.default_rng(M + N + K)
@@ -862,10 +864,10 @@ def test_linear_at_block_bench_size_sampled_rows(m):
 
 def test_linear_wide_tiles_are_deterministic(m):
     """The 256-row tiles stream their operands into LDS asynchronously and order them with explicit waits; a
-    missing wait would show as run-to-run differences.  Ten launches each, both tile widths, on fresh outputs."""
+    missing wait would show as run-to-run differences.  Ten launches each, all three tile shapes, on fresh outputs."""
     g = torch.Generator(device=DEV)
     g.manual_seed(77)
-    for (M, N, K) in ((8192, 4096, 768), (16384, 1152, 1536)):
+    for (M, N, K) in ((8192, 4096, 768), (16384, 1152, 1536), (4096, 768, 1536)):
         x = torch.randn(M, K, device=DEV, generator=g).bfloat16()
         w = (torch.randn(N, K, device=DEV, generator=g) / K ** 0.5).bfloat16()
         (first,) = m.mamba_linear_fwd(x, w)
