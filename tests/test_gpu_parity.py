@@ -580,7 +580,8 @@ def test_cfg4_wide_prefill_and_decode_sampled(m):
 
 
 # ------------------------------------------------------------------------------------ HIP graph
-def test_decode_loop_replays_in_a_hip_graph(m):
+@pytest.mark.parametrize("one_launch", [False, True])
+def test_decode_loop_replays_in_a_hip_graph(m, one_launch):
     """Every call has a fixed shape and neither allocates nor synchronizes, so a draft round can
     be captured once and replayed (Sec. 4.1: graph cache per batch size).  Each replay, with other
     work and synchronizations in between, must equal the eager result bit for bit."""
@@ -599,9 +600,15 @@ def test_decode_loop_replays_in_a_hip_graph(m):
         src_s, src_c = ssm0, conv0
         for s in range(dc["steps"]):
             dst_s, dst_c = ssm[s & 1], conv[s & 1]
-            m.mamba_state_fork(src_c, None, PAR[s], conv_dst=dst_c)
+            if not one_launch:
+                m.mamba_state_fork(src_c, None, PAR[s], conv_dst=dst_c)
             for l in range(nl):
                 t = TOK[s][l]
+                if one_launch:
+                    m.mamba_conv_state_step(src_s[l], src_c[l], t["x"], P[l]["conv_w"], P[l]["conv_bias"], t["dt"],
+                                            P[l]["A"], t["Bm"], t["Cm"], P[l]["Dskip"], t["z"], P[l]["dt_bias"],
+                                            parent_idx=PAR[s], h_out=dst_s[l], conv_state_out=dst_c[l], out=outs[s, l])
+                    continue
                 m.mamba_conv1d_fwd(t["x"].unsqueeze(1), P[l]["conv_w"], P[l]["conv_bias"],
                                    conv_state_in=dst_c[l], y=xc, conv_state_out=dst_c[l])
                 m.mamba_state_step(src_s[l], xc.squeeze(1), t["dt"], P[l]["A"], t["Bm"], t["Cm"],
