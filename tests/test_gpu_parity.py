@@ -141,6 +141,17 @@ def test_scan_state_sizes_and_random_A(m, io, N):
     check_scan(m, c2, chunk_len=50, what="odd D chunked")
 
 
+@pytest.mark.parametrize("N", [4, 8, 16, 32])
+@pytest.mark.parametrize("L,chunk_len", [(640, 16), (1000, 5), (1200, 3)])
+def test_scan_carry_variants(m, N, L, chunk_len):
+    """The three carry kernels between the passes: 40 slots (four states per lane), 200 slots (two states per lane),
+    400 slots (the looped variant), for every state size and an odd channel count."""
+    say(N=N, L=L, chunk_len=chunk_len)
+    c = synth.prefill_case(2, L, 66, N, 4, synth.F32, seed=3000 + N + L, random_A=True)
+    h0 = np.random.default_rng(N + L).standard_normal((2, 66, N)).astype(np.float32)
+    check_scan(m, c, h0=h0, chunk_len=chunk_len, what="carry over %d slots" % ((L + chunk_len - 1) // chunk_len))
+
+
 @pytest.mark.parametrize("io", [synth.F32, synth.BF16])
 def test_scan_optional_arguments(m, io):
     c = synth.prefill_case(2, 200, 128, 16, 4, io, seed=42)
