@@ -18,6 +18,8 @@ def to_dev(a, io=None):
     if a is None:
         return None
     a = np.ascontiguousarray(a)
+    if not a.flags.writeable:                                     # a read-only view (a broadcast, a stored fixture): torch wants its own
+        a = a.copy()
     if a.dtype == np.uint16:
         return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
     return torch.from_numpy(a).to(DEV)
