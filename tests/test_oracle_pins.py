@@ -461,6 +461,73 @@ def test_topk_and_embedding_reduce_to_library_routines():
     assert np.array_equal(oracle.embedding(tok, table), np.stack([table[3], table[3], table[0], table[8]]))
 
 
+def _block_weights64(rng, dm, D, N, K, R):
+    return dict(norm_w=rng.uniform(0.5, 1.5, dm), in_proj_w=rng.standard_normal((2 * D, dm)) / np.sqrt(dm),
+                conv_w=rng.standard_normal((D, K)), conv_b=rng.standard_normal(D),
+                x_proj_w=rng.standard_normal((R + 2 * N, D)) / np.sqrt(D), dt_proj_w=rng.standard_normal((D, R)),
+                dt_bias=rng.standard_normal(D) - 1.0, A=-rng.uniform(0.2, 4.0, (D, N)), Dskip=rng.standard_normal(D),
+                out_proj_w=rng.standard_normal((dm, D)) / np.sqrt(D))
+
+
+def test_block_single_token_from_zero_state_is_an_explicit_expression():
+    """Wiring of the block (Sec. 3.1, the Mamba block of the drafter): for one token and zero carried
+    states nothing recurs, so every output is a plain expression of the weights.  The conv sees only its
+    newest tap; the state is delta * x_c * B; the order x | z of in_proj's halves and dt | B | C of
+    x_proj's rows, the low-rank dt projection and the gate all show in the result.  Evaluated in
+    float64 throughout (no rounding between stages)."""
+    rng = rnd(31)
+    dm, D, N, K, R = 5, 6, 4, 4, 2
+    w = _block_weights64(rng, dm, D, N, K, R)
+    hid = rng.standard_normal((3, 1, dm))
+    out, conv_state, h = oracle.block_fwd(w, hid, round_between=False)
+    v = hid[:, 0]
+    u = v / np.sqrt(np.mean(v * v, axis=1, keepdims=True) + 1e-5) * w["norm_w"]
+    x, z = u @ w["in_proj_w"][:D].T, u @ w["in_proj_w"][D:].T
+    pre = x * w["conv_w"][:, K - 1] + w["conv_b"]
+    xc = pre * expit(pre)
+    low, Bv, Cv = xc @ w["x_proj_w"][:R].T, xc @ w["x_proj_w"][R:R + N].T, xc @ w["x_proj_w"][R + N:].T
+    delta = np.logaddexp(0.0, low @ w["dt_proj_w"].T + w["dt_bias"])
+    h_want = (delta * xc)[:, :, None] * Bv[:, None, :]
+    y = (np.einsum("bdn,bn->bd", h_want, Cv) + w["Dskip"] * xc) * (z * expit(z))
+    np.testing.assert_allclose(h, h_want, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(out[:, 0], v + y @ w["out_proj_w"].T, rtol=1e-12, atol=1e-13)
+    # the carried conv inputs: the x half before the conv, newest last, zeros in front of the sequence
+    assert conv_state.shape == (3, D, K - 1)
+    np.testing.assert_allclose(conv_state[:, :, K - 2], x, rtol=1e-12, atol=1e-13)
+    assert not conv_state[:, :, :K - 2].any()
+
+
+def test_block_degenerate_weights_and_causality():
+    """(a) out_proj = 0 leaves the residual stream unchanged; (b) so does a zero z half of in_proj (the gate
+    silu(0) is 0), while a zero x half with zero conv bias does too but a zero x half with a conv bias does
+    not (the two halves are not interchangeable); (c) a token changes no output before it, and the states a
+    split run carries make the second half equal the one-pass result; (d) rounding between the stages moves
+    the result a little (six roundings of 2^-9 each, amplified by the weights) and not by nothing."""
+    rng = rnd(32)
+    dm, D, N, K, R = 8, 12, 4, 3, 2
+    w = _block_weights64(rng, dm, D, N, K, R)
+    hid = rng.standard_normal((2, 9, dm))
+    full, cs, hs = oracle.block_fwd(w, hid, round_between=False)
+    assert np.max(np.abs(full - hid)) > 1e-2
+    assert np.array_equal(oracle.block_fwd(dict(w, out_proj_w=0 * w["out_proj_w"]), hid, round_between=False)[0], hid)
+    wz = dict(w, in_proj_w=np.concatenate([w["in_proj_w"][:D], np.zeros((D, dm))]))
+    assert np.array_equal(oracle.block_fwd(wz, hid, round_between=False)[0], hid)
+    wx = dict(w, in_proj_w=np.concatenate([np.zeros((D, dm)), w["in_proj_w"][D:]]))
+    assert np.max(np.abs(oracle.block_fwd(wx, hid, round_between=False)[0] - hid)) > 1e-3
+    assert np.array_equal(oracle.block_fwd(dict(wx, conv_b=np.zeros(D)), hid, round_between=False)[0], hid)
+    hid2 = hid.copy()
+    hid2[:, 5] += 1.0
+    other = oracle.block_fwd(w, hid2, round_between=False)[0]
+    assert np.array_equal(other[:, :5], full[:, :5]) and np.min(np.max(np.abs(other[:, 5:] - full[:, 5:]), axis=2)) > 0
+    o1, c1, s1 = oracle.block_fwd(w, hid[:, :4], round_between=False)
+    o2, c2, s2 = oracle.block_fwd(w, hid[:, 4:], conv_state_in=c1, h0=s1, round_between=False)
+    np.testing.assert_allclose(np.concatenate([o1, o2], axis=1), full, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(c2, cs, rtol=0, atol=0)
+    np.testing.assert_allclose(s2, hs, rtol=1e-12, atol=1e-13)
+    rounded = oracle.block_fwd(w, hid, round_between=True)[0]
+    assert 0 < np.max(np.abs(rounded - full)) <= 0.1 * np.sqrt(np.mean(full ** 2))
+
+
 def test_drafter_tree_reduces_to_greedy_decoding_and_to_prefill():
     """The drafter oracle against what it must reduce to: (a) along a (1, 1, 1) tree it is greedy
     decoding, so encoding prefix + drafted tokens in one pass gives the same next-token logits
