@@ -9,7 +9,7 @@ import torch
 
 import oracle
 from paper_2506_01206_amd import synth
-from gpu_util import DEV, TOL, W, assert_close, dev_case, oracle_scan, to_dev, to_host, values
+from gpu_util import DEV, TOL, W, assert_close, assert_close_but_for_flips, dev_case, oracle_scan, to_dev, to_host, values
 
 pytestmark = pytest.mark.gpu
 
@@ -917,7 +917,10 @@ def make_block(m, rng, dm, D, N, K, R):
 @pytest.mark.parametrize("B,L,dm,D,N,K,R", [(2, 96, 64, 128, 16, 4, 8), (1, 700, 768, 1536, 16, 4, 48),
                                            (3, 33, 256, 512, 8, 3, 16),
                                            # long enough for the 256-row projection tiles (in_proj and out_proj)
-                                           (1, 4096, 768, 1536, 16, 4, 48)])
+                                           (1, 4096, 768, 1536, 16, 4, 48),
+                                           # 32 states, the fastest of them decaying by exp(-16 delta) a step: the
+                                           # final state is steep in dt, see the state check below
+                                           (2, 100, 216, 1144, 32, 3, 24)])
 def test_block_prefill_against_oracle(m, B, L, dm, D, N, K, R):
     """RMSNorm -> in_proj -> conv1d -> x_proj -> dt_proj -> selective scan -> out_proj + residual as one
     call; the oracle rounds the tensors between stages to bf16 as the workspace does.  Also checked
@@ -930,7 +933,11 @@ def test_block_prefill_against_oracle(m, B, L, dm, D, N, K, R):
     ro, rc, rh = oracle.block_fwd(w64, W(hid))
     tol = TOL[synth.BF16]
     assert_close(values(to_host(out)), ro, tol, "block out")
-    assert_close(to_host(hf), rh, tol, "block ssm state")
+    # one dt rounded to the neighbouring bf16 value moves a fast state by |A| delta 2^-8 of itself per step: with 32
+    # states the oracle with and without the roundings between stages differs by 4e-2, so there a handful of elements
+    # may pass the tolerance (never three times it)
+    state_close = assert_close if N < 32 else assert_close_but_for_flips
+    state_close(to_host(hf), rh, tol, "block ssm state")
     # the conv state holds bf16 values of x; a rounding flip upstream moves one by at most an ulp
     assert_close(values(to_host(cst)), rc, tol, "block conv state")
     # the unrounded float64 block stays close as well (looser: six bf16 roundings on the way)
@@ -942,7 +949,7 @@ def test_block_prefill_against_oracle(m, B, L, dm, D, N, K, R):
     o1, c1, s1 = m.mamba_block_fwd(blk, h[:, :cut].contiguous())
     o2, c2, s2 = m.mamba_block_fwd(blk, h[:, cut:].contiguous(), conv_state_in=c1, h0=s1)
     assert_close(values(to_host(torch.cat([o1, o2], 1))), ro, tol, "block pieces out")
-    assert_close(to_host(s2), rh, tol, "block pieces state")
+    state_close(to_host(s2), rh, tol, "block pieces state")
     # in place on the residual stream
     h2 = h.clone()
     m.mamba_block_fwd(blk, h2, hidden_out=h2)
