@@ -49,6 +49,16 @@ def test_library_exports_every_declared_symbol(b):
         assert getattr(raw, name) is not None and callable(getattr(tree_search, name))
 
 
+def test_binding_without_the_library_refuses_to_import(tmp_path):
+    """No fallback: a copy of the binding that finds no built library beside it raises on import."""
+    import importlib.util
+    import shutil
+    shutil.copy(os.path.join(ROOT, "paper_2506_01206_amd", "binding.py"), tmp_path / "binding.py")
+    spec = importlib.util.spec_from_file_location("binding_without_library", tmp_path / "binding.py")
+    with pytest.raises(ImportError, match="libmamba_hip.so is missing"):
+        spec.loader.exec_module(importlib.util.module_from_spec(spec))
+
+
 def test_status_strings(b):
     seen = set()
     for code in (0, -1, -2, -3, -4, -5, -6):
