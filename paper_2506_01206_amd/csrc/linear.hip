@@ -549,40 +549,85 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
 
     // What an output element needs besides the sums: bias, residual, and for the conv tail the carried
     // window (through the parent index), the taps and the conv bias.  With one row block these loads
-    // are issued here, ahead of the main loop, so that the epilogue does not wait for them.
+    // are issued ahead of and inside the main loop, so that the epilogue does not wait for them: first what needs no
+    // parent index, and the index itself; then, once the first group of the main loop's loads is on its way, the
+    // window behind the index.  No fetch is used where it is issued (a value converted, selected or compared there
+    // is waited for there, one memory latency each): raw bits are kept, taps and window entries a short conv does not
+    // have re-read the last one and are dropped at use, and the width and pointer of an output tensor are picked
+    // from values held in registers (indexing the argument struct by a per-lane number goes through memory).
     struct Tail {
-        float bias, res, cb, wk[4];
-        uint16_t carried[3];
+        float bias, cb, wk[4];
+        uint16_t res, carried[3];
+        int32_t parent;
+    };
+    int64_t ow0 = out.width[0], ow1 = out.width[1], ow2 = out.width[2];
+    bf16_t *op0 = out.ptr[0], *op1 = out.ptr[1], *op2 = out.ptr[2];
+    asm volatile("" : "+s"(ow0), "+s"(ow1), "+s"(ow2), "+s"(op0), "+s"(op1), "+s"(op2));
+    auto locate_tail = [&](int64_t n, int64_t *col, int64_t *width, bf16_t **ptr) {
+        int64_t c = n, wd = ow0;
+        bf16_t *pt = op0;
+        int sp = 0;
+        if (c >= ow0) {
+            c -= ow0; sp = 1; wd = ow1; pt = op1;
+            if (c >= ow1) { c -= ow1; sp = 2; wd = ow2; pt = op2; }
+        }
+        *col = c; *width = wd; *ptr = pt;
+        return sp;
     };
     constexpr int OPT = 16 * 64 / (NW * 64);                      // outputs per thread and row block
-    auto load_tail = [&](int b, int j) {
-        Tail t;
-        t.bias = t.res = t.cb = 0.0f;
+    auto tail_first = [&](int b, int j, Tail &t) {
+        t.bias = t.cb = 0.0f;
+        t.res = 0;
+        t.parent = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) t.wk[k] = 0.0f;
 #pragma unroll
-        for (int k = 0; k < 3; ++k) t.carried[k] = 0x7fc0;        // NaN unless a valid parent supplies it
+        for (int k = 0; k < 3; ++k) t.carried[k] = 0;
         const int o = tid + j * NW * 64, i = o >> 6, l = o & 63;
         const int64_t m = m0 + b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
-        if (m >= M || n >= N) return t;
+        if (m >= M || n >= N) return;
         if (bias) t.bias = bias[n];
-        int64_t col;
-        const int sp = locate(out, n, &col);
-        if (residual) t.res = bf16_to_f32(residual[m * out.width[sp] + col]);
-        if (conv.w && sp == 0) {
-            const int H = conv.k - 1;
-            const int64_t p = conv.parent ? (int64_t)conv.parent[m] : m;
-            const bool p_ok = !conv.parent || (p >= 0 && p < conv.n_in);
-            const bf16_t *win = conv.src + ((p_ok ? p : 0) * out.width[0] + col) * H;
-            if (conv.bias) t.cb = conv.bias[col];
+        int64_t col, width;
+        bf16_t *ptr;
+        const int sp = locate_tail(n, &col, &width, &ptr);
+        if (residual) t.res = residual[m * width + col];
+        if (conv.w && sp == 0 && conv.parent) t.parent = conv.parent[m];
+    };
+    // (all parent indices are turned into addresses before the first window fetch: the wait for an index also
+    // waits for every fetch issued before it)
+    struct WinAddr {
+        int64_t win, col;                                         // window's first element in conv.src; channel
+        bool on;
+    };
+    auto tail_address = [&](int b, int j, const Tail &t) {
+        WinAddr a;
+        const int o = tid + j * NW * 64, i = o >> 6, l = o & 63;
+        const int64_t m = m0 + b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
+        a.on = !(m >= M || n >= N || !conv.w || n >= ow0);
+        a.col = a.on ? n : 0;
+        const int64_t p = conv.parent ? (int64_t)t.parent : m;
+        const bool p_ok = !conv.parent || (p >= 0 && p < conv.n_in);
+        a.win = (((a.on && p_ok) ? p : 0) * ow0 + a.col) * (conv.k - 1);
+        return a;
+    };
+    auto tail_window = [&](const WinAddr &a, Tail &t) {
+        if (!a.on) return;
+        const int H = conv.k - 1;
+        if (conv.bias) t.cb = conv.bias[a.col];
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (k <= H) t.wk[k] = conv.w[col * conv.k + k];
+        for (int k = 0; k < 4; ++k) t.wk[k] = conv.w[a.col * conv.k + (k <= H ? k : H)];
 #pragma unroll
-            for (int k = 0; k < 3; ++k)
-                if (k < H && p_ok) t.carried[k] = win[k];
-        }
-        return t;
+        for (int k = 0; k < 3; ++k) t.carried[k] = conv.src[a.win + (k < H ? k : H - 1)];
+    };
+    auto tail_windows = [&](int b, Tail *ts) {
+        if (!conv.w) return;
+        WinAddr wa[OPT];
+#pragma unroll
+        for (int j = 0; j < OPT; ++j) wa[j] = tail_address(b, j, ts[j]);
+#pragma unroll
+        for (int j = 0; j < OPT; ++j) asm volatile("" : "+v"(wa[j].win));  // formed here, not where it is first used
+#pragma unroll
+        for (int j = 0; j < OPT; ++j) tail_window(wa[j], ts[j]);
     };
     // projection tail: thread (group g, output j) of NW * 64 / n groups takes rows g, g + groups, ... of the
     // block; its 32 weights are fetched here, ahead of the main loop
@@ -595,9 +640,10 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
         for (int c = 0; c < 4; ++c) xw4[c] = wr[c];
     }
     Tail early[OPT];
+    bool window_pending = MB == 1;
     if constexpr (MB == 1) {
 #pragma unroll
-        for (int j = 0; j < OPT; ++j) early[j] = load_tail(0, j);
+        for (int j = 0; j < OPT; ++j) tail_first(0, j, early[j]);
     }
 
     // A wavefront's k blocks are taken G at a time: all loads of a group are issued before its first
@@ -616,14 +662,29 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
                 for (int b = 0; b < MB; ++b) xf[g][b][i] = (ok && xlive[b][i]) ? xptr[b][i][c] : make_uint4(0, 0, 0, 0);
             }
         }
+        // the norm weights of all groups go out with the group's own loads (fetched group by group where they are
+        // used, each costs a trip of its own); chunks past the end re-read the last one and are not used
+        float4 nw[G][2];
+        if (norm_w) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const int64_t c = (blk0 + (int64_t)g * NW) * 8 + lch;
+                const int64_t cc = c < kchunks ? c : kchunks - 1;
+                nw[g][0] = reinterpret_cast<const float4 *>(norm_w)[2 * cc];
+                nw[g][1] = reinterpret_cast<const float4 *>(norm_w)[2 * cc + 1];
+            }
+        }
+        if (MB == 1 && window_pending) {
+            tail_windows(0, early);
+            window_pending = false;
+        }
         if (norm_w) {
             // RMSNorm on the way in: the element-wise weight now, the row factor after the sums
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const int64_t c = (blk0 + (int64_t)g * NW) * 8 + lch;
                 if (c >= kchunks) continue;
-                const float4 g0 = reinterpret_cast<const float4 *>(norm_w)[2 * c];
-                const float4 g1 = reinterpret_cast<const float4 *>(norm_w)[2 * c + 1];
+                const float4 g0 = nw[g][0], g1 = nw[g][1];
 #pragma unroll
                 for (int b = 0; b < MB; ++b)
 #pragma unroll
@@ -666,6 +727,7 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
             wave_sync();
         }
     }
+    if (MB == 1 && window_pending) tail_windows(0, early);        // a wavefront without a k block of its own
     __syncthreads();                                              // patches are done with: their memory is reused below
 
     // acc[b][i] is C[m = 32 b + 8 (i / 4) + 4 (lane / 32) + i % 4][n = n0 + lane % 32]
@@ -690,10 +752,16 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
             }
             __syncthreads();
         }
+        Tail late[OPT];
+        if constexpr (MB != 1) {
+#pragma unroll
+            for (int j = 0; j < OPT; ++j) tail_first(b, j, late[j]);
+            tail_windows(b, late);
+        }
 #pragma unroll
         for (int j = 0; j < OPT; ++j) {
             const int o = tid + j * NW * 64, i = o >> 6, l = o & 63;
-            const Tail t = MB == 1 ? early[j] : load_tail(b, j);
+            const Tail t = MB == 1 ? early[j] : late[j];
             float v = 0.0f;
 #pragma unroll
             for (int q = 0; q < NW; ++q) v += part[q][i][l];
@@ -701,19 +769,24 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
             const int64_t m = m0 + b * 32 + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3), n = n0 + (l & 31);
             if (m >= M || n >= N) continue;
             v = bf16_to_f32(f32_to_bf16(v + t.bias));             // same two roundings as the tiled kernel
-            int64_t col;
-            const int sp = locate(out, n, &col);
-            const int64_t off = m * out.width[sp] + col;
-            if (residual) v += t.res;
+            int64_t col, width;
+            bf16_t *optr;
+            const int sp = locate_tail(n, &col, &width, &optr);
+            const int64_t off = m * width + col;
+            if (residual) v += bf16_to_f32(t.res);
             if (conv.w && sp == 0) {
                 // the window of this (row, channel): K - 1 carried values, then v; same order of operations
-                // as the stand-alone conv kernel
+                // as the stand-alone conv kernel.  A bad parent index leaves NaN in the carried places.
                 const int H = conv.k - 1;
+                const bool p_ok = !conv.parent || (t.parent >= 0 && (int64_t)t.parent < conv.n_in);
+                uint16_t carried[3];
+#pragma unroll
+                for (int k = 0; k < 3; ++k) carried[k] = p_ok ? t.carried[k] : (uint16_t)0x7fc0;
                 bf16_t *nwin = conv.dst + off * H;
                 float a = t.cb;
 #pragma unroll
                 for (int k = 0; k < 3; ++k)
-                    if (k < H) a = fmaf(t.wk[k], bf16_to_f32(t.carried[k]), a);
+                    if (k < H) a = fmaf(t.wk[k], bf16_to_f32(carried[k]), a);
                 float wlast = t.wk[0];
 #pragma unroll
                 for (int k = 1; k < 4; ++k)
@@ -721,12 +794,12 @@ linear_skinny_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
                 a = fmaf(wlast, v, a);
 #pragma unroll
                 for (int k = 0; k < 2; ++k)
-                    if (k + 1 < H) nwin[k] = t.carried[k + 1];
+                    if (k + 1 < H) nwin[k] = carried[k + 1];
                 if (H > 0) nwin[H - 1] = (bf16_t)f32_to_bf16(v);
                 v = silu_f32(a);
             }
             const uint32_t stored = f32_to_bf16(v);
-            out.ptr[sp][off] = (bf16_t)stored;
+            optr[off] = (bf16_t)stored;
             if constexpr (kTailRoom) {
                 if (xp.w && sp == 0) xc[b][8 * (i >> 2) + 4 * (l >> 5) + (i & 3)][l & 31] = bf16_to_f32(stored);
             }
