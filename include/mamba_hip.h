@@ -228,6 +228,16 @@ typedef struct {
 } mamba_block_params_t;
 
 size_t mamba_block_workspace_bytes(const mamba_block_params_t *p, int64_t batch, int64_t L);
+/*
+ * Where mamba_block_fwd leaves the stage tensors of its last call in the workspace (byte offsets from
+ * its start; host arithmetic only), so that a caller can inspect every stage on its own inputs:
+ *   offsets[0] dt (rows, d_inner)      offsets[1] z (rows, d_inner)     offsets[2] x_c (rows, d_inner)
+ *   offsets[3] y (rows, d_inner): the gated scan output               offsets[4] dt_low (rows, dt_rank)
+ *   offsets[5] B (rows, d_state)       offsets[6] C (rows, d_state)     all bf16, rows = batch * L.
+ * (x, the conv's input, shares dt's place and is overwritten by it.)  Returns MAMBA_OK or the error
+ * mamba_block_fwd would give for these parameters.
+ */
+int mamba_block_workspace_layout(const mamba_block_params_t *p, int64_t batch, int64_t L, int64_t offsets[7]);
 int mamba_block_fwd(const mamba_block_params_t *p, const void *hidden, void *hidden_out,
                     const void *conv_state_in, void *conv_state_out, const float *h0,
                     float *h_final, void *workspace, size_t workspace_bytes, int64_t batch,

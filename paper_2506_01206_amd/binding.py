@@ -57,6 +57,8 @@ def _declare(lib):
     _bpp = ctypes.POINTER(BlockParams)
     lib.mamba_block_workspace_bytes.argtypes = [_bpp, _i64, _i64]
     lib.mamba_block_workspace_bytes.restype = _sz
+    lib.mamba_block_workspace_layout.argtypes = [_bpp, _i64, _i64, ctypes.POINTER(ctypes.c_int64)]
+    lib.mamba_block_workspace_layout.restype = _int
     lib.mamba_block_fwd.argtypes = [_bpp] + [_vp] * 7 + [_sz, _i64, _i64, _vp]
     lib.mamba_block_fwd.restype = _int
     lib.mamba_block_step.argtypes = [_bpp] + [_vp] * 8 + [_sz, _i64, _i64, _vp]
@@ -102,7 +104,7 @@ lib = _declare(ctypes.CDLL(LIB_PATH))
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
            "mamba_scan_fwd", "mamba_state_step", "mamba_conv_state_step", "mamba_state_fork", "mamba_tree_plan",
            "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "mamba_block_workspace_bytes",
-           "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd",
+           "mamba_block_workspace_layout", "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd",
            "mamba2_ssd_workspace_bytes", "mamba2_ssd_fwd", "mamba2_state_step")
 
 
@@ -149,6 +151,15 @@ def _stream(stream):
     return s.cuda_stream
 
 
+def _scratch(nbytes, device, stream):
+    """A workspace the binding allocates for one call and drops on return.  The caching allocator may hand the
+    block to later work on the current stream, so when the call runs on another stream the block is tied to it."""
+    ws = torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+    if stream is not None and stream != torch.cuda.current_stream(device):
+        ws.record_stream(stream)
+    return ws
+
+
 def mamba_conv1d_fwd(x, w, bias=None, conv_state_in=None, y=None, conv_state_out=None,
                      apply_silu=True, want_state=True, stream=None):
     """x (B,L,D) f32|bf16, w (D,K) f32 -> y (B,L,D), conv_state_out (B,D,K-1)."""
@@ -185,7 +196,7 @@ def mamba_scan_fwd(x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, h0=None, 
         h_final = torch.empty((B, D, N), dtype=torch.float32, device=x.device)
     need = mamba_scan_workspace_bytes(B, L, D, N, chunk_len)
     if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        workspace = _scratch(need, x.device, stream)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st = lib.mamba_scan_fwd(
         _ptr(x, name="x"), _ptr(dt, x.dtype, (B, L, D), "dt"), _ptr(A, torch.float32, (D, N), "A"),
@@ -362,6 +373,18 @@ def mamba_block_workspace_bytes(block: Block, batch, L) -> int:
     return int(lib.mamba_block_workspace_bytes(ctypes.byref(block.c), batch, L))
 
 
+def mamba_block_workspace_layout(block: Block, batch, L, workspace):
+    """Views of the stage tensors mamba_block_fwd left in ``workspace`` (uint8 device tensor) on its last call with
+    this batch and L: dict with dt, z, x_c, y (rows, d_inner), dt_low (rows, dt_rank), B, C (rows, d_state), bf16."""
+    off = (ctypes.c_int64 * 7)()
+    _check("mamba_block_workspace_layout", lib.mamba_block_workspace_layout(ctypes.byref(block.c), batch, L, off))
+    rows = batch * L
+    widths = dict(dt=block.d_inner, z=block.d_inner, x_c=block.d_inner, y=block.d_inner, dt_low=block.dt_rank,
+                  B=block.d_state, C=block.d_state)
+    return {k: workspace[off[i]:off[i] + rows * w * 2].view(torch.bfloat16).view(rows, w)
+            for i, (k, w) in enumerate(widths.items())}
+
+
 def mamba_block_fwd(block: Block, hidden, hidden_out=None, conv_state_in=None, h0=None, conv_state_out=None,
                     h_final=None, workspace=None, want_state=True, stream=None):
     """hidden (B,L,d_model) bf16 -> hidden + mixer(rmsnorm(hidden)); also the conv and SSM states."""
@@ -375,7 +398,7 @@ def mamba_block_fwd(block: Block, hidden, hidden_out=None, conv_state_in=None, h
         h_final = torch.empty((B, D, N), dtype=torch.float32, device=hidden.device)
     need = mamba_block_workspace_bytes(block, B, L)
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=hidden.device)
+        workspace = _scratch(need, hidden.device, stream)
     st = lib.mamba_block_fwd(
         ctypes.byref(block.c), _ptr(hidden, torch.bfloat16, name="hidden"),
         _ptr(hidden_out, torch.bfloat16, (B, L, dm), "hidden_out"),
@@ -405,7 +428,7 @@ def mamba_block_step(block: Block, hidden, conv_src, ssm_src, parent_idx=None, c
             ssm_dst = torch.empty((n_out, D, N), dtype=torch.float32, device=hidden.device)
     need = mamba_block_workspace_bytes(block, n_out, 1)
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=hidden.device)
+        workspace = _scratch(need, hidden.device, stream)
     st = lib.mamba_block_step(
         ctypes.byref(block.c), _ptr(hidden, torch.bfloat16, name="hidden"),
         _ptr(hidden_out, torch.bfloat16, (n_out, dm), "hidden_out"),
@@ -458,7 +481,7 @@ def mamba2_ssd_fwd(x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, h0=None, 
         h_final = torch.empty((B, H, P, N), dtype=torch.float32, device=x.device)
     need = mamba2_ssd_workspace_bytes(B, L, H, P, N)
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+        workspace = _scratch(need, x.device, stream)
     st = lib.mamba2_ssd_fwd(
         _ptr(x, name="x"), _ptr(dt, x.dtype, (B, L, H), "dt"), _ptr(A, torch.float32, (H,), "A"),
         _ptr(Bm, x.dtype, (B, L, N), "Bm"), _ptr(Cm, x.dtype, (B, L, N), "Cm"), _ptr(Dskip, torch.float32, (H,), "Dskip"),

@@ -18,9 +18,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Wall", "-Wno-unused-function"]
 
 
-def _compile(src: str, extra=(), objdir=OBJDIR) -> str:
-    obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str) -> str:
+    obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
+    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                      if "packed-fp32-ops" not in l and "unknown target" not in l.lower())
@@ -31,18 +31,17 @@ def _compile(src: str, extra=(), objdir=OBJDIR) -> str:
     return obj
 
 
-def build(verbose: bool = False, extra=(), lib: str = LIB, objdir: str = OBJDIR) -> str:
-    """Compile every source and link `lib`.  `extra` adds compiler flags (used for tuning builds
-    that go to another `lib`/`objdir`)."""
-    os.makedirs(objdir, exist_ok=True)
+def build(verbose: bool = False) -> str:
+    """Compile every source and link libmamba_hip.so next to this file."""
+    os.makedirs(OBJDIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, extra, objdir), SOURCES))
-    tmp = lib + ".tmp%d" % os.getpid()
+        objs = list(ex.map(_compile, SOURCES))
+    tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
-    os.replace(tmp, lib)
+    os.replace(tmp, LIB)
     if verbose:
-        print("built", lib)
-    return lib
+        print("built", LIB)
+    return LIB
 
 
 if __name__ == "__main__":

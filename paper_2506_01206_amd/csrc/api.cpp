@@ -331,9 +331,10 @@ bool block_layout(const mamba_block_params_t *p, int64_t batch, int64_t L, void 
     int64_t cl, nc;
     scan_plan(batch, L, p->d_inner, p->d_state, 0, &cl, &nc);
     const size_t sws = scan_workspace_bytes(batch, p->d_inner, p->d_state, nc);
-    char *q = static_cast<char *>(base);
+    // integer arithmetic on the address: the size queries lay out from a null base
+    const uintptr_t q = reinterpret_cast<uintptr_t>(base);
     int64_t off = 0;
-    auto take = [&](int64_t n) { char *r = q + off; off += align256(n); return r; };
+    auto take = [&](int64_t n) { char *r = reinterpret_cast<char *>(q + (uintptr_t)off); off += align256(n); return r; };
     bb->a = take(big); bb->b = take(big); bb->c = take(big); bb->d = take(big);
     bb->dtl = take(dtl); bb->bm = take(bc); bb->cm = take(bc);
     int64_t xp = 0;
@@ -369,6 +370,19 @@ size_t mamba_block_workspace_bytes(const mamba_block_params_t *p, int64_t batch,
     BlockBuffers bb;
     if (!block_layout(p, batch, L, nullptr, &bb)) return 0;
     return bb.total;
+}
+
+int mamba_block_workspace_layout(const mamba_block_params_t *p, int64_t batch, int64_t L, int64_t offsets[7])
+{
+    const int st = block_params_ok(p);
+    if (st != MAMBA_OK) return st;
+    if (!offsets) return MAMBA_ERR_NULL_POINTER;
+    if (batch <= 0 || L <= 0) return MAMBA_ERR_BAD_SHAPE;
+    BlockBuffers bb;
+    if (!block_layout(p, batch, L, nullptr, &bb)) return MAMBA_ERR_BAD_SHAPE;
+    const void *at[7] = {bb.a, bb.b, bb.c, bb.d, bb.dtl, bb.bm, bb.cm};
+    for (int i = 0; i < 7; ++i) offsets[i] = (int64_t)reinterpret_cast<uintptr_t>(at[i]);   // laid out from a null base
+    return MAMBA_OK;
 }
 
 int mamba_block_fwd(const mamba_block_params_t *p, const void *hidden, void *hidden_out,

@@ -17,14 +17,8 @@
 namespace mamba {
 namespace {
 
-#ifndef MAMBA_CONV_ROWS
-#define MAMBA_CONV_ROWS 8
-#endif
-#ifndef MAMBA_CONV_TILE
-#define MAMBA_CONV_TILE 32
-#endif
 constexpr int kBlock = 64;
-constexpr int kRows = MAMBA_CONV_ROWS;  // rows loaded together, one group ahead
+constexpr int kRows = 8;       // rows loaded together, one group ahead
 
 template <typename T, int VEC> struct RowVec;
 template <> struct RowVec<float, 4> { typedef float4 type; };
@@ -210,7 +204,7 @@ template <typename T, int VEC, int K> hipError_t launch_conv_k(const ConvArgs &a
     // Time tiles: enough workgroups to fill the chip, long enough to amortize the K-1 halo rows.
     // An in-place state update keeps one tile so that a thread reads the state before it writes it.
     // Short inputs get shorter tiles (down to one group of rows) until there are about two wavefronts per SIMD.
-    int64_t tile_len = MAMBA_CONV_TILE;
+    int64_t tile_len = 32;
     while (tile_len > kRows && (int64_t)gx * ((a.L + tile_len - 1) / tile_len) * a.batch < 2048) tile_len /= 2;
     if (a.state_out && a.state_in == a.state_out) tile_len = a.L;
     if ((a.L + tile_len - 1) / tile_len > 65535) tile_len = (a.L + 65534) / 65535;

@@ -41,24 +41,10 @@ __device__ __forceinline__ void lds_barrier_linear()
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
-#ifndef MAMBA_LINEAR_BIG
-#define MAMBA_LINEAR_BIG 512
-#endif
-#ifndef MAMBA_LINEAR_MID
-#define MAMBA_LINEAR_MID 512
-#endif
-#ifndef MAMBA_LINEAR_WIDE
-#define MAMBA_LINEAR_WIDE 96
-#endif
-#ifndef MAMBA_LINEAR_WIDE_SMALL
-#define MAMBA_LINEAR_WIDE_SMALL 192
-#endif
-#ifndef MAMBA_LINEAR_WIDE_SMALL_MAX
-#define MAMBA_LINEAR_WIDE_SMALL_MAX 512
-#endif
-#ifndef MAMBA_LINEAR_DEEP
-#define MAMBA_LINEAR_DEEP 513
-#endif
+
+// tile counts from which each kernel shape takes over (measured crossovers, see launch_linear)
+constexpr int64_t kTilesBig = 512, kTilesMid = 512, kTilesWide = 96, kTilesWideSmall = 192, kTilesWideSmallMax = 512,
+                  kTilesDeep = 513;
 
 struct OutSplit {
     bf16_t *ptr[3];
@@ -876,7 +862,6 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
         return hipGetLastError();
     }
     auto tiles = [&](int64_t bm, int64_t bn) { return ((N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
-#ifndef MAMBA_LINEAR_NO_WIDE
     if (vec && a.M % 128 == 0 && a.K % (2 * kWideBK) == 0 && a.K >= 2 * kWideBK) {
         // The memory-to-LDS kernel with 128 x 128 tiles (two workgroups to a CU) from 192 tiles on, while 256 x 128
         // ones would come to fewer than two per CU: in_proj on 2048 tokens 17.6 -> 16.3 us, on 4096 tokens 32 -> 29 us,
@@ -888,27 +873,26 @@ hipError_t launch_linear(const LinearArgs &a, hipStream_t stream)
         const int64_t t256 = m256 && N % 256 == 0 ? (a.M / kWideBM) * (N / 256) : 0;
         const int64_t t128 = m256 && N % 128 == 0 ? (a.M / kWideBM) * (N / 128) : 0;
         const int64_t t128s = N % 128 == 0 ? (a.M / 128) * (N / 128) : 0;
-        if (t128s >= MAMBA_LINEAR_WIDE_SMALL && t128 < MAMBA_LINEAR_WIDE_SMALL_MAX) {
+        if (t128s >= kTilesWideSmall && t128 < kTilesWideSmallMax) {
             linear_wide_kernel<128, 128><<<(unsigned)(8 * ((t128s + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 128), (int)t128s);
             return hipGetLastError();
         }
-        if (t256 >= MAMBA_LINEAR_WIDE && (t256 % 256 == 0 || t256 >= 4 * 256 || t128 == 0)) {
+        if (t256 >= kTilesWide && (t256 % 256 == 0 || t256 >= 4 * 256 || t128 == 0)) {
             linear_wide_kernel<256, 256><<<(unsigned)(8 * ((t256 + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 256), (int)t256);
             return hipGetLastError();
         }
-        if (t128 >= MAMBA_LINEAR_WIDE) {
+        if (t128 >= kTilesWide) {
             linear_wide_kernel<256, 128><<<(unsigned)(8 * ((t128 + 7) / 8)), 256, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, (int)(N / 128), (int)t128);
             return hipGetLastError();
         }
     }
-#endif
-    if (tiles(128, 128) >= MAMBA_LINEAR_BIG) {
+    if (tiles(128, 128) >= kTilesBig) {
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 127) / 128));
         linear_kernel<128, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
-    } else if (tiles(64, 128) >= MAMBA_LINEAR_MID) {
+    } else if (tiles(64, 128) >= kTilesMid) {
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)((a.M + 63) / 64));
         linear_kernel<64, 128, 64><<<grid, kThreads, 0, stream>>>(x, w, a.bias, res, o, a.M, N, a.K, vec);
-    } else if (a.K >= 512 && tiles(64, 64) < MAMBA_LINEAR_DEEP) {
+    } else if (a.K >= 512 && tiles(64, 64) < kTilesDeep) {
         // few tiles and a long k loop (x_proj, out_proj on a context of a few thousand tokens): with one or two
         // workgroups per CU nothing hides the fetch of the next slab, so the slabs are made four times deeper
         // and the loop four times shorter

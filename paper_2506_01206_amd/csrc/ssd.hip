@@ -62,17 +62,6 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-#ifdef MAMBA_SSD_TIMING
-// tuning builds only: shader clock at the phase boundaries of one chunk of one workgroup, per wavefront
-__device__ long long g_ssd_clock[8][16];
-#define SSD_STAMP(i)                                                                                       \
-    do {                                                                                                   \
-        if (blockIdx.x == 3 && blockIdx.y == 1 && chunk == c_first + 6 && lane == 0)                       \
-            g_ssd_clock[wave][i] = (long long)__builtin_amdgcn_s_memtime();                                \
-    } while (0)
-#else
-#define SSD_STAMP(i)
-#endif
 
 // four values -> their bf16 roundings and the bf16 of what the roundings dropped, packed in order
 __device__ __forceinline__ void split4(const float *v, uint2 *top, uint2 *rem)
@@ -324,7 +313,6 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
             };
             for (int chunk = c_first; chunk < c_last; ++chunk) {
                 const int buf = (chunk - c_first) & 1;
-                SSD_STAMP(0);
                 epilogue();
                 if ((int64_t)chunk * kLc + kLc > L) {                 // only the last chunk of a row: zero C past L
 #pragma unroll
@@ -338,9 +326,7 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                     *reinterpret_cast<uint4 *>(&zt[(sx0 + 1) * kRowS + px0]) = Pz1;
                 }
                 fetch_late(chunk + 1);
-                SSD_STAMP(1);
                 lds_barrier();                                        // the raw tiles are in LDS
-                SSD_STAMP(2);
                 if (half <= tt) {                                     // the block above the diagonal is masked out entirely
                     float4 cs[4], ds[4];                              // running sums and deltas of the lane's 16 steps s
 #pragma unroll
@@ -349,7 +335,6 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                         ds[g] = delta4[buf][half * 8 + 2 * g + up];
                     }
                     const float ct = cum[buf][t];
-                    SSD_STAMP(8);
                     f32x16 gacc;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) gacc[i] = 0.0f;
@@ -365,7 +350,6 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
 #pragma unroll
                         for (int ks = 0; ks < N / 16; ++ks) gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ks], cf[ks], gacc, 0, 0, 0);
                     }
-                    SSD_STAMP(9);
                     // gacc[4 g + q] = C_t . B_s, t = 32 tt + lane % 32, s = 32 half + 8 g + 4 (lane / 32) + q
                     // M = G * exp(s_t - s_s) * delta_s for s <= t (steps past L have delta = 0), + D on the diagonal
 #pragma unroll
@@ -381,9 +365,7 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                         split4(v, reinterpret_cast<uint2 *>(&mm_hi[t * kRowS + s0]), reinterpret_cast<uint2 *>(&mm_lo[t * kRowS + s0]));
                     }
                 }
-                SSD_STAMP(3);
                 lds_barrier();                                        // M is in LDS
-                SSD_STAMP(4);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) inter[i] = intra[i] = 0.0f;
                 {
@@ -416,7 +398,6 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                             intra = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[ks], ml[ks], intra, 0, 0, 0);
                         }
                 }
-                SSD_STAMP(10);
                 // inter / intra [4 g + q]: step t = 32 tt + lane % 32, channel p = 32 half + 8 g + 4 (lane / 32) + q;
                 // what the gate needs leaves LDS now, the arithmetic waits for the next chunk's first phase
                 e_t = exp2_hw(cum[buf][t] * kLog2e);
@@ -425,9 +406,7 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                     for (int g = 0; g < 4; ++g) zq[g] = *reinterpret_cast<const uint2 *>(&zt[t * kRowS + half * 32 + 8 * g + 4 * up]);
                 }
                 tok_prev = (int64_t)chunk * kLc + t;
-                SSD_STAMP(5);
                 lds_barrier();                                        // the chunk's LDS tiles are free again
-                SSD_STAMP(6);
             }
             epilogue();
         }
@@ -435,7 +414,6 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
         // one chunk; cur holds its B and x pieces (and takes those of the chunk after the next), nxt the next chunk's
         auto walk = [&](int chunk, Early &cur, Early &nxt) {
             const int buf = (chunk - c_first) & 1;
-            if constexpr (PASS2) SSD_STAMP(0);
             if constexpr (PASS2) {
 #pragma unroll
                 for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4 *>(&b_rows[(sb0 + i) * kRowN + nb0]) = cur.b[i];
@@ -454,13 +432,10 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                 }
             }
             fetch_early(chunk + 2, cur);
-            if constexpr (PASS2) SSD_STAMP(1);
             if constexpr (PASS2) lds_barrier();                   // the raw tiles are in LDS
-            if constexpr (PASS2) SSD_STAMP(2);
             if (scan_wave && chunk + 1 < c_last) prefix(chunk + 1, dt_next, buf ^ 1);
             dt_next = dt_after;
             dt_after = fetch_dt(chunk + 3);
-            if constexpr (PASS2) SSD_STAMP(8);
             // state: acc <- exp(s_end) acc + sum_s bt[n][s] xw[p][s]
             const float dec = exp2_hw(cum[buf][kLc - 1] * kLog2e);
 #pragma unroll
@@ -475,16 +450,12 @@ ssd_segment(const bf16_t *x, const bf16_t *dt, const float *__restrict__ A, cons
                     acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, tfrag(xw_lo, pt * 32 + r, ks * 16 + hk), acc[j], 0, 0, 0);
                 }
             }
-            if constexpr (PASS2) SSD_STAMP(3);
             lds_barrier();                                        // the state operands are used up; the next delta sums are in LDS
-            if constexpr (PASS2) SSD_STAMP(4);
             if (chunk + 1 < c_last) {
                 mask_early(chunk + 1, nxt);
                 park_state_operands(nxt, buf ^ 1);
             }
-            if constexpr (PASS2) SSD_STAMP(5);
             lds_barrier();                                        // the chunk's LDS tiles are free again
-            if constexpr (PASS2) SSD_STAMP(6);
         };
         for (int chunk = c_first; chunk < c_last; chunk += 2) {
             walk(chunk, E2[0], E2[1]);
@@ -667,10 +638,3 @@ hipError_t launch_ssd_step(const SsdStepArgs &a, hipStream_t stream)
 }
 
 }  // namespace mamba
-
-#ifdef MAMBA_SSD_TIMING
-extern "C" int mamba2_debug_clock(long long *host)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mamba::g_ssd_clock), sizeof(long long) * 128);
-}
-#endif

@@ -56,9 +56,7 @@ __device__ __forceinline__ void st_stream(float4 *p, float4 v)
     __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(p));
 }
 
-#ifndef MAMBA_STEP_UNROLL
-#define MAMBA_STEP_UNROLL 4
-#endif
+constexpr int kStepUnroll = 4;
 
 // grid: (ceil(D * N / 4 / (256 * U)), n_out).  A lane owns U float4s of the branch's (D, N) state,
 // 256 float4s apart, so every wavefront load or store is still one contiguous 1 KiB run; all
@@ -500,8 +498,8 @@ template <typename T, int N> hipError_t launch_step_n(const StepArgs &a, hipStre
     // several float4s per lane as long as that still leaves about three workgroups per CU
     const int64_t row4 = a.D * (N / 4);
     auto blocks = [&](int u) { return a.n_out * ((row4 + kBlock * u - 1) / (kBlock * u)); };
-    if (blocks(MAMBA_STEP_UNROLL) >= 768) return launch_step_u<T, N, MAMBA_STEP_UNROLL>(a, stream);
-    if (MAMBA_STEP_UNROLL > 2 && blocks(2) >= 768 && !a.conv_w) return launch_step_u<T, N, 2>(a, stream);
+    if (blocks(kStepUnroll) >= 768) return launch_step_u<T, N, kStepUnroll>(a, stream);
+    if (kStepUnroll > 2 && blocks(2) >= 768 && !a.conv_w) return launch_step_u<T, N, 2>(a, stream);
     return launch_step_u<T, N, 1>(a, stream);
 }
 

@@ -125,23 +125,6 @@ def config_decode(name: str, n_layers=None):
                        SEEDS[name] + 100)
 
 
-def tree_batch_sizes(tree):
-    """Batch size at each draft position for a tree (N_1..N_gamma): the running product
-    B_i = N_1 * ... * N_i (Sec. 4.1)."""
-    sizes, b = [], 1
-    for n in tree:
-        b *= int(n)
-        sizes.append(b)
-    return sizes
-
-
-def tree_parents(tree):
-    """Parent-index arrays for a tree (N_1..N_gamma), root batch of 1: the N_i children of
-    node p at depth i occupy slots p*N_i .. p*N_i + N_i - 1, so parent[j] = j // N_i."""
-    return [np.arange(b, dtype=np.int32) // np.int32(n)
-            for b, n in zip(tree_batch_sizes(tree), tree)]
-
-
 def block_weights(rng: np.random.Generator, d_model: int, D: int, N: int, K: int, dt_rank: int):
     """Random weights of one Mamba block in storage form: the SSM-core parameters of ``layer_params``
     plus RMSNorm weight ~ 1 + 0.1 N(0,1) (fp32) and projection matrices ~ N(0, 1/fan_in) as bf16 bit

@@ -70,21 +70,6 @@ def assert_close(got, ref, tol, what=""):
     return worst
 
 
-def assert_close_but_for_flips(got, ref, tol, what="", frac=1e-3, slack=3.0):
-    """assert_close for a result behind tensors that were stored in bf16 on the way: fp32 and float64
-    accumulation can land on different sides of a rounding boundary, and where the result is steep in that tensor
-    (a state with strong decay: exp(delta A) moves by |A| delta 2^-8 per flipped dt) a few elements move by more
-    than the tolerance.  At most `frac` of the elements may exceed tol, none may exceed slack * tol."""
-    got = np.asarray(got, dtype=np.float64)
-    ref = np.asarray(ref, dtype=np.float64)
-    assert_close(got, ref, slack * tol, what)
-    rms = float(np.sqrt(np.mean(ref * ref)))
-    if ref.size == 0 or rms == 0.0:
-        return
-    beyond = int(np.count_nonzero(np.abs(got - ref) > tol * np.maximum(np.abs(ref), rms)))
-    assert beyond <= frac * ref.size, "%s: %d of %d elements beyond %.1e" % (what, beyond, ref.size, tol)
-
-
 def oracle_scan(c, channels=None, h0=None, **kw):
     """Oracle scan on a prefill case dict (optionally on a subset of channels)."""
     sl = (lambda a: a) if channels is None else (lambda a: a[..., channels])

@@ -350,6 +350,17 @@ def test_block_validation_and_workspace(b):
     assert ws_bytes(ctypes.byref(p), 0, 1) == 0 and ws_bytes(ctypes.byref(p), 1, 0) == 0
     assert ws_bytes(ctypes.byref(_block_params(b, N=5)), 1, 64) == 0 and ws_bytes(ctypes.byref(_block_params(b, dm=772)), 1, 64) == 0
 
+    # where the stage tensors lie: seven disjoint bf16 tensors inside the workspace, 256-byte aligned, dt first
+    off = (ctypes.c_int64 * 7)()
+    layout = b.lib.mamba_block_workspace_layout
+    assert layout(ctypes.byref(p), 1, 2048, off) == 0
+    sizes = [2048 * 1536 * 2] * 4 + [2048 * 48 * 2, 2048 * 16 * 2, 2048 * 16 * 2]
+    spans = sorted((int(o), int(o) + n) for o, n in zip(off, sizes))
+    assert off[0] == 0 and all(o % 256 == 0 for o in off) and spans[-1][1] <= need_prefill
+    assert all(a[1] <= c[0] for a, c in zip(spans, spans[1:]))
+    assert layout(ctypes.byref(p), 1, 2048, None) == S["NULL_POINTER"] and layout(ctypes.byref(p), 0, 5, off) == S["BAD_SHAPE"]
+    assert layout(ctypes.byref(_block_params(b, N=5)), 1, 64, off) == S["UNSUPPORTED"]
+
     def fwd(p=p, hid=P(0), out=P(1), ci=P(2), co=P(3), h0=P(4), hf=P(5), ws=P(6), wsb=need_prefill, batch=1, L=2048):
         return b.lib.mamba_block_fwd(ctypes.byref(p), hid, out, ci, co, h0, hf, ws, wsb, batch, L, None)
     assert fwd(hid=None) == S["NULL_POINTER"] and fwd(out=None) == S["NULL_POINTER"]

@@ -14,6 +14,7 @@ import pytest
 from scipy.special import expit
 
 import oracle
+from oracle import tree as oracle_tree
 from paper_2506_01206_amd import synth
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -380,8 +381,8 @@ def test_paper_tree_shapes_and_fork_chain():
     r = rnd(93)
     D, N, K = 4, 3, 4
     for tree, sizes in rows:
-        assert synth.tree_batch_sizes(tree) == sizes
-        parents = synth.tree_parents(tree)
+        assert oracle_tree.tree_batch_sizes(tree) == sizes
+        parents = oracle_tree.tree_parents(tree)
         ssm = r.standard_normal((2, 1, D, N)).astype(np.float32)          # root: one state per layer
         conv = r.standard_normal((2, 1, D, K - 1)).astype(np.float32)
         copies = 0
@@ -409,6 +410,40 @@ def test_bf16_widening_is_exact():
     assert np.array_equal(synth.f32_to_bf16_bits(back), bits)
     tie = np.array([0x3F808000, 0x3F818000], dtype=np.uint32).view(np.float32)   # exact ties
     assert list(synth.f32_to_bf16_bits(tie)) == [0x3F80, 0x3F82]
+
+
+def test_round_bf16_of_the_block_oracle():
+    """oracle._round_bf16 (the rounding a stage's stored tensor gets) against what the bfloat16 format fixes: a
+    bfloat16 keeps the sign, the 8 exponent bits and the top 7 fraction bits of a float32, nearest value, ties to
+    the even fraction.  Truncation, rounding half up and rounding half away from zero each fail a line below."""
+    rb = oracle._round_bf16
+    # known values, worked by hand from their float32 bit patterns
+    #   pi  = 0x40490FDB -> 0x4049 (low half below 0x8000: down)  = 3.140625
+    #   0.1 = 0x3DCCCCCD -> 0x3DCD (low half above 0x8000: up)    = 0.10009765625
+    #   1/3 = 0x3EAAAAAB -> 0x3EAB (up)                           = 0.333984375
+    got = rb(np.array([np.pi, 0.1, 1.0 / 3.0, -0.1]))
+    assert got.tolist() == [3.140625, 0.10009765625, 0.333984375, -0.10009765625]
+    # exact ties between neighbours 1 + k 2^-7: to the even fraction, for either sign
+    ties = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 5 * 2.0 ** -8, -(1 + 2.0 ** -8), -(1 + 3 * 2.0 ** -8)])
+    assert rb(ties).tolist() == [1.0, 1 + 2.0 ** -6, 1 + 2.0 ** -6, -1.0, -(1 + 2.0 ** -6)]
+    # just off a tie: to the nearer neighbour
+    assert rb(np.array([1 + 2.0 ** -8 + 2.0 ** -20, 1 + 2.0 ** -8 - 2.0 ** -20])).tolist() == [1 + 2.0 ** -7, 1.0]
+    # values that are bfloat16 already (8 significant bits, any exponent) are fixed points; the result always is one
+    r = rnd(96)
+    exact = np.ldexp(r.integers(128, 256, 500).astype(np.float64), r.integers(-60, 60, 500)) * r.choice([-1.0, 1.0], 500)
+    assert np.array_equal(rb(exact), exact)
+    x = r.standard_normal(4000) * np.exp(r.uniform(-20, 20, 4000))
+    y = rb(x)
+    assert np.array_equal(rb(y), y)
+    mant, _ = np.frexp(y)
+    assert np.array_equal(mant * 256, np.round(mant * 256))                  # 8 significant bits
+    # nearest: within half a unit in the last place (2^-9 relative to the power of two below |x|), some on either side
+    ulp = np.ldexp(1.0, np.floor(np.log2(np.abs(x))).astype(int) - 7)
+    assert np.all(np.abs(y - x) <= 0.5 * ulp)
+    assert (np.abs(y) > np.abs(x)).any() and (np.abs(y) < np.abs(x)).any()
+    # carry out of the fraction: just below a power of two rounds up to it
+    assert rb(np.array([1.99999, 255.9])).tolist() == [2.0, 256.0]
+    assert rb(np.array([0.0, -0.0])).tolist() == [0.0, 0.0] and rb(np.zeros((2, 3))).shape == (2, 3)
 
 
 # ---------------------------------------------------------------- dense parts of the block
