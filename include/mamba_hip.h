@@ -112,6 +112,25 @@ int mamba_scan_fwd(const void *x, const void *dt, const float *A, const void *Bm
                    mamba_dtype_t io, void *hip_stream);
 
 /*
+ * mamba_scan_fwd for callers that cannot allocate device memory or hand over a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the
+ * chunk-boundary states in a buffer that is part of the library's code object (MAMBA_SCAN_STATIC_BYTES
+ * of device memory per GPU the library runs on, held until the process ends).  Same arguments without
+ * the workspace pair.  Calls no allocating routine.  A shape whose mamba_scan_workspace_bytes exceeds
+ * MAMBA_SCAN_STATIC_BYTES is refused with MAMBA_ERR_WORKSPACE and nothing is launched.
+ * Every call on a GPU uses that GPU's one buffer: calls that overlap in time on the same GPU (two
+ * streams, two threads) race on it; calls on one stream, or ordered by events, are safe, and nothing in
+ * the buffer has to be cleared between calls (every slot is written before it is read).
+ * The buffer's address is looked up once per device on the first call there, with that device current.
+ */
+#define MAMBA_SCAN_STATIC_BYTES (32u << 20)
+int mamba_scan_fwd_static(const void *x, const void *dt, const float *A, const void *Bm,
+                          const void *Cm, const float *Dskip, const void *z, const float *dt_bias,
+                          const float *h0, void *out, float *h_final, int64_t batch, int64_t L,
+                          int64_t D, int64_t N, int64_t chunk_len, int dt_softplus,
+                          mamba_dtype_t io, void *hip_stream);
+
+/*
  * One recurrence step for all n_out live branches of a draft tree at once
  * (Sec. 4.1: batch generation with batch size B_i at draft position i; a child
  * continues from its parent's state).  Same equations as the scan with L = 1:

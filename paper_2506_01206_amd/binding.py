@@ -90,6 +90,8 @@ def _declare(lib):
     lib.mamba_scan_workspace_bytes.restype = _sz
     lib.mamba_scan_fwd.argtypes = [_vp] * 12 + [_sz] + [_i64] * 5 + [_int, _int, _vp]
     lib.mamba_scan_fwd.restype = _int
+    lib.mamba_scan_fwd_static.argtypes = [_vp] * 11 + [_i64] * 5 + [_int, _int, _vp]
+    lib.mamba_scan_fwd_static.restype = _int
     lib.mamba_state_step.argtypes = [_vp] * 12 + [_i64] * 4 + [_int, _int, _vp]
     lib.mamba_state_step.restype = _int
     lib.mamba_state_fork.argtypes = [_vp] * 5 + [_i64] * 5 + [_int, _int, _vp]
@@ -102,7 +104,7 @@ def _declare(lib):
 lib = _declare(ctypes.CDLL(LIB_PATH))
 
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
-           "mamba_scan_fwd", "mamba_state_step", "mamba_conv_state_step", "mamba_state_fork", "mamba_tree_plan",
+           "mamba_scan_fwd", "mamba_scan_fwd_static", "mamba_state_step", "mamba_conv_state_step", "mamba_state_fork", "mamba_tree_plan",
            "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "mamba_block_workspace_bytes",
            "mamba_block_workspace_layout", "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd",
            "mamba2_ssd_workspace_bytes", "mamba2_ssd_fwd", "mamba2_state_step")
@@ -207,6 +209,26 @@ def mamba_scan_fwd(x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, h0=None, 
         _ptr(workspace, name="workspace"), ws_bytes, B, L, D, N, int(chunk_len),
         int(bool(dt_softplus)), io, _stream(stream))
     _check("mamba_scan_fwd", st)
+    return out, h_final
+
+
+MAMBA_SCAN_STATIC_BYTES = 32 << 20
+
+
+def mamba_scan_fwd_static(x, dt, A, Bm, Cm, Dskip, z, dt_bias, h0, out, h_final, chunk_len=0, dt_softplus=True,
+                          stream=None):
+    """mamba_scan_fwd with the chunk states in the library's own device buffer.  Allocates nothing: the caller
+    passes every tensor, ``out`` (B,L,D) and ``h_final`` (B,D,N) or None included."""
+    B, L, D = x.shape
+    N = A.shape[1]
+    st = lib.mamba_scan_fwd_static(
+        _ptr(x, name="x"), _ptr(dt, x.dtype, (B, L, D), "dt"), _ptr(A, torch.float32, (D, N), "A"),
+        _ptr(Bm, x.dtype, (B, L, N), "Bm"), _ptr(Cm, x.dtype, (B, L, N), "Cm"),
+        _ptr(Dskip, torch.float32, (D,), "Dskip"), _ptr(z, x.dtype, (B, L, D), "z"),
+        _ptr(dt_bias, torch.float32, (D,), "dt_bias"), _ptr(h0, torch.float32, (B, D, N), "h0"),
+        _ptr(out, x.dtype, (B, L, D), "out"), _ptr(h_final, torch.float32, (B, D, N), "h_final"),
+        B, L, D, N, int(chunk_len), int(bool(dt_softplus)), _io_code(x), _stream(stream))
+    _check("mamba_scan_fwd_static", st)
     return out, h_final
 
 

@@ -92,11 +92,14 @@ size_t mamba_scan_workspace_bytes(int64_t batch, int64_t L, int64_t D, int64_t N
     return scan_workspace_bytes(batch, D, N, nc);
 }
 
-int mamba_scan_fwd(const void *x, const void *dt, const float *A, const void *Bm, const void *Cm,
-                   const float *Dskip, const void *z, const float *dt_bias, const float *h0,
-                   void *out, float *h_final, void *workspace, size_t workspace_bytes,
-                   int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len,
-                   int dt_softplus, mamba_dtype_t io, void *hip_stream)
+namespace {
+
+// validation and launch shared by the two scan entry points; static_ws: take the library's own buffer
+int scan_checked(const void *x, const void *dt, const float *A, const void *Bm, const void *Cm,
+                 const float *Dskip, const void *z, const float *dt_bias, const float *h0,
+                 void *out, float *h_final, void *workspace, size_t workspace_bytes, bool static_ws,
+                 int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len,
+                 int dt_softplus, mamba_dtype_t io, void *hip_stream)
 {
     const int e = io_size(io);
     if (e == 0) return MAMBA_ERR_UNSUPPORTED;
@@ -122,16 +125,44 @@ int mamba_scan_fwd(const void *x, const void *dt, const float *A, const void *Bm
     scan_plan(batch, L, D, N, chunk_len, &cl, &nc);
     if (nc > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
     const size_t need = scan_workspace_bytes(batch, D, N, nc);
-    if (need > 0 && (!workspace || workspace_bytes < need)) return MAMBA_ERR_WORKSPACE;
-    if (need > 0 && (overlap(workspace, (int64_t)need, out, tok_bytes) ||
-                     overlap(workspace, (int64_t)need, x, tok_bytes) ||
-                     overlap(workspace, (int64_t)need, dt, tok_bytes) ||
-                     overlap(workspace, (int64_t)need, h_final, st_bytes)))
-        return MAMBA_ERR_ALIAS;
-    ScanArgs a{x, dt, Bm, Cm, z, A, Dskip, dt_bias, h0, out, h_final,
-               need > 0 ? static_cast<float *>(workspace) : nullptr,
+    float *ws = nullptr;
+    if (static_ws) {
+        if (need > (size_t)MAMBA_SCAN_STATIC_BYTES) return MAMBA_ERR_WORKSPACE;
+        if (need > 0) {
+            const hipError_t he = scan_static_scratch(&ws);
+            if (he != hipSuccess) return (int)he;
+        }
+    } else if (need > 0) {
+        if (!workspace || workspace_bytes < need) return MAMBA_ERR_WORKSPACE;
+        if (overlap(workspace, (int64_t)need, out, tok_bytes) || overlap(workspace, (int64_t)need, x, tok_bytes) ||
+            overlap(workspace, (int64_t)need, dt, tok_bytes) || overlap(workspace, (int64_t)need, h_final, st_bytes))
+            return MAMBA_ERR_ALIAS;
+        ws = static_cast<float *>(workspace);
+    }
+    ScanArgs a{x, dt, Bm, Cm, z, A, Dskip, dt_bias, h0, out, h_final, ws,
                batch, L, D, (int)N, (int)io, dt_softplus, cl, nc};
     return (int)launch_scan(a, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // namespace
+
+int mamba_scan_fwd(const void *x, const void *dt, const float *A, const void *Bm, const void *Cm,
+                   const float *Dskip, const void *z, const float *dt_bias, const float *h0,
+                   void *out, float *h_final, void *workspace, size_t workspace_bytes,
+                   int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len,
+                   int dt_softplus, mamba_dtype_t io, void *hip_stream)
+{
+    return scan_checked(x, dt, A, Bm, Cm, Dskip, z, dt_bias, h0, out, h_final, workspace, workspace_bytes, false,
+                        batch, L, D, N, chunk_len, dt_softplus, io, hip_stream);
+}
+
+int mamba_scan_fwd_static(const void *x, const void *dt, const float *A, const void *Bm, const void *Cm,
+                          const float *Dskip, const void *z, const float *dt_bias, const float *h0,
+                          void *out, float *h_final, int64_t batch, int64_t L, int64_t D, int64_t N,
+                          int64_t chunk_len, int dt_softplus, mamba_dtype_t io, void *hip_stream)
+{
+    return scan_checked(x, dt, A, Bm, Cm, Dskip, z, dt_bias, h0, out, h_final, nullptr, 0, true,
+                        batch, L, D, N, chunk_len, dt_softplus, io, hip_stream);
 }
 
 int mamba_state_step(float *h_out, const float *h_in, const int32_t *parent_idx, const void *x,

@@ -40,6 +40,9 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
                int64_t *chunk_len, int64_t *n_chunks);
 size_t scan_workspace_bytes(int64_t batch, int64_t D, int64_t N, int64_t n_chunks);
 hipError_t launch_scan(const ScanArgs &a, hipStream_t stream);
+// Device address, on the current device, of the chunk-state buffer that is part of the code object (the
+// allocation-free scan entry point); looked up once per device.
+hipError_t scan_static_scratch(float **ptr);
 // Carry over chunk states, in place: slot 0 <- h0 (or 0); slot c <- exp(A * sumdt[c-1]) * slot[c-1] + slot[c].
 // ws_state: (batch, n_slots, D, N) fp32, slot c holding the local end state of chunk c - 1 on entry;
 // ws_sumdt: (batch, n_slots, D) fp32, entry c the sum of deltas of chunk c; A: (D, N).

@@ -19,8 +19,15 @@
 //       loop per (d, n) (the decay over a whole chunk needs only S_c, not a product per step);
 //   pass 2 (scan_chunk_out): every chunk runs the full recurrence from its true h_in[c].
 // With one chunk only pass 2 runs, straight from h0.
+#include <mutex>
+
+#include "../../include/mamba_hip.h"
 #include "device_math.h"
 #include "launch.h"
+
+// Chunk states of the allocation-free entry point (mamba_scan_fwd_static): device memory that comes with the code
+// object, one copy per GPU at its own address, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[MAMBA_SCAN_STATIC_BYTES];
 
 namespace mamba {
 namespace {
@@ -723,6 +730,31 @@ size_t scan_workspace_bytes(int64_t batch, int64_t D, int64_t N, int64_t n_chunk
 {
     if (n_chunks <= 1) return 0;
     return (size_t)batch * (size_t)n_chunks * (size_t)D * (size_t)(N + 1) * sizeof(float);
+}
+
+// ---------------------------------------------------------------------------------------
+// Address of the allocation-free entry point's chunk-state buffer (file scope, top of this file) on the current
+// device.  In host code the array's name only stands for the symbol: the address comes from hipGetSymbolAddress,
+// once per device with that device current, and only that pointer is ever handed to kernels.
+hipError_t scan_static_scratch(float **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(::scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = static_cast<float *>(per_device[dev]);
+    return hipSuccess;
 }
 
 hipError_t launch_scan(const ScanArgs &a, hipStream_t stream)

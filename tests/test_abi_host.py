@@ -105,6 +105,24 @@ def test_scan_validation(b):
     assert b.mamba_scan_workspace_bytes(1, 4096, 256, 16, 1 << 40) == 0
 
 
+def test_static_scan_validation(b):
+    """The allocation-free scan validates like mamba_scan_fwd and refuses, before any HIP call, a shape whose chunk
+    states do not fit the library's own buffer."""
+    S = b.STATUS
+
+    def sscan(x=P(0), dt=P(1), A=P(2), Bm=P(3), Cm=P(4), Dk=P(5), z=P(6), bias=P(7), h0=P(8), out=P(9), hf=P(10),
+              batch=4, L=8192, D=4096, N=16, chunk=64, sp=1, io=1):
+        return b.lib.mamba_scan_fwd_static(x, dt, A, Bm, Cm, Dk, z, bias, h0, out, hf, batch, L, D, N, chunk, sp, io, None)
+    assert b.mamba_scan_workspace_bytes(4, 8192, 4096, 16, 64) > b.MAMBA_SCAN_STATIC_BYTES
+    assert sscan() == S["WORKSPACE"]
+    assert sscan(x=None) == S["NULL_POINTER"] and sscan(out=None) == S["NULL_POINTER"]
+    assert sscan(L=-1) == S["BAD_SHAPE"] and sscan(N=17) == S["UNSUPPORTED"] and sscan(io=9) == S["UNSUPPORTED"]
+    assert sscan(x=P(0) + 8) == S["MISALIGNED"] and sscan(out=P(0)) == S["ALIAS"]
+    assert sscan(batch=0) == 0 and sscan(D=0) == 0
+    header = open(HEADER).read()
+    assert "#define MAMBA_SCAN_STATIC_BYTES (32u << 20)" in header and b.MAMBA_SCAN_STATIC_BYTES == 32 << 20
+
+
 def test_scan_workspace_query(b):
     w = b.mamba_scan_workspace_bytes
     assert w(0, 10, 10, 16, 0) == 0 and w(1, 0, 10, 16, 0) == 0 and w(1, 10, 10, 16, -1) == 0
