@@ -49,7 +49,10 @@
 extern "C" {
 #endif
 
-typedef enum { MAMBA_F32 = 0, MAMBA_BF16 = 1 } mamba_dtype_t;
+/* I/O element type of a call.  A plain int in the signatures, so that a value outside the list is an
+ * ordinary argument the library can refuse (MAMBA_ERR_UNSUPPORTED), not an invalid enumeration value. */
+typedef int mamba_dtype_t;
+enum { MAMBA_F32 = 0, MAMBA_BF16 = 1 };
 
 typedef enum {
     MAMBA_OK = 0,

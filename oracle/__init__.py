@@ -35,8 +35,10 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        other = os.environ.get("MAMBA_ORACLE_LIB")       # another build of mamba_oracle.c (the sanitizer run)
+        if not other:
+            build()
+        lib = ctypes.CDLL(other or _LIB)
         dp = ctypes.c_void_p
         lg = ctypes.c_long
         lib.oracle_num_threads.restype = ctypes.c_int

@@ -14,7 +14,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmamba_hip.so")
+# MAMBA_HIP_LIB names another build of the same library (the host-sanitizer run loads an instrumented one)
+LIB_PATH = os.environ.get("MAMBA_HIP_LIB") or os.path.join(_HERE, "libmamba_hip.so")
 
 MAMBA_F32 = 0
 MAMBA_BF16 = 1

@@ -49,8 +49,9 @@ def test_library_exports_every_declared_symbol(b):
         assert getattr(raw, name) is not None and callable(getattr(tree_search, name))
 
 
-def test_binding_without_the_library_refuses_to_import(tmp_path):
+def test_binding_without_the_library_refuses_to_import(tmp_path, monkeypatch):
     """No fallback: a copy of the binding that finds no built library beside it raises on import."""
+    monkeypatch.delenv("MAMBA_HIP_LIB", raising=False)
     import importlib.util
     import shutil
     shutil.copy(os.path.join(ROOT, "paper_2506_01206_amd", "binding.py"), tmp_path / "binding.py")
