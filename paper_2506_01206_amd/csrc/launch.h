@@ -34,7 +34,11 @@ struct ScanArgs {
     int64_t batch, L, D;
     int N, io, dt_softplus;
     int64_t chunk_len, n_chunks;
+    int direct = 0;  // 1: the single-pass kernel of scan_direct.hip (n_chunks == 1, no workspace)
 };
+// Whether the library's own choice (chunk_len = 0) for this shape is the single-pass kernel.
+bool scan_direct_applies(int64_t batch, int64_t L, int64_t D, int64_t N);
+hipError_t launch_scan_direct(const ScanArgs &a, hipStream_t stream);
 // Chunking chosen for a shape when the caller passes chunk_len = 0 (pure function of the shape).
 void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len_req,
                int64_t *chunk_len, int64_t *n_chunks);

@@ -697,7 +697,6 @@ hipError_t launch_copy_state(const float *src, float *dst, int64_t n, hipStream_
 void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len_req,
                int64_t *chunk_len, int64_t *n_chunks)
 {
-    (void)N;
     if (L <= 0 || batch <= 0 || D <= 0) {
         *chunk_len = L > 0 ? L : 1;
         *n_chunks = 1;
@@ -706,6 +705,8 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
     int64_t cl;
     if (chunk_len_req > 0) {
         cl = chunk_len_req;
+    } else if (scan_direct_applies(batch, L, D, N)) {
+        cl = L;  // enough independent channels: one pass, no chunks
     } else {
         const int64_t cpl = scan_channels_per_lane(batch, L, D);
         const int64_t columns = batch * ((D + kWave * cpl - 1) / (kWave * cpl));
@@ -722,6 +723,8 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
         }
     }
     if (cl > L) cl = L;
+    // the chunk index is a grid dimension: the library's own choice never asks for more chunks than that allows
+    if (chunk_len_req <= 0 && (L + cl - 1) / cl > 65535) cl = ((L + 65534) / 65535 + kTile - 1) / kTile * kTile;
     *chunk_len = cl;
     *n_chunks = (L + cl - 1) / cl;
 }
@@ -767,6 +770,7 @@ hipError_t launch_scan(const ScanArgs &a, hipStream_t stream)
         }
         return hipSuccess;
     }
+    if (a.direct) return launch_scan_direct(a, stream);
     if (a.io == kIoBf16) return launch_scan_io<bf16_t>(a, stream);
     return launch_scan_io<float>(a, stream);
 }

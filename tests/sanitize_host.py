@@ -4,7 +4,8 @@
 
 Builds, into a temporary directory, (1) libmamba_hip.so with its host side instrumented (argument validation,
 plans, workspace layouts, the tree search; the device code is compiled as usual and never runs here) and
-(2) oracle/mamba_oracle.c, both with -fsanitize=address,undefined and the shared sanitizer runtime, then runs the
+(2) oracle/mamba_oracle.c, both with the address and undefined-behaviour sanitizers (host code only) and the shared
+sanitizer runtime, then runs the
 host tests (tests/test_abi_host.py, tests/test_tree_search.py, tests/test_oracle_pins.py) in a child process that
 loads those two libraries instead of the regular ones (MAMBA_HIP_LIB, MAMBA_ORACLE_LIB) with the runtime preloaded.
 Exit status 0: tests green and no sanitizer report.  GPU code is not covered (no GPU sanitizer on this pool).
@@ -20,8 +21,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 CLANG = os.environ.get("MAMBA_CLANG", "/opt/rocm/lib/llvm/bin/clang")
-SAN = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
-       "-Xarch_host", "-fno-sanitize-recover=undefined"]
+# host code only: never the device code
+SAN = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined"]
+LINK_SAN = ["-fsanitize=address,undefined", "-fno-gpu-sanitize", "-shared-libasan"]
 
 
 def runtime():
@@ -44,12 +46,11 @@ def build(tmp):
     with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(one, hip_build.SOURCES))
     hip_lib = os.path.join(tmp, "libmamba_hip_san.so")
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address,undefined",
-                           "-fno-gpu-sanitize", "-shared-libasan", "-o", hip_lib] + objs)
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + LINK_SAN + ["-o", hip_lib] + objs)
     oracle_lib = os.path.join(tmp, "libmamba_oracle_san.so")
-    subprocess.check_call([CLANG, "-O1", "-g", "-fno-omit-frame-pointer", "-std=c11", "-fPIC", "-shared",
-                           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-shared-libasan",
-                           "-ffp-contract=off", "-o", oracle_lib, os.path.join(ROOT, "oracle", "mamba_oracle.c"), "-lm"])
+    subprocess.check_call([CLANG, "-O1", "-g", "-fno-omit-frame-pointer", "-std=c11", "-fPIC", "-shared"] + LINK_SAN +
+                          ["-fno-sanitize-recover=undefined", "-ffp-contract=off", "-Wno-unused-command-line-argument",
+                           "-o", oracle_lib, os.path.join(ROOT, "oracle", "mamba_oracle.c"), "-lm"])
     return hip_lib, oracle_lib
 
 

@@ -139,6 +139,12 @@ def test_scan_workspace_query(b):
     assert 2 <= n_chunks <= 32768 // 32
     # a batch-rich shape fills the chip without cutting time
     assert w(128, 4096, 4096, 16, 0) == 0
+    # a very long batch-1 sequence: the library's own chunking stays within the 65535 chunks a launch can index
+    # (an explicit chunk length that needs more is refused by the call itself)
+    L = 256 * 65535 + 12345
+    n = w(1, L, 8, 16, 0) // (8 * 17 * 4)
+    assert 2 <= n <= 65535
+    assert scan(b, L=L, D=8, batch=1, chunk=256, ws_bytes=1 << 40) == b.STATUS["UNSUPPORTED"]
 
 
 def conv(b, x=P(0), w=P(1), bias=P(2), si=P(3), y=P(4), so=P(5), batch=2, L=100, D=64, K=4,

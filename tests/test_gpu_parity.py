@@ -154,6 +154,35 @@ def test_scan_carry_variants(m, N, L, chunk_len):
 
 
 @pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("N", [4, 8, 16, 32])
+@pytest.mark.parametrize("B,L,D", [(56, 1, 256), (56, 31, 256), (28, 65, 512), (56, 100, 200), (224, 129, 64), (230, 7, 8)])
+def test_scan_single_pass_shapes(m, io, N, B, L, D):
+    """Shapes with enough independent channels that the library walks every token once (no time chunks, no
+    workspace): tile tails, a channel block that is only partly there (D = 200, D = 8), every state size."""
+    say(io=io, N=N, B=B, L=L, D=D)
+    assert m.mamba_scan_workspace_bytes(B, L, D, N) == 0
+    c = synth.prefill_case(B, L, D, N, 4, io, seed=40000 + N + L + D, random_A=True)
+    h0 = np.random.default_rng(N + L + D).standard_normal((B, D, N)).astype(np.float32)
+    check_scan(m, c, h0=h0, what="single pass")
+    if L == 100:
+        check_scan(m, c, what="single pass, zero state, no gate", z=None)
+        check_scan(m, c, h0=h0, what="single pass, no skip, no bias", Dskip=None, dt_bias=None)
+        c3 = dict(c)
+        c3["dt"] = synth.to_io(np.abs(synth.io_values(c["dt"], io)) + 0.01, io)
+        check_scan(m, c3, h0=h0, dt_softplus=False, dt_bias=None, what="single pass, delta given directly")
+        # the same inputs cut in time take the two-pass kernels: same result within the tolerance of each
+        o1, h1 = run_scan(m, c, h0=h0)
+        o2, h2 = run_scan(m, c, h0=h0, chunk_len=16)
+        assert_close(values(o1), values(o2), 2 * TOL[io], "single pass vs chunked out")
+        assert_close(h1, h2, 2 * TOL[io], "single pass vs chunked state")
+        # in-place state
+        d = dev_case(c)
+        st = to_dev(h0).clone()
+        m.mamba_scan_fwd(d["x"], d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"], d["dt_bias"], h0=st, h_final=st)
+        assert np.array_equal(to_host(st), h1)
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
 def test_scan_optional_arguments(m, io):
     c = synth.prefill_case(2, 200, 128, 16, 4, io, seed=42)
     h0 = np.random.default_rng(3).standard_normal((2, 128, 16)).astype(np.float32)
