@@ -141,7 +141,7 @@ int scan_checked(const void *x, const void *dt, const float *A, const void *Bm, 
     }
     ScanArgs a{x, dt, Bm, Cm, z, A, Dskip, dt_bias, h0, out, h_final, ws,
                batch, L, D, (int)N, (int)io, dt_softplus, cl, nc};
-    a.direct = chunk_len == 0 && L > 0 && scan_direct_applies(batch, L, D, N);
+    a.single_pass = (chunk_len == 0 && L > 0) ? scan_kernel_choice(batch, L, D, N) : kScanChunked;
     return (int)launch_scan(a, static_cast<hipStream_t>(hip_stream));
 }
 

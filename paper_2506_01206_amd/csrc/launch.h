@@ -34,11 +34,17 @@ struct ScanArgs {
     int64_t batch, L, D;
     int N, io, dt_softplus;
     int64_t chunk_len, n_chunks;
-    int direct = 0;  // 1: the single-pass kernel of scan_direct.hip (n_chunks == 1, no workspace)
+    int single_pass = 0;  // kScanDirect / kScanLanes: one of the single-pass kernels (n_chunks == 1, no workspace)
 };
-// Whether the library's own choice (chunk_len = 0) for this shape is the single-pass kernel.
+constexpr int kScanChunked = 0, kScanDirect = 1, kScanLanes = 2;
+// The library's own choice (chunk_len = 0) of kernel for a shape: channels across lanes (scan_direct.hip) when
+// there are many independent channels, time across lanes (scan_lanes.hip) for one or a few sequences of a
+// narrow layer, else time chunks across workgroups (scan.hip).
+int scan_kernel_choice(int64_t batch, int64_t L, int64_t D, int64_t N);
 bool scan_direct_applies(int64_t batch, int64_t L, int64_t D, int64_t N);
+bool scan_lanes_applies(int64_t batch, int64_t L, int64_t D, int64_t N);
 hipError_t launch_scan_direct(const ScanArgs &a, hipStream_t stream);
+hipError_t launch_scan_lanes(const ScanArgs &a, hipStream_t stream);
 // Chunking chosen for a shape when the caller passes chunk_len = 0 (pure function of the shape).
 void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len_req,
                int64_t *chunk_len, int64_t *n_chunks);

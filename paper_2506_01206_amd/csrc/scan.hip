@@ -705,8 +705,8 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
     int64_t cl;
     if (chunk_len_req > 0) {
         cl = chunk_len_req;
-    } else if (scan_direct_applies(batch, L, D, N)) {
-        cl = L;  // enough independent channels: one pass, no chunks
+    } else if (scan_kernel_choice(batch, L, D, N) != kScanChunked) {
+        cl = L;  // one of the single-pass kernels: no chunks
     } else {
         const int64_t cpl = scan_channels_per_lane(batch, L, D);
         const int64_t columns = batch * ((D + kWave * cpl - 1) / (kWave * cpl));
@@ -727,6 +727,13 @@ void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len
     if (chunk_len_req <= 0 && (L + cl - 1) / cl > 65535) cl = ((L + 65534) / 65535 + kTile - 1) / kTile * kTile;
     *chunk_len = cl;
     *n_chunks = (L + cl - 1) / cl;
+}
+
+int scan_kernel_choice(int64_t batch, int64_t L, int64_t D, int64_t N)
+{
+    if (scan_direct_applies(batch, L, D, N)) return kScanDirect;
+    if (scan_lanes_applies(batch, L, D, N)) return kScanLanes;
+    return kScanChunked;
 }
 
 size_t scan_workspace_bytes(int64_t batch, int64_t D, int64_t N, int64_t n_chunks)
@@ -770,7 +777,8 @@ hipError_t launch_scan(const ScanArgs &a, hipStream_t stream)
         }
         return hipSuccess;
     }
-    if (a.direct) return launch_scan_direct(a, stream);
+    if (a.single_pass == kScanDirect) return launch_scan_direct(a, stream);
+    if (a.single_pass == kScanLanes) return launch_scan_lanes(a, stream);
     if (a.io == kIoBf16) return launch_scan_io<bf16_t>(a, stream);
     return launch_scan_io<float>(a, stream);
 }

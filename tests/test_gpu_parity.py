@@ -183,6 +183,49 @@ def test_scan_single_pass_shapes(m, io, N, B, L, D):
 
 
 @pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("B,L,D", [(1, 64, 576), (1, 513, 576), (2, 1000, 290), (1, 1030, 580), (3, 700, 198),
+                                   (1, 1537, 1536), (16, 100, 36)])
+def test_scan_time_across_lanes_shapes(m, io, B, L, D):
+    """One or a few sequences of a narrow layer with 16 states: the library scans time across the lanes of a
+    wavefront (super-steps of 512 tokens, no chunks, no workspace).  Ragged last super-step, several super-steps,
+    channel counts that leave the last workgroup 2 or 4 channels of its own, a nonzero incoming state."""
+    say(io=io, B=B, L=L, D=D)
+    N = 16
+    assert m.mamba_scan_workspace_bytes(B, L, D, N) == 0
+    c = synth.prefill_case(B, L, D, N, 4, io, seed=50000 + L + D, random_A=True)
+    h0 = np.random.default_rng(L + D).standard_normal((B, D, N)).astype(np.float32)
+    check_scan(m, c, h0=h0, what="lanes")
+    if L in (513, 1000):
+        check_scan(m, c, what="lanes, zero state, no gate", z=None)
+        check_scan(m, c, h0=h0, what="lanes, no skip, no bias", Dskip=None, dt_bias=None)
+        c3 = dict(c)
+        c3["dt"] = synth.to_io(np.abs(synth.io_values(c["dt"], io)) + 0.01, io)
+        check_scan(m, c3, h0=h0, dt_softplus=False, dt_bias=None, what="lanes, delta given directly")
+        c4 = dict(c)
+        c4["A"] = np.zeros_like(c["A"])
+        check_scan(m, c4, h0=h0, what="lanes, A = 0")
+        # the same inputs cut into time chunks take the two-pass kernels
+        o1, h1 = run_scan(m, c, h0=h0)
+        o2, h2 = run_scan(m, c, h0=h0, chunk_len=100)
+        assert_close(values(o1), values(o2), 2 * TOL[io], "lanes vs chunked out")
+        assert_close(h1, h2, 2 * TOL[io], "lanes vs chunked state")
+        # in-place state, and run-to-run determinism
+        d = dev_case(c)
+        st = to_dev(h0).clone()
+        o3, _ = m.mamba_scan_fwd(d["x"], d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"], d["dt_bias"], h0=st, h_final=st)
+        assert np.array_equal(to_host(st), h1) and np.array_equal(to_host(o3), o1)
+
+
+def test_scan_time_across_lanes_delta_to_zero_keeps_state(m):
+    # dt = -1e4 under softplus: every decay is exactly 1 and every input term 0, also through the scan over lanes
+    c = synth.prefill_case(1, 700, 576, 16, 4, synth.F32, seed=19)
+    c["dt"] = np.full_like(c["dt"], -1e4)
+    h0 = np.random.default_rng(2).standard_normal((1, 576, 16)).astype(np.float32)
+    _, hf = run_scan(m, c, h0=h0)
+    assert np.array_equal(hf, h0)
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
 def test_scan_optional_arguments(m, io):
     c = synth.prefill_case(2, 200, 128, 16, 4, io, seed=42)
     h0 = np.random.default_rng(3).standard_normal((2, 128, 16)).astype(np.float32)
