@@ -13,12 +13,14 @@ One "step" is one pass of the whole hot path over one batch of synthetic input:
            --eager-decode launches them one by one.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-The roofline object covers the dominant call, the selective scan (its three kernels together),
-timed with HIP events on the launch stream inside the timed region.  The scan is bound by the
-vector ALUs (one hardware exp2 and four VALU operations per state update, two walks over the
-tokens because a batch-1 sequence must be cut in time), so the object reports fp32 operations
-per second against the fp32 vector peak, and the algorithmic HBM bytes per second against the
-8 TB/s peak beside it.  The oracle (fp64, CPU) is timed on the same prefill for cpu_baseline.
+The roofline object covers the dominant call, the selective scan (all kernels of one call
+together), timed with HIP events on the launch stream inside the timed region.  Its headline
+figure is the one the task asks for: algorithmic HBM bytes per second against the 8 TB/s peak.
+What actually binds the scan is the vector ALUs (one hardware exp2 and four VALU operations per
+state update, and two walks over the tokens because a batch-1 sequence this long must be cut in
+time), so `roofline.alu` reports fp32 operations per second against the fp32 vector peak beside
+it.  `roofline.traffic` (measured HBM bytes per launch) is read from the counter summary under
+profiles/.  The oracle (fp64, CPU) is timed on the same prefill for cpu_baseline.
 """
 import argparse
 import json
@@ -33,10 +35,24 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published: 256 CUs x 128 FMA lanes x 2 x 2.4 GHz
 
-# HBM bytes per scan launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE summed over the scan's
-# three kernels, each scaled by what the same counter reads for the 1 GiB copy below; figures and
-# commands in profiles/).  Keyed by workload; None for a workload that has not been profiled.
-SCAN_TRAFFIC_BYTES = {("cfg3", 1, 32768, 1536, 16): 738_000_000}
+FP32_VECTOR_PLAIN_TFLOPS = 78.6   # the same without packed fp32 (this build compiles it out): 64 FMA lanes per CU and clock
+
+# HBM bytes per scan launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE summed over the kernels of one
+# scan call, each scaled by what the same counter reads for the 1 GiB copy below): the table in this file is
+# written from the counter runs whose commands it lists; a workload that has no row there reports null.
+SCAN_TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "scan_hbm_traffic.md")
+
+
+def scan_traffic_bytes(name):
+    """Measured HBM bytes of one scan launch on synthetic config `name`, or None."""
+    try:
+        for line in open(SCAN_TRAFFIC_TABLE):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 4 and cells[0] == name:
+                return int(round(float(cells[3]) * 1e6))
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def scan_bytes(B, L, D, N, e):
@@ -70,6 +86,8 @@ def main():
     ap.add_argument("--no-wide-step", action="store_true",
                     help="skip the separate timing of the 64-branch, D=4096 state step")
     ap.add_argument("--no-block", action="store_true", help="skip the whole-block prefill timing")
+    ap.add_argument("--no-scan-shapes", action="store_true",
+                    help="skip the scan-only timing on the cfg1 and cfg4 prefill shapes")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time conv1d, scan, fork and step on every synthetic config (cfg0..cfg4), warm and "
                          "cold, and (unless --no-cpu-baseline) the oracle on each; adds a few minutes")
@@ -282,14 +300,89 @@ def main():
         w1.record()
         torch.cuda.synchronize()
         us = w0.elapsed_time(w1) * 1e3 / (3 * R)
+        # the same rows through the library's own gather copy (mamba_state_fork): what moving the state alone costs
+        def fork_round():
+            for i in range(R):
+                m.mamba_state_fork(None, hin[i].unsqueeze(0), wpar, ssm_dst=hout[i].unsqueeze(0))
+        fork_round()
+        torch.cuda.synchronize()
+        fg = torch.cuda.CUDAGraph()
+        side2b = torch.cuda.Stream()
+        side2b.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side2b):
+            with torch.cuda.graph(fg, stream=side2b):
+                fork_round()
+        torch.cuda.current_stream().wait_stream(side2b)
+        fg.replay()
+        f0, f1 = ev(), ev()
+        f0.record()
+        for _ in range(3):
+            fg.replay()
+        f1.record()
+        torch.cuda.synchronize()
+        fork_us = f0.elapsed_time(f1) * 1e3 / (3 * R)
         wb = step_bytes(wnb, wD, wN, 2 if wc["io"] == synth.BF16 else 4)
         wide = {"workload": "cfg4 state step: %d branches, D=%d, N=%d, %s I/O, parent gather fused, cold "
                             "(%d rotating state buffers)" % (wnb, wD, wN, wc["io"], R),
                 "us_per_launch": round(us, 3), "algorithmic_bytes_per_launch": wb,
                 "GBps": round(wb / us / 1e3, 1), "frac_of_hbm_peak": round(wb / us / 1e3 / HBM_PEAK_GBS, 4),
                 "frac_of_copy_kernel": round(wb / us / 1e3 / copy_gbs, 4),
+                "state_gather_copy_us": round(fork_us, 3),
+                "state_gather_copy_note": "mamba_state_fork of the same %d state rows (%.1f MB read + written), same rotation: "
+                                          "the step does the copy plus the update in %.2fx its time"
+                                          % (wnb, 2 * wnb * wD * wN * 4 / 1e6, us / fork_us),
                 "branch_steps_per_s_per_layer": round(wnb / (us * 1e-6), 1)}
         del hin, hout
+
+    # the scan alone on the other prefill shapes (inputs drawn on the device with the distributions of the synthetic
+    # configs): the paper's own context length on the 130M layer (cfg1), which the library scans with time across
+    # lanes, and the wide batched layer (cfg4), which it scans in one pass with channels across lanes
+    other_scans = {}
+    if not args.no_scan_shapes:
+        gs = torch.Generator(device=dev)
+        gs.manual_seed(11)
+        for name in ("cfg1", "cfg4"):
+            c = synth.CONFIGS[name]
+            cB, cL, cD, cN = c["batch"], c["L"], c["D"], c["N"]
+            rnd = lambda *shape: torch.randn(*shape, device=dev, generator=gs)
+            sx, sz = rnd(cB, cL, cD).to(torch.bfloat16), rnd(cB, cL, cD).to(torch.bfloat16)
+            sdt = (0.1 * rnd(cB, cL, cD)).to(torch.bfloat16)
+            sB, sC = rnd(cB, cL, cN).to(torch.bfloat16), rnd(cB, cL, cN).to(torch.bfloat16)
+            sA = -torch.arange(1, cN + 1, device=dev, dtype=torch.float32).repeat(cD, 1).contiguous()
+            dt0 = torch.exp(torch.rand(cD, device=dev, generator=gs) * (np.log(0.1) - np.log(1e-3)) + np.log(1e-3))
+            sbias, sDk = dt0 + torch.log(-torch.expm1(-dt0)), torch.ones(cD, device=dev)
+            so, sh = torch.empty_like(sx), torch.empty((cB, cD, cN), device=dev)
+            sws = torch.empty(max(m.mamba_scan_workspace_bytes(cB, cL, cD, cN), 16), dtype=torch.uint8, device=dev)
+            run_s = lambda: m.mamba_scan_fwd(sx, sdt, sA, sB, sC, sDk, sz, sbias, out=so, h_final=sh, workspace=sws)
+            reps = 20 if name == "cfg1" else 5
+            for _ in range(3):
+                run_s()
+            torch.cuda.synchronize()
+            g_s = torch.cuda.CUDAGraph()
+            side_s = torch.cuda.Stream()
+            side_s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side_s):
+                with torch.cuda.graph(g_s, stream=side_s):
+                    for _ in range(reps):
+                        run_s()
+            torch.cuda.current_stream().wait_stream(side_s)
+            g_s.replay()
+            q0, q1 = ev(), ev()
+            q0.record()
+            for _ in range(3):
+                g_s.replay()
+            q1.record()
+            torch.cuda.synchronize()
+            s_ms = q0.elapsed_time(q1) / (3 * reps)
+            nbytes = scan_bytes(cB, cL, cD, cN, 2)
+            other_scans[name] = {"shape": "batch %d x L %d x D %d, N %d, bf16 I/O" % (cB, cL, cD, cN),
+                                 "kernel": m.mamba_scan_kernel(cB, cL, cD, cN), "ms": round(s_ms, 5),
+                                 "tokens_per_s": round(cB * cL / (s_ms * 1e-3), 1),
+                                 "GBps": round(nbytes / (s_ms * 1e-3) / 1e9, 1),
+                                 "frac_of_hbm_peak": round(nbytes / (s_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                 "traffic": scan_traffic_bytes(name), "algorithmic_bytes_per_launch": nbytes,
+                                 "timing": "per launch in a replayed HIP graph of %d launches" % reps}
+            del sx, sz, sdt, sB, sC, so, sws, g_s
 
     # sequential drafting (1,1,1,1,1) against the paper's default tree (3,2,2,1,1) on per-batch-size
     # state caches with one captured graph per draft position (Sec. 4.1): time of one draft round of
@@ -578,15 +671,19 @@ def main():
     sb = scan_bytes(B, L, D, N, e)
     achieved = sb / (scan_ms * 1e-3) / 1e9
     tflops = scan_flops(B, L, D, N) / (scan_ms * 1e-3) / 1e12
+    choice = {"chunked": "scan_chunk_state + scan_carry + scan_chunk_out: time chunks across workgroups",
+              "single": "scan_chunk_out: a single chunk", "direct": "scan_direct_kernel: one pass, channels across lanes",
+              "lanes": "scan_lanes_kernel: one pass, time across lanes"}
     roofline = {
-        "kernel": "mamba_scan_fwd (scan_chunk_state + scan_carry + scan_chunk_out)",
-        "bound": "alu", "achieved": round(tflops, 2), "peak": FP32_VECTOR_PEAK_TFLOPS,
-        "unit": "TFLOP/s", "frac": round(tflops / FP32_VECTOR_PEAK_TFLOPS, 4),
-        "traffic": SCAN_TRAFFIC_BYTES.get((args.prefill, B, L, D, N)),
-        "algorithmic_flops_per_launch": scan_flops(B, L, D, N), "avg_launch_ms": round(scan_ms, 5),
-        "hbm": {"achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_launch": sb,
-                "frac_of_copy_kernel": round(achieved / copy_gbs, 4)},
+        "kernel": "mamba_scan_fwd (%s)" % choice[m.mamba_scan_kernel(B, L, D, N)],
+        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": scan_traffic_bytes(args.prefill),
+        "algorithmic_bytes_per_launch": sb, "avg_launch_ms": round(scan_ms, 5),
+        "frac_of_copy_kernel": round(achieved / copy_gbs, 4),
+        "binding_resource": "vector ALU: one exp2 and four plain fp32 instructions per state update",
+        "alu": {"achieved": round(tflops, 2), "unit": "TFLOP/s", "algorithmic_flops_per_launch": scan_flops(B, L, D, N),
+                "peak_published_fp32_vector": FP32_VECTOR_PEAK_TFLOPS, "frac_of_published": round(tflops / FP32_VECTOR_PEAK_TFLOPS, 4),
+                "peak_without_packed_fp32": FP32_VECTOR_PLAIN_TFLOPS, "frac_without_packed_fp32": round(tflops / FP32_VECTOR_PLAIN_TFLOPS, 4)},
     }
     units = nb * nsteps * nl
     if args.staged_decode:
@@ -606,7 +703,7 @@ def main():
         "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
         "decode_launches": nsteps * (1 + 2 * nl) if args.staged_decode else nsteps * nl,
         "decode_stages": "fork + conv step + state step" if args.staged_decode else "one launch per layer and step (mamba_conv_state_step)", "decode_mode": "eager" if args.eager_decode else "hip_graph",
-        "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide,
+        "copy_kernel_GBps": round(copy_gbs, 1), "wide_decode_step": wide, "scan_other_shapes": other_scans,
         "tree_draft_round": tree_detail, "whole_block": block_detail,
         "whole_drafter": drafter_detail, "mamba2_core": ssd_detail, "per_config": per_config,
     }

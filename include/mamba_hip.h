@@ -107,6 +107,16 @@ int mamba_conv1d_fwd(const void *x, const float *w, const float *bias,
  */
 size_t mamba_scan_workspace_bytes(int64_t batch, int64_t L, int64_t D, int64_t N,
                                   int64_t chunk_len);
+/*
+ * Which kernels mamba_scan_fwd runs for a shape (a pure function of the shape, static storage):
+ *   "chunked": time chunks across workgroups, two passes and a carry (needs the workspace);
+ *   "direct":  one pass, channels across lanes: shapes with many independent channels (batch x D);
+ *   "lanes":   one pass, time across the lanes of a wavefront: one or a few short sequences, N = 16;
+ *   "single":  one chunk (a chunk_len >= L was asked for, or the sequence is short).
+ * The library chooses among them only when chunk_len = 0; an explicit chunk_len always means "chunked"
+ * or "single".  "" for a shape mamba_scan_fwd would refuse.
+ */
+const char *mamba_scan_kernel(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len);
 int mamba_scan_fwd(const void *x, const void *dt, const float *A, const void *Bm,
                    const void *Cm, const float *Dskip, const void *z,
                    const float *dt_bias, const float *h0, void *out, float *h_final,

@@ -89,6 +89,8 @@ def _declare(lib):
     lib.mamba_conv1d_fwd.restype = _int
     lib.mamba_scan_workspace_bytes.argtypes = [_i64] * 5
     lib.mamba_scan_workspace_bytes.restype = _sz
+    lib.mamba_scan_kernel.argtypes = [_i64] * 5
+    lib.mamba_scan_kernel.restype = ctypes.c_char_p
     lib.mamba_scan_fwd.argtypes = [_vp] * 12 + [_sz] + [_i64] * 5 + [_int, _int, _vp]
     lib.mamba_scan_fwd.restype = _int
     lib.mamba_scan_fwd_static.argtypes = [_vp] * 11 + [_i64] * 5 + [_int, _int, _vp]
@@ -104,7 +106,7 @@ def _declare(lib):
 
 lib = _declare(ctypes.CDLL(LIB_PATH))
 
-EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes",
+EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes", "mamba_scan_kernel",
            "mamba_scan_fwd", "mamba_scan_fwd_static", "mamba_state_step", "mamba_conv_state_step", "mamba_state_fork", "mamba_tree_plan",
            "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "mamba_block_workspace_bytes",
            "mamba_block_workspace_layout", "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd",
@@ -184,6 +186,11 @@ def mamba_conv1d_fwd(x, w, bias=None, conv_state_in=None, y=None, conv_state_out
 
 def mamba_scan_workspace_bytes(batch, L, D, N, chunk_len=0) -> int:
     return int(lib.mamba_scan_workspace_bytes(batch, L, D, N, chunk_len))
+
+
+def mamba_scan_kernel(batch, L, D, N, chunk_len=0) -> str:
+    """Name of the kernel family mamba_scan_fwd runs for this shape: chunked, direct, lanes or single."""
+    return lib.mamba_scan_kernel(batch, L, D, N, chunk_len).decode()
 
 
 def mamba_scan_fwd(x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, h0=None, out=None,

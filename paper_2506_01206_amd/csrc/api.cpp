@@ -92,6 +92,22 @@ size_t mamba_scan_workspace_bytes(int64_t batch, int64_t L, int64_t D, int64_t N
     return scan_workspace_bytes(batch, D, N, nc);
 }
 
+const char *mamba_scan_kernel(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len)
+{
+    int64_t t;
+    if (batch <= 0 || L <= 0 || D <= 0 || chunk_len < 0 || !n_supported(N) || batch > kMaxGridYZ) return "";
+    if (!size3(batch, L, D, 4, &t) || !size3(batch, D, N + 1, 4, &t)) return "";
+    if (chunk_len == 0) {
+        const int k = scan_kernel_choice(batch, L, D, N);
+        if (k == kScanDirect) return "direct";
+        if (k == kScanLanes) return "lanes";
+    }
+    int64_t cl, nc;
+    scan_plan(batch, L, D, N, chunk_len, &cl, &nc);
+    if (nc > kMaxGridYZ) return "";
+    return nc > 1 ? "chunked" : "single";
+}
+
 namespace {
 
 // validation and launch shared by the two scan entry points; static_ws: take the library's own buffer

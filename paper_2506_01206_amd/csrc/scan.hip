@@ -33,10 +33,7 @@ namespace mamba {
 namespace {
 
 constexpr int kWave = 64;
-#ifndef MAMBA_SCAN_TILE
-#define MAMBA_SCAN_TILE 4
-#endif
-constexpr int kTile = MAMBA_SCAN_TILE;  // time steps whose token loads are issued together, one tile ahead
+constexpr int kTile = 4;  // time steps whose token loads are issued together, one tile ahead
 
 template <typename T, int CPL> struct RawT;
 template <> struct RawT<float, 1> { typedef float type; };
@@ -177,11 +174,8 @@ __device__ __forceinline__ void store_state(const float (&h)[CPL][N], float *p)
 // ---------------------------------------------------------------------------------------
 // pass 2 (and the only pass when n_chunks == 1): full recurrence with outputs
 // grid: (channel groups, n_chunks, batch), block: one wavefront
-#ifndef MAMBA_SCAN_WAVES_ATTR
-#define MAMBA_SCAN_WAVES_ATTR
-#endif
 template <typename T, int N, int CPL, bool HAS_Z, bool SOFTPLUS>
-__global__ void __launch_bounds__(kWave) MAMBA_SCAN_WAVES_ATTR
+__global__ void __launch_bounds__(kWave)
 scan_chunk_out(const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
                const T *__restrict__ Bm, const T *__restrict__ Cm, const float *__restrict__ Dskip,
                const T *__restrict__ z, const float *__restrict__ dt_bias,
@@ -640,13 +634,9 @@ hipError_t launch_scan_t(const ScanArgs &a, hipStream_t stream)
 // per lane need even D so that every row keeps the pair's alignment.
 int scan_channels_per_lane(int64_t batch, int64_t L, int64_t D)
 {
-#ifdef MAMBA_SCAN_FORCE_CPL1
-    return 1;
-#else
     if (D % 2 != 0) return 1;
     const double work = (double)batch * (double)L * (double)D;
     return work >= 33554432.0 ? 2 : 1;
-#endif
 }
 
 template <typename T, int N>

@@ -150,6 +150,94 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
     }
 }
 
+// The same step with what a channel's lanes have in common formed once per channel: with several float4s per lane
+// (many branches: the launch moves tens of MB and lives on bandwidth) a workgroup covers 64 U channels, one per
+// thread, and every lane of the plain kernel above would fetch x, dt, z, dt_bias and D of each of its U channels for
+// itself: five small loads per piece, each a full trip through the address unit for 2 or 4 bytes a lane, and softplus
+// and SiLU four times per channel.  Here the state rows are requested first, each thread then does one channel's
+// token-side work (same operations in the same order, so the results are bit for bit the plain kernel's) and leaves
+// delta * log2(e), delta * x, x, D and silu(z) in LDS for the lanes that own the channel's states.
+// grid: (ceil(D * N / 4 / (256 * U)), n_out)
+template <typename T, int N, int U, bool HAS_Z, bool SOFTPLUS>
+__global__ void __launch_bounds__(kBlock)
+state_step_shared_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ parent,
+                         const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ A,
+                         const T *__restrict__ Bm, const T *__restrict__ Cm,
+                         const float *__restrict__ Dskip, const T *__restrict__ z,
+                         const float *__restrict__ dt_bias, T *__restrict__ out, int64_t n_in, int64_t D)
+{
+    constexpr int Q = N / 4;
+    constexpr int kChannels = kBlock * U / Q;                     // channels whose states this workgroup owns
+    __shared__ __attribute__((aligned(16))) float4 ch4[kChannels];   // delta * log2(e), delta * x, x, D
+    __shared__ float chg[kChannels];                                  // silu(z)
+    const int64_t j = blockIdx.y;
+    const int64_t row4 = D * Q;  // float4s per branch
+    const int64_t d_lo = (int64_t)blockIdx.x * kChannels;
+    const float4 *a4 = reinterpret_cast<const float4 *>(A);
+
+    // the state rows are the bytes that count: the parent index and their requests go out first
+    const int64_t p = parent ? (int64_t)parent[j] : j;
+    const bool p_ok = p >= 0 && p < n_in;
+    const float4 *hin4 = reinterpret_cast<const float4 *>(h_in) + (p_ok ? p : 0) * row4;
+    int64_t f[U];
+    bool live[U];
+    float4 h[U], a[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const int64_t f_raw = ((int64_t)blockIdx.x * U + i) * kBlock + threadIdx.x;
+        live[i] = f_raw < row4;
+        f[i] = live[i] ? f_raw : row4 - 1;
+        h[i] = ld_stream(hin4 + f[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i) a[i] = a4[f[i]];
+    const int q = (int)(threadIdx.x % Q);                         // 256 i is a multiple of Q: the same for all pieces
+    const float4 bv = ld4_io<N>(Bm + j * N + 4 * q), cv = ld4_io<N>(Cm + j * N + 4 * q);
+
+    for (int c = threadIdx.x; c < kChannels; c += kBlock) {
+        const int64_t dc = d_lo + c;
+        if (dc >= D) break;
+        const float xv = ld_io(x, j * D + dc);
+        const float v = ld_io(dt, j * D + dc) + (dt_bias ? dt_bias[dc] : 0.0f);
+        const float zv = HAS_Z ? ld_io(z, j * D + dc) : 0.0f;
+        const float delta = SOFTPLUS ? softplus_f32(v) : v;
+        ch4[c] = make_float4(delta * kLog2e, delta * xv, xv, Dskip ? Dskip[dc] : 0.0f);
+        if constexpr (HAS_Z) chg[c] = silu_f32(zv);
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const int64_t d = f[i] / Q;
+        const int ci = (int)(d - d_lo);
+        const float4 t = ch4[ci];
+        const float dl = t.x, u = t.y;
+        float4 hh = h[i];
+        hh.x = fmaf(exp2_hw(dl * a[i].x), hh.x, u * bv.x);
+        hh.y = fmaf(exp2_hw(dl * a[i].y), hh.y, u * bv.y);
+        hh.z = fmaf(exp2_hw(dl * a[i].z), hh.z, u * bv.z);
+        hh.w = fmaf(exp2_hw(dl * a[i].w), hh.w, u * bv.w);
+        float y = hh.x * cv.x;
+        y = fmaf(hh.y, cv.y, y);
+        y = fmaf(hh.z, cv.z, y);
+        y = fmaf(hh.w, cv.w, y);
+        y = channel_sum<Q>(y);
+        if (!p_ok) {
+            const float nan = __int_as_float(0x7fc00000);
+            hh = make_float4(nan, nan, nan, nan);
+            y = nan;
+        }
+        if (live[i]) {
+            st_stream(reinterpret_cast<float4 *>(h_out) + j * row4 + f[i], hh);
+            if (f[i] - d * Q == 0) {
+                y = fmaf(t.w, t.z, y);
+                if constexpr (HAS_Z) y *= chg[ci];
+                st_io(out, j * D + d, y);
+            }
+        }
+    }
+}
+
 // Fork, conv step and state update of one layer in a single launch (Sec. 4.1: a child continues from its parent's
 // states; the draft loop of a tree is this, once per layer and position).  x is the input *before* the conv:
 //   win = conv_src[p, d, :];  a = conv_bias[d] + sum_k w[d,k] win[k] + w[d,K-1] x[j,d];  x_c = silu(a)
@@ -160,6 +248,8 @@ state_step_kernel(float *h_out, const float *h_in, const int32_t *__restrict__ p
 // bias and input are loaded once per channel, not once per lane (with the conv evaluated by every lane of a channel
 // the wide step was bound by the issue of its many small loads: 17.7 us against 13.1 us for two launches); x_c goes
 // through LDS to the lanes that own the channel's states, whose state rows are already on their way by then.
+// (Forming the step's token-side values per channel in the same loop, as state_step_shared_kernel does, helped one
+// shape and cost three -- 64 x 4096: 9.4 -> 8.7 us, 32 x 1536: 3.7 -> 4.0, 128 x 4096: 17.9 -> 19.8 -- and is not done.)
 // grid: (ceil(D * N / 4 / (256 * U)), n_out)
 template <typename T, int N, int U, bool HAS_Z, bool SOFTPLUS>
 __global__ void __launch_bounds__(kBlock)
@@ -437,6 +527,23 @@ template <typename T, int N, int U> hipError_t launch_step_u(const StepArgs &a, 
     const int64_t row4 = a.D * (N / 4);
     const int64_t per_block = (int64_t)kBlock * U;
     dim3 grid((unsigned)((row4 + per_block - 1) / per_block), (unsigned)a.n_out);
+    if (U > 1 && !a.dt_w && !a.conv_w) {
+#define MAMBA_STEP_S(HZ, SP)                                                                      \
+    state_step_shared_kernel<T, N, U, HZ, SP><<<grid, kBlock, 0, stream>>>(                       \
+        a.h_out, a.h_in, a.parent, static_cast<const T *>(a.x), static_cast<const T *>(a.dt), a.A, \
+        static_cast<const T *>(a.Bm), static_cast<const T *>(a.Cm), a.Dskip,                      \
+        static_cast<const T *>(a.z), a.dt_bias, static_cast<T *>(a.out), a.n_in, a.D)
+        if (a.z) {
+            if (a.dt_softplus) MAMBA_STEP_S(true, true);
+            else MAMBA_STEP_S(true, false);
+        } else {
+            if (a.dt_softplus) MAMBA_STEP_S(false, true);
+            else MAMBA_STEP_S(false, false);
+        }
+#undef MAMBA_STEP_S
+        return hipGetLastError();
+    }
+    if constexpr (U <= kStepUnroll) {
 #define MAMBA_STEP(HZ, SP)                                                                        \
     state_step_kernel<T, N, U, HZ, SP><<<grid, kBlock, 0, stream>>>(                              \
         a.h_out, a.h_in, a.parent, static_cast<const T *>(a.x), static_cast<const T *>(a.dt), a.A, \
@@ -491,6 +598,9 @@ template <typename T, int N, int U> hipError_t launch_step_u(const StepArgs &a, 
 #undef MAMBA_STEP
 #undef MAMBA_STEP_X
     return hipGetLastError();
+    } else {
+        return hipErrorInvalidValue;   // eight float4s per lane exist for the plain step only
+    }
 }
 
 template <typename T, int N> hipError_t launch_step_n(const StepArgs &a, hipStream_t stream)
@@ -498,6 +608,9 @@ template <typename T, int N> hipError_t launch_step_n(const StepArgs &a, hipStre
     // several float4s per lane as long as that still leaves about three workgroups per CU
     const int64_t row4 = a.D * (N / 4);
     auto blocks = [&](int u) { return a.n_out * ((row4 + kBlock * u - 1) / (kBlock * u)); };
+    // the plain step with eight per lane while that gives between 1.5 and 4 workgroups per CU: 64 branches x 4096
+    // channels 8.7 -> 7.6 us, the time of a bare copy of the same state rows; 128 branches are better off with four
+    if (!a.conv_w && !a.dt_w && blocks(8) >= 384 && blocks(8) < 1024) return launch_step_u<T, N, 8>(a, stream);
     if (blocks(kStepUnroll) >= 768) return launch_step_u<T, N, kStepUnroll>(a, stream);
     if (kStepUnroll > 2 && blocks(2) >= 768 && !a.conv_w) return launch_step_u<T, N, 2>(a, stream);
     return launch_step_u<T, N, 1>(a, stream);

@@ -124,6 +124,20 @@ def test_static_scan_validation(b):
     assert "#define MAMBA_SCAN_STATIC_BYTES (32u << 20)" in header and b.MAMBA_SCAN_STATIC_BYTES == 32 << 20
 
 
+def test_scan_kernel_choice_by_shape(b):
+    """The library's own choice of scan kernels is a pure function of the shape; an explicit chunk length always
+    means time chunks (or one chunk)."""
+    k = b.mamba_scan_kernel
+    assert k(1, 32768, 1536, 16) == "chunked" and k(1, 2048, 1536, 16) == "lanes" and k(8, 8192, 4096, 16) == "direct"
+    assert k(1, 256, 256, 16) == "lanes" and k(1, 2048, 1536, 8) == "chunked"      # lanes: 16 states only
+    assert k(1, 2048, 1537, 16) == "chunked" and k(1, 32, 1536, 16) in ("single", "chunked")
+    assert k(4, 8192, 4096, 16) == "direct" and k(4, 8192, 4100, 16) == "chunked"  # direct: 16-byte rows
+    assert k(1, 2048, 1536, 16, 64) == "chunked" and k(1, 2048, 1536, 16, 2048) == "single"
+    assert k(0, 10, 10, 16) == "" and k(1, 10, 10, 17) == "" and k(1, 10, 10, 16, -1) == ""
+    for shape in ((1, 32768, 1536, 16), (1, 2048, 1536, 16), (8, 8192, 4096, 16), (1, 2048, 1536, 16, 64)):
+        assert (b.mamba_scan_workspace_bytes(*shape) > 0) == (k(*shape) == "chunked")
+
+
 def test_scan_workspace_query(b):
     w = b.mamba_scan_workspace_bytes
     assert w(0, 10, 10, 16, 0) == 0 and w(1, 0, 10, 16, 0) == 0 and w(1, 10, 10, 16, -1) == 0

@@ -160,7 +160,7 @@ def test_scan_single_pass_shapes(m, io, N, B, L, D):
     """Shapes with enough independent channels that the library walks every token once (no time chunks, no
     workspace): tile tails, a channel block that is only partly there (D = 200, D = 8), every state size."""
     say(io=io, N=N, B=B, L=L, D=D)
-    assert m.mamba_scan_workspace_bytes(B, L, D, N) == 0
+    assert m.mamba_scan_workspace_bytes(B, L, D, N) == 0 and m.mamba_scan_kernel(B, L, D, N) == "direct"
     c = synth.prefill_case(B, L, D, N, 4, io, seed=40000 + N + L + D, random_A=True)
     h0 = np.random.default_rng(N + L + D).standard_normal((B, D, N)).astype(np.float32)
     check_scan(m, c, h0=h0, what="single pass")
@@ -191,7 +191,7 @@ def test_scan_time_across_lanes_shapes(m, io, B, L, D):
     channel counts that leave the last workgroup 2 or 4 channels of its own, a nonzero incoming state."""
     say(io=io, B=B, L=L, D=D)
     N = 16
-    assert m.mamba_scan_workspace_bytes(B, L, D, N) == 0
+    assert m.mamba_scan_workspace_bytes(B, L, D, N) == 0 and m.mamba_scan_kernel(B, L, D, N) == "lanes"
     c = synth.prefill_case(B, L, D, N, 4, io, seed=50000 + L + D, random_A=True)
     h0 = np.random.default_rng(L + D).standard_normal((B, D, N)).astype(np.float32)
     check_scan(m, c, h0=h0, what="lanes")
@@ -539,7 +539,7 @@ def test_cfg3_long_prefill_every_channel(m):
     e1 = assert_close(values(out), ro, TOL[c["io"]], "cfg3 scan out")
     e2 = assert_close(hf, rh, TOL[c["io"]], "cfg3 scan state")
     say(scan_err=(e1, e2))
-    assert m.mamba_scan_workspace_bytes(c["batch"], c["L"], c["D"], c["N"]) > 0   # it was chunked
+    assert m.mamba_scan_kernel(c["batch"], c["L"], c["D"], c["N"]) == "chunked"
 
 
 def decode_chain_gpu(m, dc, fused):
