@@ -97,10 +97,15 @@ int mamba_conv1d_fwd(const void *x, const float *w, const float *bias,
  *   out_t[d] = y_t[d] * silu(z_t[d])            (no gate when z is NULL)
  *   h_{-1} = h0 (zeros when NULL);  h_final = h_{L-1}.
  * Nullable: Dskip (no skip term), z, dt_bias (zero), h0, h_final (not written).
- * Long sequences are cut into time chunks of `chunk_len` tokens that run in
- * parallel, with the chunk-boundary state carried through `workspace`; the
- * result does not depend on the chunking beyond float32 rounding order.
- * chunk_len = 0 lets the library choose; chunk_len >= L means one chunk.
+ * Time has to run in parallel somewhere when batch x D channels do not fill the
+ * chip.  With chunk_len > 0 the sequence is cut into time chunks of that many
+ * tokens that run in parallel across workgroups, the chunk-boundary states
+ * carried through `workspace`; chunk_len >= L means one chunk.  chunk_len = 0
+ * lets the library choose by shape: such chunks, or one of two single-pass
+ * kernels that need no workspace (channels across lanes when batch x D is large,
+ * time across the lanes of a wavefront for one or a few short sequences); see
+ * mamba_scan_kernel.  The result does not depend on the choice beyond float32
+ * rounding order, and is bitwise reproducible from run to run.
  * mamba_scan_workspace_bytes gives the bytes needed for the same
  * (batch, L, D, N, chunk_len); workspace may be NULL when that is 0.
  * h_final may alias h0.  out must not overlap any input.
