@@ -45,6 +45,7 @@ constexpr int kThreadsL = 64 * kWaves;   // 768
 constexpr int kTau = 8;                  // tokens per lane and super-step
 constexpr int kT = 64 * kTau;            // tokens per super-step
 constexpr int kTokenThreads = kT;        // one token row per thread of the first 8 wavefronts
+constexpr int kBcPart = 66, kBcTau = kParts * kBcPart + 1;   // slots per state group and per token j of lds_B / lds_C
 
 __device__ __forceinline__ void lds_barrier_l()
 {
@@ -185,14 +186,16 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
                   const float *__restrict__ Dskip, const T *z, const float *__restrict__ dt_bias,
                   const float *h0 /* may alias h_final */, T *out, float *h_final, int64_t L, int64_t D)
 {
-    // [token j of the lane's block][state group][lane][4 states]: the lanes of a wavefront read consecutive slots
-    // (rows padded by one slot: the wavefronts that fill them write 8 different rows at a time)
-    __shared__ __attribute__((aligned(16))) float4 lds_B[kTau][kParts][65];
-    __shared__ __attribute__((aligned(16))) float4 lds_C[kTau][kParts][65];
+    // [token j of the lane's block][state group][lane][4 states]: the lanes of a wavefront read consecutive slots.
+    // The threads that fill them write, eight lanes at a time, four consecutive tokens (j) x two state groups two
+    // apart: with rows of 66 slots and 265 slots per j those eight 16-byte slots fall on eight different quarters
+    // of the banks (j * 265 + 2 * 66 * pos = j + 4 * pos mod 8).
+    __shared__ __attribute__((aligned(16))) float4 lds_B[kTau * kBcTau];
+    __shared__ __attribute__((aligned(16))) float4 lds_C[kTau * kBcTau];
     // [channel][half of the block][lane][4 tokens]
     __shared__ __attribute__((aligned(16))) float4 lds_d[kG][kTau / 4][64];   // delta
     __shared__ __attribute__((aligned(16))) float4 lds_u[kG][kTau / 4][64];   // delta * x
-    __shared__ float lds_y[kParts][kG][kTau][64];                              // C . h per token: one part per state group
+    __shared__ __attribute__((aligned(16))) float4 lds_y[kParts][kG][kTau / 4][64];   // C . h per token, same layout: one part per state group
     __shared__ float lds_par[2][kG];                                           // dt_bias, D of the workgroup's channels
 
     const int tid = threadIdx.x;
@@ -217,9 +220,11 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
     }
     const int64_t row0 = b * L;
 
-    // ---- token layout (threads of the first 8 wavefronts): token 8 * lane + wave of the super-step
+    // ---- token layout (threads of the first 8 wavefronts): thread t has token t of the super-step, which is token
+    // tj of the block of lane ti.  (A wavefront's 4-byte accesses to the [..][lane][4 tokens] arrays then cover all
+    // banks: 8 lanes x 4 positions.)
     const bool token_thread = tid < kTokenThreads;
-    const int tj = wave & (kTau - 1), ti = lane;
+    const int tj = tid & (kTau - 1), ti = (tid >> 3) & 63;
     if (tid < kG) {
         lds_par[0][tid] = dt_bias ? dt_bias[c0 + tid] : 0.0f;
         lds_par[1][tid] = Dskip ? Dskip[c0 + tid] : 0.0f;
@@ -263,19 +268,18 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
             }
         }
     };
-    auto publish_bc = [&](int64_t t_base, int first) {
-        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto publish_bc = [&](int first) {
 #pragma unroll
         for (int it = 0; it < kBcHeld; ++it) {
             const int q = tid + (first + it) * kThreadsL;
             if (kChunks % kThreadsL == 0 || q < kChunks) {
                 const int arr = q / (kT * kChunksPerRow), r = q % (kT * kChunksPerRow);
                 const int tok = r / kChunksPerRow, pos = r % kChunksPerRow;
-                const bool valid = t_base + tok < L;         // a token past the end must not touch the state
-                float4(*dst)[kParts][65] = arr ? lds_C : lds_B;
+                // (a token past the end re-reads the last row: its delta is zero, which alone keeps the state as it is)
+                float4 *dst = arr ? lds_C : lds_B;
 #pragma unroll
                 for (int g = 0; g < kChunkGroups; ++g)
-                    dst[tok & (kTau - 1)][pos * kChunkGroups + g][tok / kTau] = valid ? bc_nxt[it].group(g) : zero;
+                    dst[(tok & (kTau - 1)) * kBcTau + (pos * kChunkGroups + g) * kBcPart + tok / kTau] = bc_nxt[it].group(g);
             }
         }
     };
@@ -312,7 +316,8 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
 #pragma unroll
         for (int c = 0; c < kG; ++c) {
             // the four state groups in a fixed order: the result does not depend on which wavefront was first
-            const float ch = (lds_y[0][c][tj][ti] + lds_y[1][c][tj][ti]) + (lds_y[2][c][tj][ti] + lds_y[3][c][tj][ti]);
+            auto part_y = [&](int p) { return reinterpret_cast<const float *>(&lds_y[p][c][tj >> 2][ti])[tj & 3]; };
+            const float ch = (part_y(0) + part_y(1)) + (part_y(2) + part_y(3));
             const float y = fmaf(lds_par[1][c], xv[c], ch);
             ov[c] = HAS_Z ? y * silu_f32(zv[c]) : y;
         }
@@ -327,10 +332,10 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
     fetch_bc(0, 0);
     lds_barrier_l();   // the channel parameters are in LDS
     if (token_thread) publish(0);
-    publish_bc(0, 0);
+    publish_bc(0);
     if constexpr (kBcIters > kBcHeld) {
         fetch_bc(0, kBcHeld);
-        publish_bc(0, kBcHeld);
+        publish_bc(kBcHeld);
     }
     lds_barrier_l();
 
@@ -357,7 +362,7 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const int j = 4 * jh + jj;
-                const float4 b4 = lds_B[j][part][lane];
+                const float4 b4 = lds_B[j * kBcTau + part * kBcPart + lane];
                 const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
                 for (int ch = 0; ch < 2; ++ch) {
@@ -407,12 +412,13 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
         for (int jh = 0; jh < kTau / 4; ++jh) {
             __builtin_amdgcn_sched_barrier(0);
             float4 u4[2];
+            float yq[2][4];
 #pragma unroll
             for (int ch = 0; ch < 2; ++ch) u4[ch] = lds_u[ca + ch][jh][lane];
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const int j = 4 * jh + jj;
-                const float4 b4 = lds_B[j][part][lane], c4 = lds_C[j][part][lane];
+                const float4 b4 = lds_B[j * kBcTau + part * kBcPart + lane], c4 = lds_C[j * kBcTau + part * kBcPart + lane];
                 const float bv[4] = {b4.x, b4.y, b4.z, b4.w}, cv[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
                 for (int ch = 0; ch < 2; ++ch) {
@@ -423,9 +429,11 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
                         hin[ch][n] = fmaf(a[j][ch][n], hin[ch][n], u * bv[n]);
                         yp = fmaf(hin[ch][n], cv[n], yp);
                     }
-                    lds_y[part][ca + ch][j][lane] = yp;
+                    yq[ch][jj] = yp;
                 }
             }
+#pragma unroll
+            for (int ch = 0; ch < 2; ++ch) lds_y[part][ca + ch][jh][lane] = make_float4(yq[ch][0], yq[ch][1], yq[ch][2], yq[ch][3]);
         }
         lds_barrier_l();   // y of the super-step is complete; its operands are used up
 
@@ -437,10 +445,10 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
             if (more) publish(t_base + kT);
         }
         if (more) {
-            publish_bc(t_base + kT, 0);
+            publish_bc(0);
             if constexpr (kBcIters > kBcHeld) {
                 fetch_bc(t_base + kT, kBcHeld);
-                publish_bc(t_base + kT, kBcHeld);
+                publish_bc(kBcHeld);
             }
         }
         lds_barrier_l();   // the next super-step is in LDS
