@@ -225,9 +225,13 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
     // banks: 8 lanes x 4 positions.)
     const bool token_thread = tid < kTokenThreads;
     const int tj = tid & (kTau - 1), ti = (tid >> 3) & 63;
-    if (tid < kG) {
-        lds_par[0][tid] = dt_bias ? dt_bias[c0 + tid] : 0.0f;
-        lds_par[1][tid] = Dskip ? Dskip[c0 + tid] : 0.0f;
+    // dt_bias and D of the workgroup's channels: one load per thread, requested here and put into LDS only after the
+    // first rows have been requested as well (written where it is fetched, wavefront 0 would sit through two
+    // memory round trips before it asks for anything else, and the whole workgroup waits for it at the barrier)
+    float par = 0.0f;
+    if (tid < 2 * kG) {
+        const float *src = tid < kG ? dt_bias : Dskip;
+        if (src) par = src[c0 + (tid < kG ? tid : tid - kG)];
     }
 
     // ---- state layout: channels ca, ca + 1 of the workgroup, states 4 * part .. 4 * part + 3, tokens 8 * lane ..
@@ -330,6 +334,7 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
     const int64_t n_super = (L + kT - 1) / kT;
     if (token_thread) fetch(0);
     fetch_bc(0, 0);
+    if (tid < 2 * kG) (&lds_par[0][0])[tid] = par;
     lds_barrier_l();   // the channel parameters are in LDS
     if (token_thread) publish(0);
     publish_bc(0);
