@@ -149,6 +149,36 @@ int mamba_scan_fwd_static(const void *x, const void *dt, const float *A, const v
                           mamba_dtype_t io, void *hip_stream);
 
 /*
+ * The conv1d and the scan above for token tensors in another layout (the layer's equations, Sec. 3.1, do not
+ * fix one; a channel-major (batch, D, L) caller, or tensors that are column ranges of a wider row such as
+ * x | z side by side, are expressible this way).  A stride triple is a HOST array of three element counts
+ * {batch, token, channel}: element (b, t, d) lies at b * s[0] + t * s[1] + d * s[2] elements from the base;
+ * NULL means contiguous time-major, {L * D, D, 1}.  Strided tensors: x, y of the conv; x, dt, z, out of the
+ * scan.  Everything else (w, bias, the conv states, A, Bm, Cm, Dskip, dt_bias, h0, h_final) is laid out as in
+ * mamba_conv1d_fwd / mamba_scan_fwd.
+ * When every triple describes the contiguous layout and the strided tensors' bases are 16-byte aligned the call
+ * IS mamba_conv1d_fwd / mamba_scan_fwd (chunk_len 0; their aliasing and workspace rules, same kernels, same
+ * bits).  Otherwise a plain kernel runs:
+ * one lane per channel walking time, no workspace, not tuned (the tuned kernels need contiguous rows), results
+ * within the same tolerance.  Rules of that path: strides >= 0, and for an output (y, out) a layout in which
+ * different (b, t, d) never share an element (checked: sorted by stride, each stride covers the extent below
+ * it), else MAMBA_ERR_BAD_SHAPE; base pointers aligned to the element size, the rest to 16 bytes; the byte
+ * range an output spans must not overlap the range any input spans (MAMBA_ERR_ALIAS; ranges, not elements:
+ * interleaved views of one buffer are refused); conv_state_out must not be conv_state_in; L <= 65535 * 128
+ * for the conv.  workspace / workspace_bytes are only looked at on the contiguous path.
+ */
+int mamba_conv1d_fwd_strided(const void *x, const int64_t *x_strides, const float *w, const float *bias,
+                             const void *conv_state_in, void *y, const int64_t *y_strides,
+                             void *conv_state_out, int64_t batch, int64_t L, int64_t D, int K,
+                             int apply_silu, mamba_dtype_t io, void *hip_stream);
+int mamba_scan_fwd_strided(const void *x, const int64_t *x_strides, const void *dt, const int64_t *dt_strides,
+                           const float *A, const void *Bm, const void *Cm, const float *Dskip,
+                           const void *z, const int64_t *z_strides, const float *dt_bias, const float *h0,
+                           void *out, const int64_t *out_strides, float *h_final, void *workspace,
+                           size_t workspace_bytes, int64_t batch, int64_t L, int64_t D, int64_t N,
+                           int dt_softplus, mamba_dtype_t io, void *hip_stream);
+
+/*
  * One recurrence step for all n_out live branches of a draft tree at once
  * (Sec. 4.1: batch generation with batch size B_i at draft position i; a child
  * continues from its parent's state).  Same equations as the scan with L = 1:

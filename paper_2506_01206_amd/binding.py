@@ -95,6 +95,10 @@ def _declare(lib):
     lib.mamba_scan_fwd.restype = _int
     lib.mamba_scan_fwd_static.argtypes = [_vp] * 11 + [_i64] * 5 + [_int, _int, _vp]
     lib.mamba_scan_fwd_static.restype = _int
+    lib.mamba_conv1d_fwd_strided.argtypes = [_vp] * 8 + [_i64, _i64, _i64, _int, _int, _int, _vp]
+    lib.mamba_conv1d_fwd_strided.restype = _int
+    lib.mamba_scan_fwd_strided.argtypes = [_vp] * 16 + [_sz] + [_i64] * 4 + [_int, _int, _vp]
+    lib.mamba_scan_fwd_strided.restype = _int
     lib.mamba_state_step.argtypes = [_vp] * 12 + [_i64] * 4 + [_int, _int, _vp]
     lib.mamba_state_step.restype = _int
     lib.mamba_state_fork.argtypes = [_vp] * 5 + [_i64] * 5 + [_int, _int, _vp]
@@ -107,7 +111,7 @@ def _declare(lib):
 lib = _declare(ctypes.CDLL(LIB_PATH))
 
 EXPORTS = ("mamba_status_string", "mamba_conv1d_fwd", "mamba_scan_workspace_bytes", "mamba_scan_kernel",
-           "mamba_scan_fwd", "mamba_scan_fwd_static", "mamba_state_step", "mamba_conv_state_step", "mamba_state_fork", "mamba_tree_plan",
+           "mamba_scan_fwd", "mamba_scan_fwd_static", "mamba_conv1d_fwd_strided", "mamba_scan_fwd_strided", "mamba_state_step", "mamba_conv_state_step", "mamba_state_fork", "mamba_tree_plan",
            "mamba_tree_parents", "mamba_linear_fwd", "mamba_rmsnorm_fwd", "mamba_block_workspace_bytes",
            "mamba_block_workspace_layout", "mamba_block_fwd", "mamba_block_step", "mamba_embedding_fwd", "mamba_topk_fwd",
            "mamba2_ssd_workspace_bytes", "mamba2_ssd_fwd", "mamba2_state_step")
@@ -237,6 +241,68 @@ def mamba_scan_fwd_static(x, dt, A, Bm, Cm, Dskip, z, dt_bias, h0, out, h_final,
         _ptr(out, x.dtype, (B, L, D), "out"), _ptr(h_final, torch.float32, (B, D, N), "h_final"),
         B, L, D, N, int(chunk_len), int(bool(dt_softplus)), _io_code(x), _stream(stream))
     _check("mamba_scan_fwd_static", st)
+    return out, h_final
+
+
+def _view(t, dtype=None, shape=None, name="tensor"):
+    """(device pointer, host stride triple) of a CUDA tensor of logical shape (B, L, D) in any layout."""
+    if t is None:
+        return None, None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return (t.data_ptr() if t.numel() > 0 else None), (ctypes.c_int64 * 3)(*t.stride())
+
+
+def mamba_conv1d_fwd_strided(x, w, bias=None, conv_state_in=None, y=None, conv_state_out=None,
+                             apply_silu=True, want_state=True, stream=None):
+    """mamba_conv1d_fwd for x and y of logical shape (B,L,D) in any layout (a transposed (B,D,L) tensor, a column
+    range of a wider tensor): their strides go to the library as they are.  y defaults to a contiguous tensor."""
+    B, L, D = x.shape
+    K = w.shape[1]
+    if y is None:
+        y = torch.empty((B, L, D), dtype=x.dtype, device=x.device)
+    if conv_state_out is None and want_state:
+        conv_state_out = torch.empty((B, D, K - 1), dtype=x.dtype, device=x.device)
+    xp, xs = _view(x, name="x")
+    yp, ys = _view(y, x.dtype, (B, L, D), "y")
+    st = lib.mamba_conv1d_fwd_strided(
+        xp, xs, _ptr(w, torch.float32, (D, K), "w"), _ptr(bias, torch.float32, (D,), "bias"),
+        _ptr(conv_state_in, x.dtype, (B, D, K - 1), "conv_state_in"), yp, ys,
+        _ptr(conv_state_out, x.dtype, (B, D, K - 1), "conv_state_out"),
+        B, L, D, K, int(bool(apply_silu)), _io_code(x), _stream(stream))
+    _check("mamba_conv1d_fwd_strided", st)
+    return y, conv_state_out
+
+
+def mamba_scan_fwd_strided(x, dt, A, Bm, Cm, Dskip=None, z=None, dt_bias=None, h0=None, out=None,
+                           h_final=None, workspace=None, dt_softplus=True, want_state=True, stream=None):
+    """mamba_scan_fwd for x, dt, z, out of logical shape (B,L,D) in any layout, each with its own strides;
+    Bm, Cm (B,L,N) and the rest contiguous as there.  out defaults to a contiguous tensor."""
+    B, L, D = x.shape
+    N = A.shape[1]
+    if out is None:
+        out = torch.empty((B, L, D), dtype=x.dtype, device=x.device)
+    if h_final is None and want_state:
+        h_final = torch.empty((B, D, N), dtype=torch.float32, device=x.device)
+    need = mamba_scan_workspace_bytes(B, L, D, N, 0)     # only used when every layout is the contiguous one
+    if workspace is None and need > 0:
+        workspace = _scratch(need, x.device, stream)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    xp, xs = _view(x, name="x")
+    dp, ds = _view(dt, x.dtype, (B, L, D), "dt")
+    zp, zs = _view(z, x.dtype, (B, L, D), "z")
+    op, os_ = _view(out, x.dtype, (B, L, D), "out")
+    st = lib.mamba_scan_fwd_strided(
+        xp, xs, dp, ds, _ptr(A, torch.float32, (D, N), "A"), _ptr(Bm, x.dtype, (B, L, N), "Bm"),
+        _ptr(Cm, x.dtype, (B, L, N), "Cm"), _ptr(Dskip, torch.float32, (D,), "Dskip"), zp, zs,
+        _ptr(dt_bias, torch.float32, (D,), "dt_bias"), _ptr(h0, torch.float32, (B, D, N), "h0"), op, os_,
+        _ptr(h_final, torch.float32, (B, D, N), "h_final"), _ptr(workspace, name="workspace"), ws_bytes,
+        B, L, D, N, int(bool(dt_softplus)), _io_code(x), _stream(stream))
+    _check("mamba_scan_fwd_strided", st)
     return out, h_final
 
 

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmamba_hip.so")
-SOURCES = ["api.cpp", "sd_tree_search.cpp", "conv1d.hip", "scan.hip", "scan_direct.hip", "scan_lanes.hip", "step.hip", "fork.hip", "linear.hip", "norm.hip", "vocab.hip", "ssd.hip"]
+SOURCES = ["api.cpp", "sd_tree_search.cpp", "conv1d.hip", "scan.hip", "scan_direct.hip", "scan_lanes.hip", "strided.hip", "step.hip", "fork.hip", "linear.hip", "norm.hip", "vocab.hip", "ssd.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU instructions are switched off for every device function
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

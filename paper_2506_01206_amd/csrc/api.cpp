@@ -182,6 +182,131 @@ int mamba_scan_fwd_static(const void *x, const void *dt, const float *A, const v
                         batch, L, D, N, chunk_len, dt_softplus, io, hip_stream);
 }
 
+namespace {
+
+// A stride triple {batch, token, channel} resolved for a (batch, L, D) tensor of e-byte elements (all sizes >= 1).
+struct Layout {
+    int64_t s[3];
+    int64_t bytes;      // bytes from the base to the end of the last element
+    bool contiguous;    // time-major without gaps (strides of axes of length 1 do not matter)
+};
+
+bool resolve_layout(const int64_t *strides, int64_t batch, int64_t L, int64_t D, int e, Layout *o)
+{
+    const int64_t dims[3] = {batch, L, D};
+    int64_t ld;
+    if (!mul_ok(L, D, &ld)) return false;
+    const int64_t dense[3] = {ld, D, 1};
+    int64_t last = 0;
+    o->contiguous = true;
+    for (int i = 0; i < 3; ++i) {
+        o->s[i] = strides ? strides[i] : dense[i];
+        if (o->s[i] < 0) return false;
+        int64_t t;
+        if (!mul_ok(dims[i] - 1, o->s[i], &t) || __builtin_add_overflow(last, t, &last)) return false;
+        if (dims[i] > 1 && o->s[i] != dense[i]) o->contiguous = false;
+    }
+    if (__builtin_add_overflow(last, (int64_t)1, &last) || !mul_ok(last, e, &o->bytes)) return false;
+    return o->bytes <= (int64_t)1 << 62;
+}
+
+// no two (b, t, d) of an output may share an element.  Sufficient and easy to state: taken in order of
+// increasing stride, every axis steps past everything the axes before it can reach.
+bool injective(const Layout &l, int64_t batch, int64_t L, int64_t D)
+{
+    const int64_t dims[3] = {batch, L, D};
+    int order[3] = {0, 1, 2};
+    for (int i = 0; i < 3; ++i)
+        for (int j = i + 1; j < 3; ++j)
+            if (l.s[order[j]] < l.s[order[i]]) { const int t = order[i]; order[i] = order[j]; order[j] = t; }
+    int64_t reach = 0;   // largest offset the axes handled so far can produce (resolve_layout showed no overflow)
+    for (int i = 0; i < 3; ++i) {
+        const int a = order[i];
+        if (dims[a] == 1) continue;
+        if (l.s[a] <= reach) return false;
+        reach += (dims[a] - 1) * l.s[a];
+    }
+    return true;
+}
+
+bool aligned_to(const void *p, int e) { return (reinterpret_cast<uintptr_t>(p) & (uintptr_t)(e - 1)) == 0; }
+
+}  // namespace
+
+int mamba_conv1d_fwd_strided(const void *x, const int64_t *x_strides, const float *w, const float *bias,
+                             const void *conv_state_in, void *y, const int64_t *y_strides,
+                             void *conv_state_out, int64_t batch, int64_t L, int64_t D, int K,
+                             int apply_silu, mamba_dtype_t io, void *hip_stream)
+{
+    const int e = io_size(io);
+    if (e == 0 || !k_supported(K)) return MAMBA_ERR_UNSUPPORTED;
+    int64_t tok_bytes, st_bytes;
+    if (!size3(batch, L, D, e, &tok_bytes) || !size3(batch, D, K - 1, e, &st_bytes)) return MAMBA_ERR_BAD_SHAPE;
+    if (batch == 0 || D == 0 || L == 0)   // nothing strided to touch: the contiguous call's own rules
+        return mamba_conv1d_fwd(x, w, bias, conv_state_in, y, conv_state_out, batch, L, D, K, apply_silu, io, hip_stream);
+    Layout lx, ly;
+    if (!resolve_layout(x_strides, batch, L, D, e, &lx) || !resolve_layout(y_strides, batch, L, D, e, &ly))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (lx.contiguous && ly.contiguous && aligned16(x) && aligned16(y))
+        return mamba_conv1d_fwd(x, w, bias, conv_state_in, y, conv_state_out, batch, L, D, K, apply_silu, io, hip_stream);
+    if (!injective(ly, batch, L, D)) return MAMBA_ERR_BAD_SHAPE;
+    if (batch > kMaxGridYZ || (L + 127) / 128 > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    if (!w || !x || !y) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned_to(x, e) || !aligned_to(y, e) || !aligned16(w) || !aligned16(bias) || !aligned16(conv_state_in) ||
+        !aligned16(conv_state_out))
+        return MAMBA_ERR_MISALIGNED;
+    if (overlap(y, ly.bytes, x, lx.bytes) || overlap(y, ly.bytes, conv_state_in, st_bytes) ||
+        overlap(y, ly.bytes, conv_state_out, st_bytes) || overlap(x, lx.bytes, conv_state_out, st_bytes) ||
+        overlap(conv_state_in, st_bytes, conv_state_out, st_bytes))
+        return MAMBA_ERR_ALIAS;
+    ConvStridedArgs a{x, w, bias, conv_state_in, y, conv_state_out, batch, L, D, K, apply_silu, (int)io,
+                      {lx.s[0], lx.s[1], lx.s[2]}, {ly.s[0], ly.s[1], ly.s[2]}};
+    return (int)launch_conv1d_strided(a, static_cast<hipStream_t>(hip_stream));
+}
+
+int mamba_scan_fwd_strided(const void *x, const int64_t *x_strides, const void *dt, const int64_t *dt_strides,
+                           const float *A, const void *Bm, const void *Cm, const float *Dskip,
+                           const void *z, const int64_t *z_strides, const float *dt_bias, const float *h0,
+                           void *out, const int64_t *out_strides, float *h_final, void *workspace,
+                           size_t workspace_bytes, int64_t batch, int64_t L, int64_t D, int64_t N,
+                           int dt_softplus, mamba_dtype_t io, void *hip_stream)
+{
+    const int e = io_size(io);
+    if (e == 0) return MAMBA_ERR_UNSUPPORTED;
+    if (N < 0) return MAMBA_ERR_BAD_SHAPE;
+    int64_t tok_bytes, bc_bytes, st_bytes;
+    if (!size3(batch, L, D, e, &tok_bytes) || !size3(batch, L, N, e, &bc_bytes) || !size3(batch, D, N, 4, &st_bytes))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (batch == 0 || D == 0 || L == 0)
+        return mamba_scan_fwd(x, dt, A, Bm, Cm, Dskip, z, dt_bias, h0, out, h_final, workspace, workspace_bytes,
+                              batch, L, D, N, 0, dt_softplus, io, hip_stream);
+    Layout lx, ld, lz, lo;
+    if (!resolve_layout(x_strides, batch, L, D, e, &lx) || !resolve_layout(dt_strides, batch, L, D, e, &ld) ||
+        !resolve_layout(z_strides, batch, L, D, e, &lz) || !resolve_layout(out_strides, batch, L, D, e, &lo))
+        return MAMBA_ERR_BAD_SHAPE;
+    if (lx.contiguous && ld.contiguous && (lz.contiguous || !z) && lo.contiguous && aligned16(x) && aligned16(dt) &&
+        aligned16(z) && aligned16(out))
+        return mamba_scan_fwd(x, dt, A, Bm, Cm, Dskip, z, dt_bias, h0, out, h_final, workspace, workspace_bytes,
+                              batch, L, D, N, 0, dt_softplus, io, hip_stream);
+    if (!injective(lo, batch, L, D)) return MAMBA_ERR_BAD_SHAPE;
+    if (!n_supported(N) || batch > kMaxGridYZ) return MAMBA_ERR_UNSUPPORTED;
+    if (!A || !x || !dt || !Bm || !Cm || !out) return MAMBA_ERR_NULL_POINTER;
+    if (!aligned_to(x, e) || !aligned_to(dt, e) || !aligned_to(z, e) || !aligned_to(out, e) || !aligned16(A) ||
+        !aligned16(Bm) || !aligned16(Cm) || !aligned16(Dskip) || !aligned16(dt_bias) || !aligned16(h0) ||
+        !aligned16(h_final))
+        return MAMBA_ERR_MISALIGNED;
+    if (overlap(out, lo.bytes, x, lx.bytes) || overlap(out, lo.bytes, dt, ld.bytes) ||
+        overlap(out, lo.bytes, z, lz.bytes) || overlap(out, lo.bytes, Bm, bc_bytes) ||
+        overlap(out, lo.bytes, Cm, bc_bytes) || overlap(out, lo.bytes, h0, st_bytes) ||
+        overlap(out, lo.bytes, h_final, st_bytes))
+        return MAMBA_ERR_ALIAS;
+    if (h_final != h0 && overlap(h_final, st_bytes, h0, st_bytes)) return MAMBA_ERR_ALIAS;
+    ScanStridedArgs a{x, dt, Bm, Cm, z, A, Dskip, dt_bias, h0, out, h_final, batch, L, D, (int)N, (int)io, dt_softplus,
+                      {lx.s[0], lx.s[1], lx.s[2]}, {ld.s[0], ld.s[1], ld.s[2]}, {lz.s[0], lz.s[1], lz.s[2]},
+                      {lo.s[0], lo.s[1], lo.s[2]}};
+    return (int)launch_scan_strided(a, static_cast<hipStream_t>(hip_stream));
+}
+
 int mamba_state_step(float *h_out, const float *h_in, const int32_t *parent_idx, const void *x,
                      const void *dt, const float *A, const void *Bm, const void *Cm,
                      const float *Dskip, const void *z, const float *dt_bias, void *out,

@@ -45,6 +45,28 @@ bool scan_direct_applies(int64_t batch, int64_t L, int64_t D, int64_t N);
 bool scan_lanes_applies(int64_t batch, int64_t L, int64_t D, int64_t N);
 hipError_t launch_scan_direct(const ScanArgs &a, hipStream_t stream);
 hipError_t launch_scan_lanes(const ScanArgs &a, hipStream_t stream);
+// Token tensors with element strides {batch, token, channel} (strided.hip): plain kernels, one lane per channel.
+struct ConvStridedArgs {
+    const void *x;
+    const float *w, *bias;
+    const void *state_in;
+    void *y;
+    void *state_out;
+    int64_t batch, L, D;
+    int K, apply_silu, io;
+    int64_t xs[3], ys[3];
+};
+struct ScanStridedArgs {
+    const void *x, *dt, *Bm, *Cm, *z;
+    const float *A, *Dskip, *dt_bias, *h0;
+    void *out;
+    float *h_final;
+    int64_t batch, L, D;
+    int N, io, dt_softplus;
+    int64_t xs[3], ds[3], zs[3], os[3];
+};
+hipError_t launch_conv1d_strided(const ConvStridedArgs &a, hipStream_t stream);
+hipError_t launch_scan_strided(const ScanStridedArgs &a, hipStream_t stream);
 // Chunking chosen for a shape when the caller passes chunk_len = 0 (pure function of the shape).
 void scan_plan(int64_t batch, int64_t L, int64_t D, int64_t N, int64_t chunk_len_req,
                int64_t *chunk_len, int64_t *n_chunks);

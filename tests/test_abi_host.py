@@ -124,6 +124,48 @@ def test_static_scan_validation(b):
     assert "#define MAMBA_SCAN_STATIC_BYTES (32u << 20)" in header and b.MAMBA_SCAN_STATIC_BYTES == 32 << 20
 
 
+def test_strided_entry_points_validation(b):
+    """Stride triples are host arrays of element counts {batch, token, channel}.  Everything is refused or found
+    empty before any HIP call: negative strides, output layouts in which two elements coincide, byte ranges of an
+    output and an input that overlap, base pointers not aligned to the element; NULL triples and triples that
+    describe the contiguous layout fall through to the contiguous entry points' own rules."""
+    S = b.STATUS
+    I3 = ctypes.c_int64 * 3
+    B, L, D, N = 2, 40, 24, 16
+
+    def conv(x=P(0), xs=None, w=P(1), bias=P(2), cin=P(3), y=P(4), ys=None, cout=P(5), batch=B, L=L, D=D, K=4, io=1):
+        return b.lib.mamba_conv1d_fwd_strided(x, xs, w, bias, cin, y, ys, cout, batch, L, D, K, 1, io, None)
+
+    def scan(x=P(0), xs=None, dt=P(1), ds=None, A=P(2), Bm=P(3), Cm=P(4), Dk=P(5), z=P(6), zs=None, bias=P(7), h0=P(8),
+             out=P(9), os_=None, hf=P(10), batch=B, L=L, D=D, N=N, io=1):
+        return b.lib.mamba_scan_fwd_strided(x, xs, dt, ds, A, Bm, Cm, Dk, z, zs, bias, h0, out, os_, hf, None, 0,
+                                            batch, L, D, N, 1, io, None)
+    cm = I3(D * L, 1, L)                 # channel-major (batch, D, L)
+    wide = I3(L * 2 * D, 2 * D, 1)       # a column range of rows twice as wide
+    # what the contiguous calls refuse is refused here too, whatever the strides
+    assert conv(io=7) == S["UNSUPPORTED"] and conv(K=9) == S["UNSUPPORTED"] and conv(L=-1) == S["BAD_SHAPE"]
+    assert scan(io=7) == S["UNSUPPORTED"] and scan(N=-1) == S["BAD_SHAPE"] and scan(xs=cm, N=17) == S["UNSUPPORTED"]
+    assert conv(batch=0, xs=cm) == 0 and scan(D=0, xs=cm) == 0
+    # contiguous triples and 16-byte aligned bases: the contiguous entry point and its rules
+    dense = I3(L * D, D, 1)
+    assert conv(xs=dense, ys=dense, w=P(1) + 4) == S["MISALIGNED"]
+    assert scan(xs=dense, ds=dense, zs=dense, os_=dense, out=P(0)) == S["ALIAS"]
+    long = I3(32768 * 1536, 1536, 1)     # a shape the library cuts into time chunks: needs the workspace
+    assert scan(xs=long, ds=long, zs=long, os_=long, L=32768, D=1536, batch=1) == S["WORKSPACE"]
+    # strided path
+    assert conv(xs=I3(D * L, -1, L)) == S["BAD_SHAPE"] and scan(ds=I3(-5, D, 1)) == S["BAD_SHAPE"]
+    assert conv(xs=I3(1 << 62, 1 << 61, 1)) == S["BAD_SHAPE"]                      # extent overflows
+    assert conv(ys=I3(D * L, 1, 1)) == S["BAD_SHAPE"] and scan(os_=I3(0, D, 1)) == S["BAD_SHAPE"]   # elements coincide
+    assert scan(os_=I3(L * D, D - 1, 1)) == S["BAD_SHAPE"]
+    assert conv(xs=cm, x=None) == S["NULL_POINTER"] and scan(os_=cm, A=None) == S["NULL_POINTER"]
+    assert conv(xs=cm, x=P(0) + 1) == S["MISALIGNED"] and conv(xs=cm, w=P(1) + 4) == S["MISALIGNED"]
+    assert scan(xs=cm, x=P(0) + 2, io=0) == S["MISALIGNED"] and scan(xs=cm, Bm=P(3) + 2) == S["MISALIGNED"]
+    # ranges: an output inside the byte range an input spans is refused, also when no element coincides
+    assert scan(xs=wide, os_=wide, out=P(0) + 2 * D) == S["ALIAS"]
+    assert conv(xs=cm, y=P(0) + 2 * (L + 1)) == S["ALIAS"] and conv(xs=cm, cout=P(3)) == S["ALIAS"]
+    assert conv(xs=cm, L=65535 * 128 + 1) == S["UNSUPPORTED"] and scan(xs=cm, batch=65536) == S["UNSUPPORTED"]
+
+
 def test_scan_kernel_choice_by_shape(b):
     """The library's own choice of scan kernels is a pure function of the shape; an explicit chunk length always
     means time chunks (or one chunk)."""

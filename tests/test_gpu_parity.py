@@ -225,6 +225,80 @@ def test_scan_time_across_lanes_delta_to_zero_keeps_state(m):
     assert np.array_equal(hf, h0)
 
 
+# ------------------------------------------------------------------------------------ other layouts
+def channel_major(t):
+    """A (B,L,D) device tensor re-stored as (B,D,L) and handed back as its (B,L,D) view."""
+    return t.transpose(1, 2).contiguous().transpose(1, 2)
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("B,L,D,N", [(2, 150, 100, 16), (1, 1, 7, 4), (3, 33, 64, 8), (1, 700, 130, 32)])
+def test_scan_strided_layouts(m, io, B, L, D, N):
+    """mamba_scan_fwd_strided: channel-major tensors, x and z as the two halves of one wide tensor, an output
+    written into a wider buffer; each against the oracle on the logical (B,L,D) arrays.  Strides that describe the
+    contiguous layout give the bits of mamba_scan_fwd."""
+    say(io=io, B=B, L=L, D=D, N=N)
+    c = synth.prefill_case(B, L, D, N, 4, io, seed=61000 + L + D, random_A=True)
+    h0 = np.random.default_rng(L + D).standard_normal((B, D, N)).astype(np.float32)
+    ro, rh = oracle_scan(c, h0=h0.astype(np.float64))
+    d = dev_case(c)
+    fixed = dict(A=d["A"], Bm=d["Bm"], Cm=d["Cm"], Dskip=d["Dskip"], dt_bias=d["dt_bias"], h0=to_dev(h0))
+    # channel-major inputs and output
+    out_cm = torch.empty((B, D, L), dtype=d["x"].dtype, device=DEV).transpose(1, 2)
+    o, hf = m.mamba_scan_fwd_strided(channel_major(d["x"]), channel_major(d["dt"]), z=channel_major(d["z"]), out=out_cm, **fixed)
+    assert o.stride() == (D * L, 1, L)
+    assert_close(values(to_host(o.contiguous())), ro, TOL[io], "channel-major out")
+    assert_close(to_host(hf), rh, TOL[io], "channel-major h_final")
+    # x | z side by side in one (B, L, 2D) tensor, dt contiguous, out into columns D/2.. of a wider buffer
+    xz = torch.cat([d["x"], d["z"]], dim=2)
+    wide = torch.full((B, L, 2 * D + 3), 7.0, dtype=d["x"].dtype, device=DEV)
+    o2, hf2 = m.mamba_scan_fwd_strided(xz[..., :D], d["dt"], z=xz[..., D:], out=wide[..., 3:3 + D], **fixed)
+    assert_close(values(to_host(o2.contiguous())), ro, TOL[io], "packed x|z out")
+    assert_close(to_host(hf2), rh, TOL[io], "packed x|z h_final")
+    assert torch.all(wide[..., :3] == 7.0) and torch.all(wide[..., 3 + D:] == 7.0)      # nothing outside the view
+    assert torch.equal(o2.contiguous(), o.contiguous()) and torch.equal(hf2, hf)         # one kernel, one order
+    # no gate, no state in or out
+    o3, none = m.mamba_scan_fwd_strided(channel_major(d["x"]), d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"],
+                                        dt_bias=d["dt_bias"], want_state=False)
+    ro3, _ = oracle_scan(c, z=None)
+    assert none is None
+    assert_close(values(to_host(o3)), ro3, TOL[io], "no gate out")
+    # contiguous strides: the tuned kernels, bit for bit
+    o4, hf4 = m.mamba_scan_fwd_strided(d["x"], d["dt"], z=d["z"], **fixed)
+    o5, hf5 = m.mamba_scan_fwd(d["x"], d["dt"], z=d["z"], **fixed)
+    assert torch.equal(o4, o5) and torch.equal(hf4, hf5)
+
+
+@pytest.mark.parametrize("io", [synth.F32, synth.BF16])
+@pytest.mark.parametrize("K", [2, 4])
+@pytest.mark.parametrize("B,L,D", [(2, 150, 100), (1, 2, 9), (3, 300, 64), (1, 1, 1)])
+def test_conv_strided_layouts(m, io, K, B, L, D):
+    """mamba_conv1d_fwd_strided on channel-major tensors and on a column range of a wider tensor, with a carried
+    window; outputs within tolerance of the oracle and bit-identical to the contiguous call (same order of
+    operations), carried states exact."""
+    say(io=io, K=K, B=B, L=L, D=D)
+    c = synth.prefill_case(B, L, D, 16, K, io, seed=62000 + L + D + K)
+    rng = np.random.default_rng(9)
+    c["conv_bias"] = rng.standard_normal(D).astype(np.float32)
+    st0 = synth.to_io(rng.standard_normal((B, D, K - 1)).astype(np.float32), io)
+    ry, rst = oracle.conv1d_fwd(W(c["x"]), W(c["conv_w"]), W(c["conv_bias"]), W(st0), True)
+    d = dev_case(c, ("x", "conv_w", "conv_bias"))
+    y_ref, st_ref = m.mamba_conv1d_fwd(d["x"], d["conv_w"], d["conv_bias"], to_dev(st0))
+    y_cm = torch.empty((B, D, L), dtype=d["x"].dtype, device=DEV).transpose(1, 2)
+    y, st = m.mamba_conv1d_fwd_strided(channel_major(d["x"]), d["conv_w"], d["conv_bias"], to_dev(st0), y=y_cm)
+    assert_close(values(to_host(y.contiguous())), ry, TOL[io], "channel-major conv y")
+    assert np.array_equal(values(to_host(st)), rst)
+    assert torch.equal(y.contiguous(), y_ref) and torch.equal(st, st_ref)
+    wide = torch.cat([d["x"], d["x"]], dim=2)
+    y2, st2 = m.mamba_conv1d_fwd_strided(wide[..., D:], d["conv_w"], d["conv_bias"], to_dev(st0))
+    assert torch.equal(y2, y_ref) and torch.equal(st2, st_ref)
+    # no carried window, no activation, no state wanted
+    y3, none = m.mamba_conv1d_fwd_strided(channel_major(d["x"]), d["conv_w"], None, apply_silu=False, want_state=False)
+    ry3, _ = oracle.conv1d_fwd(W(c["x"]), W(c["conv_w"]), None, None, False)
+    assert none is None
+    assert_close(values(to_host(y3)), ry3, TOL[io], "plain conv y")
+
+
 @pytest.mark.parametrize("io", [synth.F32, synth.BF16])
 def test_scan_optional_arguments(m, io):
     c = synth.prefill_case(2, 200, 128, 16, 4, io, seed=42)
