@@ -808,6 +808,63 @@ def test_decode_loop_replays_in_a_hip_graph(m, one_launch):
         assert torch.equal(outs, ref[0]) and torch.equal(fin_s, ref[1]) and torch.equal(fin_c, ref[2]), i
 
 
+@pytest.mark.parametrize("B,L,D,kind,static", [(1, 1100, 576, "lanes", False), (56, 130, 256, "direct", False),
+                                               (1, 3000, 256, "chunked", False), (1, 3000, 256, "chunked", True)])
+def test_prefill_replays_in_a_hip_graph(m, B, L, D, kind, static):
+    """Conv1d and scan of a prefix, every scan kernel family, captured once and replayed on new inputs written into
+    the captured buffers, with other work and synchronizations in between: each replay equals the eager call on
+    the same inputs bit for bit.  (The chunked family also through the entry point that brings its own chunk-state
+    buffer, the one meant for callers that capture.)"""
+    say(B=B, L=L, D=D, kind=kind, static=static)
+    N, K, io = 16, 4, synth.BF16
+    assert m.mamba_scan_kernel(B, L, D, N) == kind
+    cases = [synth.prefill_case(B, L, D, N, K, io, seed=70000 + i) for i in range(3)]
+    d = dev_case(cases[0])
+    h0 = torch.zeros((B, D, N), dtype=torch.float32, device=DEV)
+    xc, cst = torch.empty_like(d["x"]), torch.empty((B, D, K - 1), dtype=d["x"].dtype, device=DEV)
+    out, hf = torch.empty_like(d["x"]), torch.empty((B, D, N), dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(m.mamba_scan_workspace_bytes(B, L, D, N), 16), dtype=torch.uint8, device=DEV)
+
+    def prefill():
+        m.mamba_conv1d_fwd(d["x"], d["conv_w"], d["conv_bias"], y=xc, conv_state_out=cst)
+        if static:
+            m.mamba_scan_fwd_static(xc, d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"], d["dt_bias"], h0, out, hf)
+        else:
+            m.mamba_scan_fwd(xc, d["dt"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["z"], d["dt_bias"], h0=h0, out=out,
+                             h_final=hf, workspace=ws)
+
+    prefill()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            prefill()
+    torch.cuda.current_stream().wait_stream(side)
+    scratch = torch.empty(1 << 22, device=DEV)
+    for i in (1, 2, 0, 1):
+        for k in ("x", "dt", "z", "Bm", "Cm"):
+            d[k].copy_(to_dev(cases[i][k]))
+        h0.fill_(0.25 * i)
+        prefill()                                   # eager, same buffers
+        torch.cuda.synchronize()
+        ref = (xc.clone(), cst.clone(), out.clone(), hf.clone())
+        for t in (xc, cst, out, hf, ws):
+            t.zero_()
+        scratch.normal_()                           # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xc, ref[0]) and torch.equal(cst, ref[1]) and torch.equal(out, ref[2]) and torch.equal(hf, ref[3]), i
+    # and against the oracle once, on the last inputs
+    ro, rh = oracle.scan_fwd(values(to_host(xc)), W(cases[1]["dt"]), W(cases[0]["A"]), W(cases[1]["Bm"]), W(cases[1]["Cm"]),
+                             W(cases[0]["Dskip"]), W(cases[1]["z"]), W(cases[0]["dt_bias"]),   # parameters stay those of case 0
+                             np.full((B, D, N), 0.25, dtype=np.float64))
+    assert_close(values(to_host(out)), ro, TOL[io], "replayed scan out")
+    assert_close(to_host(hf), rh, TOL[io], "replayed scan state")
+
+
 def test_softplus_and_silu_accuracy_through_the_step(m):
     """N = 4, A = 0, zero state, B = (1,0,0,0), C = (1,0,0,0), x = 1, no skip: out = delta * silu(z)
     and h[.,0] = delta, so the kernel's softplus and SiLU can be read off directly."""
