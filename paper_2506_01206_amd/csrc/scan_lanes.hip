@@ -472,18 +472,19 @@ scan_lanes_kernel(const T *x, const T *dt, const float *__restrict__ A, const T 
 
 // Shapes the lane-scan kernel serves: 16 states, token rows that can be read in 4-byte pieces from any even
 // channel, at least one full workgroup; and among those the ones it is expected to finish before the two-pass
-// kernels of scan.hip.  Its time is rounds x (about 7 us + 12 ns per token), a round being 256 workgroups of 6
-// channels (every workgroup walks the whole sequence, and each 12-byte row piece costs a 64-byte L2 request, which
-// is what bounds it); the two-pass kernels take about 20 us + 8.8 ns per token and 1536 channels.  Measured on
-// 1536 channels: 2048 tokens 31 us against 43, 4096 tokens 57 against 62, 8192 tokens 105 against 99; 2048
-// channels (342 workgroups, two rounds) 58 against 47.
+// kernels of scan.hip.  Its time is rounds x (about 6 us + 11.6 ns per token), a round being 256 workgroups of 6
+// channels (every workgroup walks the whole sequence); the two-pass kernels take about 24 us + 9.8 ns per token
+// and 1536 channels.  Measured in one run, lanes against two-pass, 1536 channels: 2048 tokens 31 against 43 us,
+// 5120 tokens 71 against 78, 8192 tokens 101 against 104, 10240 tokens 121 against 122, 32768 tokens 461 against
+// 353; two sequences of 2048 tokens 56 against 60, of 4096 tokens 102 against 101; 768 channels x 4096 tokens 48
+// against 44; 2048 channels (342 workgroups, two rounds) x 4096 tokens 105 against 76.
 bool scan_lanes_applies(int64_t batch, int64_t L, int64_t D, int64_t N)
 {
     if (N != kN || D % 2 != 0 || D < kG || L < 64 || batch > 65535) return false;
     const double groups = (double)batch * (double)((D + kG - 1) / kG);
     const double rounds = (double)(int64_t)((groups + 255.0) / 256.0);
-    const double lanes_ns = rounds * (7000.0 + 11.9 * (double)L);
-    const double two_pass_ns = 20000.0 + 8.8 * (double)L * ((double)batch * (double)D / 1536.0);
+    const double lanes_ns = rounds * (6000.0 + 11.6 * (double)L);
+    const double two_pass_ns = 24000.0 + 9.8 * (double)L * ((double)batch * (double)D / 1536.0);
     return lanes_ns < two_pass_ns;
 }
 
