@@ -13,7 +13,7 @@
 //     its 8 tokens (softplus once per token and channel, not once per state lane) and leaves them in LDS,
 //     and after the recurrence picks up y for the same tokens, adds the skip term, gates and stores;
 //   * state layout (the recurrence): a lane owns N / 4 states of one channel, the four lanes of a channel
-//     sit in one quad and add their partial C . h with two DPP exchanges.  States and A * log2(e) stay in
+//     sit in one quad and add their partial C . h with DPP exchanges (four steps at a time).  States and A * log2(e) stay in
 //     registers for the whole sequence; delta, delta * x (8 bytes per channel and step) and B_t, C_t come
 //     from LDS.  Per state update: mul, exp2, mul, fma, fma.
 // With N / 4 states per lane a layer of 4096 channels x 8 rows gives 2048 wavefronts, two per SIMD.
@@ -80,16 +80,22 @@ __device__ __forceinline__ float4 load4(const bf16_t *p)
 }
 __device__ __forceinline__ float4 load4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 
-template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
+template <int CTRL> __device__ __forceinline__ float dpp_take(float v)
 {
-    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-    return v + __int_as_float(o);
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
-// sum over the four lanes of a quad; every lane gets the total
-__device__ __forceinline__ float quad_sum(float v)
+// Four values per lane, summed over the four lanes of a quad, lane q keeping the total of value q.  The lanes
+// swap what they do not keep twice (pairs, then pairs of pairs): 3 additions and 6 selects, against 8 additions
+// and 4 selects for four full sums of which each lane would keep one.
+__device__ __forceinline__ float quad_sum_scatter(const float (&p)[4], int q)
 {
-    v = dpp_add<0xB1>(v);      // quad_perm [1,0,3,2]
-    return dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    const bool odd = q & 1, high = q & 2;
+    const float keep0 = odd ? p[1] : p[0], send0 = odd ? p[0] : p[1];
+    const float keep1 = odd ? p[3] : p[2], send1 = odd ? p[2] : p[3];
+    const float r0 = keep0 + dpp_take<0xB1>(send0);      // quad_perm [1,0,3,2]: values 0 / 1 over the pair
+    const float r1 = keep1 + dpp_take<0xB1>(send1);      // values 2 / 3 over the pair
+    const float keep = high ? r1 : r0, send = high ? r0 : r1;
+    return keep + dpp_take<0x4E>(send);                  // quad_perm [2,3,0,1]
 }
 
 // grid: (ceil(D / 64), batch); block: 256.  D % 8 == 0, N % 4 == 0.
@@ -276,20 +282,18 @@ scan_direct_kernel(const T *x, const T *dt, const float *__restrict__ A, const T
         for (int s4 = 0; s4 < kTile; s4 += 4) {
             Group ahead;
             read_group(ahead, (s4 + 4) & (kTile - 1));       // the last group re-reads the first, unused
-            float ysel = 0.0f;
+            float yp[4];
 #pragma unroll
             for (int j4 = 0; j4 < 4; ++j4) {
-                float yp = 0.0f;
+                yp[j4] = 0.0f;
 #pragma unroll
                 for (int j = 0; j < SPL; ++j) {
                     const float a = exp2_hw(cur.du[j4].x * a2[j]);
                     h[j] = fmaf(a, h[j], cur.du[j4].y * cur.bv[j4][j]);
-                    yp = fmaf(h[j], cur.cv[j4][j], yp);
+                    yp[j4] = fmaf(h[j], cur.cv[j4][j], yp[j4]);
                 }
-                yp = quad_sum(yp);
-                ysel = (q == j4) ? yp : ysel;
             }
-            lds_y[s4 + q][cc] = ysel;
+            lds_y[s4 + q][cc] = quad_sum_scatter(yp, q);
             cur = ahead;
         }
         lds_barrier();   // y of the tile is complete; delta, delta * x, B and C of the tile are used up
