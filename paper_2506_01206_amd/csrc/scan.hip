@@ -68,6 +68,8 @@ template <int CPL> __device__ __forceinline__ void st_pack(bf16_t *p, const floa
 // every step then reads its N values with wave-uniform (broadcast) 16-byte LDS reads into
 // VGPRs.  Compared with scalar loads this keeps SGPR operands (which issue slower) and the
 // bf16 unpacking out of the inner loop.  NARR = 1 stages B only, 2 stages B and C.
+// sched_barrier mask: scalar, memory and LDS instructions may still be moved across; vector ALU ones stay put
+constexpr int kSchedMemoryOnly = 0x4 | 0x10 | 0x20 | 0x40 | 0x80 | 0x100 | 0x200;
 constexpr int kBcTile = 16;
 static_assert(kBcTile % kTile == 0, "B/C tiles must start on a token-tile boundary");
 
@@ -240,10 +242,20 @@ scan_chunk_out(const T *__restrict__ x, const T *__restrict__ dt, const float *_
             const float delta = SOFTPLUS ? softplus_f32(v) : v;
             const float u = delta * xv[c];
             float y = s.dskip[c] * xv[c];
+            // The exponentials of a channel's states are issued as one run, the plain instructions around them
+            // as runs of their own: exp2 next to exp2 issues at its own rate, exp2 scattered among multiplies
+            // costs every neighbour extra (a bare loop of this update: 22 cycles per update in runs of 16, 25 to
+            // 28 interleaved, which is what the compiler's scheduler produces when left alone).
+            float a[N];
+#pragma unroll
+            for (int n = 0; n < N; ++n) a[n] = delta * s.a2[c][n];
+            __builtin_amdgcn_sched_barrier(kSchedMemoryOnly);
+#pragma unroll
+            for (int n = 0; n < N; ++n) a[n] = exp2_hw(a[n]);
+            __builtin_amdgcn_sched_barrier(kSchedMemoryOnly);
 #pragma unroll
             for (int n = 0; n < N; ++n) {
-                const float a = exp2_hw(delta * s.a2[c][n]);
-                s.h[c][n] = fmaf(a, s.h[c][n], u * bf[n]);
+                s.h[c][n] = fmaf(a[n], s.h[c][n], u * bf[n]);
                 y = fmaf(s.h[c][n], cf[n], y);
             }
             ov[c] = HAS_Z ? y * silu_f32(zv[c]) : y;
@@ -351,11 +363,16 @@ scan_chunk_state(const T *__restrict__ x, const T *__restrict__ dt, const float 
             const float delta = SOFTPLUS ? softplus_f32(v) : v;
             const float u = delta * xv[c];
             sum[c] += delta;
+            // exponentials as one run per channel (see pass 2)
+            float a[N];
 #pragma unroll
-            for (int n = 0; n < N; ++n) {
-                const float a = exp2_hw(delta * s.a2[c][n]);
-                s.h[c][n] = fmaf(a, s.h[c][n], u * bf[n]);
-            }
+            for (int n = 0; n < N; ++n) a[n] = delta * s.a2[c][n];
+            __builtin_amdgcn_sched_barrier(kSchedMemoryOnly);
+#pragma unroll
+            for (int n = 0; n < N; ++n) a[n] = exp2_hw(a[n]);
+            __builtin_amdgcn_sched_barrier(kSchedMemoryOnly);
+#pragma unroll
+            for (int n = 0; n < N; ++n) s.h[c][n] = fmaf(a[n], s.h[c][n], u * bf[n]);
         }
     };
 

@@ -25,6 +25,8 @@
 namespace mamba {
 namespace {
 
+// sched_barrier mask: scalar, memory and LDS instructions may still be moved across; vector ALU ones stay put
+constexpr int kSchedMemoryOnly = 0x4 | 0x10 | 0x20 | 0x40 | 0x80 | 0x100 | 0x200;
 constexpr int kThreads = 256;
 constexpr int kChannels = 64;   // channels per workgroup
 constexpr int kTile = 64;       // steps per tile (a multiple of 32)
@@ -282,14 +284,25 @@ scan_direct_kernel(const T *x, const T *dt, const float *__restrict__ A, const T
         for (int s4 = 0; s4 < kTile; s4 += 4) {
             Group ahead;
             read_group(ahead, (s4 + 4) & (kTile - 1));       // the last group re-reads the first, unused
-            float yp[4];
+            // the exponentials of the four steps as one run (exp2 next to exp2 issues at its own rate, scattered
+            // among multiplies it slows its neighbours), then the updates
+            float a[4][SPL], yp[4];
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4)
+#pragma unroll
+                for (int j = 0; j < SPL; ++j) a[j4][j] = cur.du[j4].x * a2[j];
+            __builtin_amdgcn_sched_barrier(kSchedMemoryOnly);
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4)
+#pragma unroll
+                for (int j = 0; j < SPL; ++j) a[j4][j] = exp2_hw(a[j4][j]);
+            __builtin_amdgcn_sched_barrier(kSchedMemoryOnly);
 #pragma unroll
             for (int j4 = 0; j4 < 4; ++j4) {
                 yp[j4] = 0.0f;
 #pragma unroll
                 for (int j = 0; j < SPL; ++j) {
-                    const float a = exp2_hw(cur.du[j4].x * a2[j]);
-                    h[j] = fmaf(a, h[j], cur.du[j4].y * cur.bv[j4][j]);
+                    h[j] = fmaf(a[j4][j], h[j], cur.du[j4].y * cur.bv[j4][j]);
                     yp[j4] = fmaf(h[j], cur.cv[j4][j], yp[j4]);
                 }
             }
