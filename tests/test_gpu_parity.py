@@ -922,6 +922,18 @@ def test_largest_grids(m):
     c = synth.prefill_case(65535, 5, 2, 4, 3, synth.F32, seed=3)
     check_scan(m, c, what="65535-row scan")
     check_conv(m, c)
+    # the single-pass kernel on as many batch rows as the grid allows
+    c = synth.prefill_case(65535, 3, 8, 16, 4, synth.BF16, seed=6, random_A=True)
+    assert m.mamba_scan_kernel(65535, 3, 8, 16) == "direct"
+    check_scan(m, c, what="65535-row single-pass scan")
+    # the scan over the lanes of a wavefront at the longest sequence it is chosen for (20 super-steps, ragged)
+    assert m.mamba_scan_kernel(1, 9999, 1536, 16) == "lanes" and m.mamba_scan_kernel(1, 12000, 1536, 16) == "chunked"
+    c = synth.prefill_case(1, 9999, 1536, 16, 4, synth.BF16, seed=7)
+    ch = np.arange(0, 1536, 7)
+    out, hf = run_scan(m, c)
+    ro, rh = oracle_scan(c, channels=ch)
+    assert_close(values(out)[..., ch], ro, TOL[synth.BF16], "9999-token lanes scan out")
+    assert_close(hf[:, ch], rh, TOL[synth.BF16], "9999-token lanes scan state")
     # scan: as many time chunks as the grid allows (one token per chunk)
     c = synth.prefill_case(1, 65535, 2, 4, 2, synth.BF16, seed=4, random_A=True)
     check_scan(m, c, chunk_len=1, what="65535-chunk scan")
