@@ -299,6 +299,31 @@ def test_conv_strided_layouts(m, io, K, B, L, D):
     assert_close(values(to_host(y3)), ry3, TOL[io], "plain conv y")
 
 
+@pytest.mark.parametrize("B,L,D,kind", [(1, 1100, 576, "lanes"), (56, 130, 256, "direct"), (1, 3000, 256, "chunked")])
+def test_scan_nan_stays_in_its_channel(m, B, L, D, kind):
+    """A NaN in x at one (row, token, channel): that channel's outputs are NaN from that token on, and its final
+    state; every other element is bit for bit what it is without the NaN (channels are independent recurrences, in
+    every kernel family: across time chunks, across the lanes that scan time, across the lanes that share a channel)."""
+    say(B=B, L=L, D=D, kind=kind)
+    N, io = 16, synth.BF16
+    assert m.mamba_scan_kernel(B, L, D, N) == kind
+    c = synth.prefill_case(B, L, D, N, 4, io, seed=81000 + L)
+    clean_out, clean_h = run_scan(m, c)
+    b, t, d = B // 2, L // 3, D // 2 + 1
+    c2 = dict(c)
+    c2["x"] = c["x"].copy()
+    c2["x"][b, t, d] = 0x7FC0                       # bfloat16 quiet NaN
+    out, hf = run_scan(m, c2)
+    o, h = values(out), hf
+    assert np.isnan(o[b, t:, d]).all() and np.isnan(h[b, d]).all()
+    o_mask = np.ones(o.shape, bool)
+    o_mask[b, t:, d] = False
+    h_mask = np.ones(h.shape, bool)
+    h_mask[b, d] = False
+    assert np.array_equal(out[o_mask], clean_out[o_mask]) and np.array_equal(hf[h_mask], clean_h[h_mask])
+    assert not np.isnan(o[o_mask]).any()
+
+
 @pytest.mark.parametrize("io", [synth.F32, synth.BF16])
 def test_scan_optional_arguments(m, io):
     c = synth.prefill_case(2, 200, 128, 16, 4, io, seed=42)
