@@ -389,6 +389,32 @@ def test_scan_is_deterministic(m):
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
 
 
+@pytest.mark.parametrize("B,L,D,kind", [(1, 1500, 576, "lanes"), (56, 200, 256, "direct"), (1, 3000, 256, "chunked")])
+def test_scan_kernel_families_repeat_and_carry(m, B, L, D, kind):
+    """Each kernel family as the library chooses it: two runs give the same bits; a sequence scanned in two pieces
+    with the state carried over (the second piece in place on the state buffer) matches the oracle on the whole,
+    whichever kernels the pieces take."""
+    say(B=B, L=L, D=D, kind=kind)
+    N, io = 16, synth.BF16
+    assert m.mamba_scan_kernel(B, L, D, N) == kind
+    c = synth.prefill_case(B, L, D, N, 4, io, seed=83000 + L, random_A=True)
+    a, b = run_scan(m, c), run_scan(m, c)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    ro, rh = oracle_scan(c)
+    d = dev_case(c)
+    cut = 2 * L // 3 + 1
+    piece = lambda k, lo, hi: d[k][:, lo:hi].contiguous()
+    state = torch.zeros((B, D, N), dtype=torch.float32, device=DEV)
+    outs = []
+    for lo, hi in ((0, cut), (cut, L)):
+        say(piece=(lo, hi), kernel=m.mamba_scan_kernel(B, hi - lo, D, N))
+        o, _ = m.mamba_scan_fwd(piece("x", lo, hi), piece("dt", lo, hi), d["A"], piece("Bm", lo, hi), piece("Cm", lo, hi),
+                                d["Dskip"], piece("z", lo, hi), d["dt_bias"], h0=state, h_final=state)
+        outs.append(o)
+    assert_close(values(to_host(torch.cat(outs, 1))), ro, TOL[io], "two pieces out")
+    assert_close(to_host(state), rh, TOL[io], "two pieces state")
+
+
 # ------------------------------------------------------------------------------------ step
 def tok_slice(c, t):
     return {k: np.ascontiguousarray(c[k][:, t]) for k in ("x", "dt", "z", "Bm", "Cm")}
